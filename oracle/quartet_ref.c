@@ -1,0 +1,494 @@
+/*
+ * quartet_ref.c -- CPU oracle for the Quartet MXFP4 linear-layer path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP kernels are checked against.  It shares no code, header, table or helper
+ * with the GPU library, and nothing in the product path may call it.
+ *
+ * Every function follows the paper (arXiv 2505.14669) step by step:
+ *   - block Hadamard H_g, g = 32            : Section 3, "Outlier mitigation"
+ *   - MXFP4 = E2M1 codes + E8M0 scale / 32  : Section 3, "Blackwell Architecture Support"
+ *   - forward QuEST projection + clip mask  : Section 4.3 scheme 4; Algorithm 1 Forward
+ *   - backward randomized Hadamard, 3/4 range matching, RTN or stochastic rounding
+ *                                           : Section 3 "Rounding"; Algorithm 1 Backward
+ *   - GEMM_LP  D = (A x SFA)(B x SFB)^T     : Section 4.4 "Stage 2"
+ *   - gradient epilogue 16/9 H^-1(G . M)    : Algorithm 1 Backward
+ * Where the paper is silent the reading taken here is stated next to the code.
+ *
+ * Arithmetic: every fp32 step is a single IEEE-754 binary32 operation, rounded
+ * to nearest even, never contracted into an FMA (build with -ffp-contract=off,
+ * no fast-math).  GEMM sums are accumulated in fp64 in increasing k.
+ *
+ * Pins (tests/test_oracle_*.py): E2M1 grid and tie table, E8M0 powers of two,
+ * H H^T = 32 I and the dense-matrix product, Philox known answers, power-of-two
+ * scaling equivariance, "nothing saturates" in the backward, stochastic-rounding
+ * probabilities enumerated over all 2^16 draws, Gaussian MSE bands of Table 1,
+ * exhaustive one-group GEMMs and numpy fp64 matmul of decoded operands.
+ * Parity unpinned: the QuEST clip constant (the paper prints no value; see
+ * QUEST_LOG2_C2 below) -- only the Table 1 MSE band constrains it.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define G 32 /* Hadamard block = MX group size (Section 4.4, "Costs and format specialization") */
+
+/* number of random bits one element consumes in stochastic rounding */
+#define SR_BITS 16
+
+/* QuEST clip constant, as log2(c^2): group scale = 2^floor(log2(c * RMS)), c^2 = 1/2.
+ * The paper says "RMSE-based clipping" with a power-of-two scale and prints no constant;
+ * c^2 = 1/2 sits in the flat minimum of the Gaussian MSE for this family of rules. */
+#define QUEST_LOG2_C2 (-1)
+
+static const double E2M1_MAG[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+/* ------------------------------------------------------------------ helpers */
+
+static float bits_to_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t f32_to_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float bf16_to_f32(uint16_t b) { return bits_to_f32((uint32_t)b << 16); }
+
+static int64_t floor_div(int64_t a, int64_t b) { /* b > 0 */
+    int64_t q = a / b;
+    if ((a % b) != 0 && a < 0) q -= 1;
+    return q;
+}
+
+int quartet_ref_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void quartet_ref_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ------------------------------------------------------- E2M1 / E8M0 formats */
+
+/* value of a 4-bit E2M1 code: bit 3 sign, bits 2:0 index into {0,.5,1,1.5,2,3,4,6} */
+double quartet_ref_e2m1_decode(uint8_t code) {
+    double m = E2M1_MAG[code & 7];
+    return (code & 8) ? -m : m;
+}
+
+/* value of an E8M0 scale byte: 2^(b-127) */
+double quartet_ref_e8m0_decode(uint8_t b) { return ldexp(1.0, (int)b - 127); }
+
+/* round-to-nearest onto the E2M1 grid, saturating at 6; ties go to the even code
+ * (IEEE roundTiesToEven on the one mantissa bit).  The sign bit of the code is the
+ * sign bit of v, so -0 and negative values that round to zero give code 8. */
+uint8_t quartet_ref_e2m1_rtn(float v) {
+    double a = fabs((double)v);
+    int best = 0;
+    double bestd = fabs(a - E2M1_MAG[0]);
+    if (a >= E2M1_MAG[7]) return (uint8_t)(7 | ((f32_to_bits(v) >> 31) << 3)); /* saturate */
+    for (int c = 1; c < 8; ++c) {
+        double d = fabs(a - E2M1_MAG[c]);
+        if (d < bestd || (d == bestd && (c & 1) == 0)) { best = c; bestd = d; }
+    }
+    return (uint8_t)(best | ((f32_to_bits(v) >> 31) << 3));
+}
+
+/* stochastic rounding onto the E2M1 grid for |v| < 6 (Section 3, "Rounding":
+ * up or down with probability given by the distance to the two neighbours).
+ * lo <= |v| < hi are adjacent grid points, f = (|v|-lo)/(hi-lo) in [0,1);
+ * r is a uniform SR_BITS-bit integer, u = (r + 1/2) / 2^SR_BITS; the result is hi
+ * iff u < f.  Grid points never move (f = 0); P(up) differs from f by < 2^-SR_BITS. */
+uint8_t quartet_ref_e2m1_sr(float v, uint32_t r) {
+    double a = fabs((double)v);
+    int lo = 0;
+    for (int c = 1; c < 8; ++c)
+        if (E2M1_MAG[c] <= a) lo = c;
+    int code = lo;
+    if (lo < 7) {
+        double f = (a - E2M1_MAG[lo]) / (E2M1_MAG[lo + 1] - E2M1_MAG[lo]);
+        double u = ((double)(r & ((1u << SR_BITS) - 1)) + 0.5) / (double)(1u << SR_BITS);
+        if (u < f) code = lo + 1;
+    }
+    return (uint8_t)(code | ((f32_to_bits(v) >> 31) << 3));
+}
+
+/* ------------------------------------------------------------ Philox4x32-10 */
+
+/* Salmon et al., "Parallel random numbers: as easy as 1, 2, 3" (SC'11). */
+void quartet_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Random integer for the element at linear position L = row*K + kk of the quantized
+ * (output-logical) matrix.  One Philox call serves 128/SR_BITS consecutive elements:
+ * counter = (q_lo, q_hi, stream_id, 0) with q = L / (128/SR_BITS), key = (seed_lo, seed_hi);
+ * element j = L mod (128/SR_BITS) takes bits [SR_BITS*j, SR_BITS*(j+1)) of the 128-bit
+ * output w0|w1<<32|w2<<64|w3<<96. */
+uint32_t quartet_ref_sr_draw(uint64_t seed, uint32_t stream_id, uint64_t L) {
+    const unsigned per_call = 128 / SR_BITS;
+    const unsigned per_word = 32 / SR_BITS;
+    uint64_t q = L / per_call;
+    unsigned j = (unsigned)(L % per_call);
+    uint32_t ctr[4] = {(uint32_t)q, (uint32_t)(q >> 32), stream_id, 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    quartet_ref_philox4x32_10(ctr, key, w);
+    return (w[j / per_word] >> (SR_BITS * (j % per_word))) & ((1u << SR_BITS) - 1);
+}
+
+/* Sign word of the randomized Hadamard used by one backward pass with seed xi:
+ * first output word of Philox at counter (0,0,0,0xFFFFFFFF) under the same key. */
+uint32_t quartet_ref_sign_word(uint64_t seed) {
+    uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    quartet_ref_philox4x32_10(ctr, key, w);
+    return w[0];
+}
+
+/* ------------------------------------------------------- block Hadamard (g=32) */
+
+/* v <- H_32 (d . v): d_i = -1 iff bit i of sign_word (sign_word = 0 is the fixed H_g).
+ * H_32 is the normalized Sylvester matrix from H_d = (1/sqrt 2) H_2 (x) H_{d/2}:
+ * five butterfly stages with stride 1,2,4,8,16, then one multiply by fl(1/sqrt 32).
+ * The matrix is symmetric and orthogonal, so it is its own inverse. */
+void quartet_ref_hadamard32(float v[G], uint32_t sign_word) {
+    const float c = 0.17677669529663687f; /* fl(1/sqrt(32)) = 0x3E3504F3 */
+    for (int i = 0; i < G; ++i)
+        if ((sign_word >> i) & 1u) v[i] = -v[i];
+    for (int h = 1; h < G; h <<= 1) {
+        for (int i = 0; i < G; ++i) {
+            if (i & h) continue;
+            float a = v[i], b = v[i + h];
+            v[i] = a + b;
+            v[i + h] = a - b;
+        }
+    }
+    for (int i = 0; i < G; ++i) v[i] = v[i] * c;
+}
+
+/* ------------------------------------------------------------- input sources */
+
+/* A quantizer reads a logical matrix A[rows x k] (groups of 32 along k) from
+ *   SRC_BF16   : x bf16 stored [rows x ldx]
+ *   SRC_BF16_T : x bf16 stored [k x ldx], A = x^T
+ *   SRC_MX_T   : an MXFP4 tensor stored [k x rows] (codes [k x rows/2], scales [k x rows/32]),
+ *                A = decode(src)^T; decoding is exact in fp32. */
+enum { SRC_BF16 = 0, SRC_BF16_T = 1, SRC_MX_T = 2 };
+
+typedef struct {
+    int kind;
+    const uint16_t *x;
+    int64_t ldx;
+    const uint8_t *codes, *scales;
+    int64_t rows, k;
+} Src;
+
+static float src_get(const Src *s, int64_t r, int64_t kk) {
+    switch (s->kind) {
+    case SRC_BF16: return bf16_to_f32(s->x[r * s->ldx + kk]);
+    case SRC_BF16_T: return bf16_to_f32(s->x[kk * s->ldx + r]);
+    default: {
+        uint8_t byte = s->codes[kk * (s->rows / 2) + r / 2];
+        uint8_t code = (r & 1) ? (byte >> 4) : (byte & 15);
+        uint8_t sb = s->scales[kk * (s->rows / G) + r / G];
+        return (float)(quartet_ref_e2m1_decode(code) * quartet_ref_e8m0_decode(sb));
+    }
+    }
+}
+
+static void put_code(uint8_t *codes, int64_t idx, uint8_t code) {
+    /* element 2j in bits 3:0 of byte j, element 2j+1 in bits 7:4 */
+    if (idx & 1) codes[idx >> 1] = (uint8_t)((codes[idx >> 1] & 0x0F) | (code << 4));
+    else codes[idx >> 1] = (uint8_t)((codes[idx >> 1] & 0xF0) | code);
+}
+
+/* ------------------------------------------------------ forward quantizer */
+
+/* One group of the forward (QuEST) projection, Algorithm 1 Forward:
+ *   h = H_32 x; ss = sum h_i^2 (pairwise xor-tree, fp32);
+ *   scale exponent e = floor((floor(log2 ss) - 5 + log2 c^2) / 2), i.e. 2^e = 2^floor(log2(c sqrt(ss/32)));
+ *   v_i = h_i 2^-e (exact); code_i = RTN(v_i) saturating at 6; mask bit i = (|v_i| <= 6).
+ * ss zero or subnormal: e = 0. */
+static void quant_fwd_group(float h[G], uint8_t code[G], uint8_t *scale_byte, uint32_t *mask_word) {
+    float t[G], t2[G];
+    quartet_ref_hadamard32(h, 0u);
+    for (int i = 0; i < G; ++i) t[i] = h[i] * h[i];
+    for (int s = 1; s < G; s <<= 1) {
+        for (int i = 0; i < G; ++i) t2[i] = t[i] + t[i ^ s];
+        memcpy(t, t2, sizeof t);
+    }
+    float ss = t[0];
+    int E = (int)((f32_to_bits(ss) >> 23) & 0xFF);
+    int e = 0;
+    if (E != 0) e = (int)floor_div((int64_t)E - 127 - 5 + QUEST_LOG2_C2, 2);
+    int b = e + 127;
+    if (b < 0) b = 0;
+    if (b > 254) b = 254;
+    e = b - 127;
+    uint32_t m = 0;
+    for (int i = 0; i < G; ++i) {
+        float v = ldexpf(h[i], -e);
+        code[i] = quartet_ref_e2m1_rtn(v);
+        if (fabsf(v) <= 6.0f) m |= (1u << i);
+    }
+    *scale_byte = (uint8_t)b;
+    *mask_word = m;
+}
+
+static int check_quant_args(int64_t rows, int64_t k) {
+    if (rows < 0 || k < 0 || (k % G) != 0) return -1;
+    return 0;
+}
+
+/* codes [rows x k/2], scales [rows x k/32], mask [rows x k/32] (bit i of word j <-> element 32j+i;
+ * may be NULL).  transpose = 0: A = x[rows x ldx];  transpose = 1: A = x^T, x stored [k x ldx]. */
+int quartet_ref_quant_fwd(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                          uint8_t *codes, uint8_t *scales, uint32_t *mask) {
+    if (check_quant_args(rows, k)) return -1;
+    Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
+    int64_t gk = k / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < gk; ++g) {
+            float h[G];
+            uint8_t code[G], sb;
+            uint32_t mw;
+            for (int i = 0; i < G; ++i) h[i] = src_get(&s, r, g * G + i);
+            quant_fwd_group(h, code, &sb, &mw);
+            for (int i = 0; i < G; ++i) put_code(codes, r * k + g * G + i, code[i]);
+            scales[r * gk + g] = sb;
+            if (mask) mask[r * gk + g] = mw;
+        }
+    }
+    return 0;
+}
+
+/* ----------------------------------------------------- backward quantizer */
+
+/* One group of the backward quantizer, Algorithm 1 Backward:
+ *   h = H_32 (d . x) with the seed's sign vector;  m = max |h_i|;
+ *   AbsMax power-of-two scale with the OCP floor rule: e = floor(log2 m) - 2 (2 = emax of E2M1),
+ *   so |h_i| 2^-e < 8;  v_i = fl((h_i 2^-e) * 3/4), |v_i| < 6: nothing saturates;
+ *   code_i = RTN(v_i) (rounding = 1, Algorithm 1 as printed) or SR(v_i, draw) (rounding = 0).
+ * The stored scale is 2^e; the 3/4 is undone by the 16/9 of the gradient epilogue.
+ * m zero or subnormal: e = 0. */
+static void quant_bwd_group(float h[G], uint32_t sign_word, int rounding, uint64_t seed,
+                            uint32_t stream_id, uint64_t L0, uint8_t code[G], uint8_t *scale_byte) {
+    quartet_ref_hadamard32(h, sign_word);
+    float m = 0.0f;
+    for (int i = 0; i < G; ++i)
+        if (fabsf(h[i]) > m) m = fabsf(h[i]);
+    int E = (int)((f32_to_bits(m) >> 23) & 0xFF);
+    int b = 127;
+    if (E != 0) b = E - 2;
+    if (b < 0) b = 0;
+    if (b > 254) b = 254;
+    int e = b - 127;
+    for (int i = 0; i < G; ++i) {
+        float v = ldexpf(h[i], -e) * 0.75f;
+        if (rounding == 1) code[i] = quartet_ref_e2m1_rtn(v);
+        else code[i] = quartet_ref_e2m1_sr(v, quartet_ref_sr_draw(seed, stream_id, L0 + (uint64_t)i));
+    }
+    *scale_byte = (uint8_t)b;
+}
+
+static int quant_bwd_src(const Src *s, uint32_t sign_word, uint64_t seed, uint32_t stream_id,
+                         int rounding, uint8_t *codes, uint8_t *scales) {
+    int64_t rows = s->rows, k = s->k, gk = k / G;
+    if (rounding != 0 && rounding != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t g = 0; g < gk; ++g) {
+            float h[G];
+            uint8_t code[G], sb;
+            for (int i = 0; i < G; ++i) h[i] = src_get(s, r, g * G + i);
+            quant_bwd_group(h, sign_word, rounding, seed, stream_id, (uint64_t)(r * k + g * G), code, &sb);
+            for (int i = 0; i < G; ++i) put_code(codes, r * k + g * G + i, code[i]);
+            scales[r * gk + g] = sb;
+        }
+    }
+    return 0;
+}
+
+/* rounding: 0 = stochastic, 1 = nearest.  Layout of x and outputs as in quartet_ref_quant_fwd. */
+int quartet_ref_quant_bwd_sr(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                             uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
+                             uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k)) return -1;
+    Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, codes, scales);
+}
+
+/* Source is an MXFP4 tensor stored [k x rows] (its groups run along `rows`); the output is the
+ * backward quantization of decode(src)^T, a [rows x k] matrix with groups along k. */
+int quartet_ref_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_scales,
+                                     int64_t rows, int64_t k, uint32_t sign_word, uint64_t seed,
+                                     uint32_t stream_id, int rounding, uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k) || (rows % G) != 0) return -1;
+    Src s = {SRC_MX_T, 0, 0, src_codes, src_scales, rows, k};
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, codes, scales);
+}
+
+/* ----------------------------------------------------------------- decode */
+
+/* out[rows x k] (fp64) = E2M1 value x 2^(scale-127) */
+int quartet_ref_mxfp4_dequant(const uint8_t *codes, const uint8_t *scales, int64_t rows, int64_t k,
+                              double *out) {
+    if (check_quant_args(rows, k)) return -1;
+    int64_t gk = k / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t kk = 0; kk < k; ++kk) {
+            uint8_t byte = codes[(r * k + kk) >> 1];
+            uint8_t code = (kk & 1) ? (byte >> 4) : (byte & 15);
+            out[r * k + kk] = quartet_ref_e2m1_decode(code) * quartet_ref_e8m0_decode(scales[r * gk + kk / G]);
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------- GEMM */
+
+/* D[m x n] = alpha * sum_k dec(A)[m,k] dec(B)[n,k]: both operands K-contiguous MXFP4,
+ * one scale per 32 along K (Section 4.4, Stage 2); fp64 accumulation in increasing k.
+ * Only rows [row_begin, row_end) of D are computed (d still has leading dimension n and
+ * is indexed by absolute row), so large cases can be checked on a slab. */
+int quartet_ref_mxfp4_gemm_rows(const uint8_t *a_codes, const uint8_t *a_scales,
+                                const uint8_t *b_codes, const uint8_t *b_scales,
+                                int64_t m, int64_t n, int64_t k, double alpha,
+                                int64_t row_begin, int64_t row_end, double *d) {
+    if (m < 0 || n < 0 || check_quant_args(m, k)) return -1;
+    if (row_begin < 0 || row_end > m || row_begin > row_end) return -1;
+    if (n == 0 || row_begin == row_end) return 0;
+    int64_t mr = row_end - row_begin;
+    double *da = (double *)malloc(sizeof(double) * (size_t)(mr > 0 ? mr : 1) * (size_t)(k > 0 ? k : 1));
+    double *db = (double *)malloc(sizeof(double) * (size_t)n * (size_t)(k > 0 ? k : 1));
+    if (!da || !db) { free(da); free(db); return -2; }
+    int64_t gk = k / G;
+    quartet_ref_mxfp4_dequant(a_codes + row_begin * (k / 2), a_scales + row_begin * gk, mr, k, da);
+    quartet_ref_mxfp4_dequant(b_codes, b_scales, n, k, db);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < mr; ++i) {
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            const double *pa = da + i * k, *pb = db + j * k;
+            for (int64_t kk = 0; kk < k; ++kk) acc += pa[kk] * pb[kk];
+            d[(row_begin + i) * n + j] = alpha * acc;
+        }
+    }
+    free(da);
+    free(db);
+    return 0;
+}
+
+int quartet_ref_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
+                           const uint8_t *b_codes, const uint8_t *b_scales,
+                           int64_t m, int64_t n, int64_t k, double alpha, double *d) {
+    return quartet_ref_mxfp4_gemm_rows(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, 0, m, d);
+}
+
+/* ------------------------------------------------------- gradient epilogue */
+
+/* out[m x n] = scale * H_32( g . M ) along n (Algorithm 1 Backward: 16/9 H^-1(G . M); H_32 is
+ * its own inverse).  g . M keeps g where the mask bit is set and puts +0 elsewhere; fp32 steps
+ * in the Hadamard order above, the scale multiply last.  mask NULL = all ones. */
+int quartet_ref_grad_epilogue(const float *g, const uint32_t *mask, int64_t m, int64_t n,
+                              float scale, float *out) {
+    if (check_quant_args(m, n)) return -1;
+    int64_t gn = n / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < m; ++r)
+        for (int64_t j = 0; j < gn; ++j) {
+            float t[G];
+            uint32_t mw = mask ? mask[r * gn + j] : 0xFFFFFFFFu;
+            for (int i = 0; i < G; ++i) t[i] = ((mw >> i) & 1u) ? g[r * n + j * G + i] : 0.0f;
+            quartet_ref_hadamard32(t, 0u);
+            for (int i = 0; i < G; ++i) out[r * n + j * G + i] = t[i] * scale;
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------ linear layer fwd/bwd */
+
+static void round_to_f32(const double *src, float *dst, int64_t n) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) dst[i] = (float)src[i];
+}
+
+/* Algorithm 1 Forward: X[tokens x in], W[out x in] bf16 -> y[tokens x out] fp32 and
+ * ctx = {X_q, W_q, M_x, M_w}. */
+int quartet_ref_linear_fwd(const uint16_t *x, const uint16_t *w, int64_t tokens, int64_t in, int64_t out,
+                           float *y, uint8_t *xq_codes, uint8_t *xq_scales, uint32_t *x_mask,
+                           uint8_t *wq_codes, uint8_t *wq_scales, uint32_t *w_mask) {
+    if (tokens < 0 || in < 0 || out < 0 || (in % G) != 0) return -1;
+    if (quartet_ref_quant_fwd(x, tokens, in, in, 0, xq_codes, xq_scales, x_mask)) return -1;
+    if (quartet_ref_quant_fwd(w, out, in, in, 0, wq_codes, wq_scales, w_mask)) return -1;
+    double *d = (double *)malloc(sizeof(double) * (size_t)(tokens * out + 1));
+    if (!d) return -2;
+    int rc = quartet_ref_mxfp4_gemm(xq_codes, xq_scales, wq_codes, wq_scales, tokens, out, in, 1.0, d);
+    if (!rc) round_to_f32(d, y, tokens * out);
+    free(d);
+    return rc;
+}
+
+/* Algorithm 1 Backward with seed xi.  The sign vector comes from the seed; Philox stream ids
+ * 0,1,2,3 serve dy, W_q^T, dy^T, X_q^T.  dx[tokens x in], dw[out x in] fp32. */
+int quartet_ref_linear_bwd(const uint16_t *dy, int64_t tokens, int64_t in, int64_t out,
+                           const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,
+                           const uint8_t *wq_codes, const uint8_t *wq_scales, const uint32_t *w_mask,
+                           uint64_t seed, int rounding, float *dx, float *dw) {
+    if (tokens < 0 || in < 0 || out < 0) return -1;
+    if ((in % G) != 0 || (out % G) != 0 || (tokens % G) != 0) return -1;
+    const float c169 = 1.7777777777777777f; /* fl(16/9) = 0x3FE38E39 */
+    uint32_t sw = quartet_ref_sign_word(seed);
+    int rc = 0;
+    size_t sz_g = (size_t)(tokens * out), sz_w = (size_t)(in * out), sz_x = (size_t)(tokens * in);
+    uint8_t *gq = malloc(sz_g / 2 + 1), *gs = malloc(sz_g / G + 1);
+    uint8_t *wt = malloc(sz_w / 2 + 1), *ws = malloc(sz_w / G + 1);
+    uint8_t *gt = malloc(sz_g / 2 + 1), *gts = malloc(sz_g / G + 1);
+    uint8_t *xt = malloc(sz_x / 2 + 1), *xs = malloc(sz_x / G + 1);
+    size_t big = sz_x > sz_w ? sz_x : sz_w;
+    double *acc = malloc(sizeof(double) * (big + 1));
+    float *accf = malloc(sizeof(float) * (big + 1));
+    if (!gq || !gs || !wt || !ws || !gt || !gts || !xt || !xs || !acc || !accf) { rc = -2; goto done; }
+
+    /* dx = 16/9 H( (G_q W_q^T') . M_x ) : inner dimension = out */
+    rc |= quartet_ref_quant_bwd_sr(dy, tokens, out, out, 0, sw, seed, 0u, rounding, gq, gs);
+    rc |= quartet_ref_requant_transpose_sr(wq_codes, wq_scales, in, out, sw, seed, 1u, rounding, wt, ws);
+    rc |= quartet_ref_mxfp4_gemm(gq, gs, wt, ws, tokens, in, out, 1.0, acc);
+    if (rc) goto done;
+    round_to_f32(acc, accf, tokens * in);
+    rc |= quartet_ref_grad_epilogue(accf, x_mask, tokens, in, c169, dx);
+
+    /* dW = 16/9 H( (G^T_q X^T_q') . M_w ) : inner dimension = tokens */
+    rc |= quartet_ref_quant_bwd_sr(dy, out, tokens, out, 1, sw, seed, 2u, rounding, gt, gts);
+    rc |= quartet_ref_requant_transpose_sr(xq_codes, xq_scales, in, tokens, sw, seed, 3u, rounding, xt, xs);
+    rc |= quartet_ref_mxfp4_gemm(gt, gts, xt, xs, out, in, tokens, 1.0, acc);
+    if (rc) goto done;
+    round_to_f32(acc, accf, out * in);
+    rc |= quartet_ref_grad_epilogue(accf, w_mask, out, in, c169, dw);
+done:
+    free(gq); free(gs); free(wt); free(ws); free(gt); free(gts); free(xt); free(xs); free(acc); free(accf);
+    return rc;
+}

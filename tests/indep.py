@@ -1,0 +1,64 @@
+"""Independent numpy/scipy building blocks used only to pin the oracle.
+
+Nothing here is shared with oracle/ or with the HIP path: the Hadamard matrix comes from
+scipy, the E2M1 grid from the golden fixture, decoding is plain table look-up in fp64.
+"""
+import os
+
+import numpy as np
+from scipy.linalg import hadamard
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+H32 = hadamard(32).astype(np.float64)  # Sylvester order, entries +-1
+
+
+def load_grid():
+    vals = np.zeros(16)
+    with open(os.path.join(GOLDEN, "e2m1_grid.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            c, v = line.split()
+            vals[int(c)] = float(v)
+    return vals
+
+
+GRID = load_grid()
+
+
+def unpack_codes(codes):
+    """[rows, k/2] bytes -> [rows, k] 4-bit codes (element 2j = low nibble of byte j)."""
+    c = np.asarray(codes, dtype=np.uint8)
+    out = np.empty((c.shape[0], c.shape[1] * 2), dtype=np.uint8)
+    out[:, 0::2] = c & 15
+    out[:, 1::2] = c >> 4
+    return out
+
+
+def decode(codes, scales):
+    """fp64 values of an MXFP4 tensor."""
+    nib = unpack_codes(codes)
+    vals = GRID[nib]
+    vals = np.where(nib == 8, -0.0, vals)
+    s = np.ldexp(1.0, np.asarray(scales, dtype=np.int64) - 127)
+    return vals * np.repeat(s, 32, axis=1)
+
+
+def dense_hadamard_rows(x, sign_word=0):
+    """Normalized block Hadamard along the last axis in fp64: each block of 32 becomes
+    H32 @ (d * block) / sqrt(32)."""
+    x = np.asarray(x, dtype=np.float64)
+    d = np.array([-1.0 if (sign_word >> i) & 1 else 1.0 for i in range(32)])
+    blocks = x.reshape(x.shape[0], -1, 32) * d
+    return (blocks @ H32.T / np.sqrt(32.0)).reshape(x.shape)
+
+
+def read_table1():
+    out = {}
+    with open(os.path.join(GOLDEN, "table1_gaussian_mse.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, paper, lo, hi = line.split()
+            out[name] = (float(paper), float(lo), float(hi))
+    return out

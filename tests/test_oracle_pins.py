@@ -1,0 +1,496 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test checks oracle/ against something other than itself: golden values with a citation,
+closed forms, invariants, library routines (scipy's Hadamard matrix, numpy fp64 matmul) or
+brute force on small inputs.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_14669_amd import synth
+from indep import GOLDEN, GRID, H32, decode, dense_hadamard_rows, read_table1, unpack_codes
+
+
+def f32(x):
+    return np.float32(x)
+
+
+# ------------------------------------------------------------------ formats
+
+def test_e2m1_grid_matches_golden():
+    for code in range(16):
+        v = oracle.e2m1_decode(code)
+        assert v == GRID[code]
+        assert np.signbit(v) == (code >= 8)
+    mags = sorted(set(abs(GRID)))
+    assert mags == [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+
+
+def test_e2m1_bit_fields():
+    # 1 sign, 2 exponent (bias 1), 1 mantissa: value = (-1)^s 2^(e-1) (1 + m/2), subnormal e=0: m/2
+    for code in range(16):
+        s, e, m = code >> 3, (code >> 1) & 3, code & 1
+        mag = 0.5 * m if e == 0 else 2.0 ** (e - 1) * (1 + 0.5 * m)
+        assert oracle.e2m1_decode(code) == (-mag if s else mag)
+
+
+def test_e2m1_roundtrip_grid_values():
+    for code in range(16):
+        assert oracle.e2m1_rtn(GRID[code] if code != 8 else -0.0) == code
+        assert oracle.e2m1_sr(GRID[code] if code != 8 else -0.0, 12345) == code
+
+
+def test_e8m0_all_bytes():
+    for b in range(255):
+        assert oracle.e8m0_decode(b) == 2.0 ** (b - 127)
+
+
+def test_rtn_tie_table_and_saturation():
+    ties = {0.25: 0.0, 0.75: 1.0, 1.25: 1.0, 1.75: 2.0, 2.5: 2.0, 3.5: 4.0, 5.0: 4.0}
+    for v, want in ties.items():
+        assert GRID[oracle.e2m1_rtn(v)] == want
+        assert GRID[oracle.e2m1_rtn(-v)] == -want
+    for v in (6.0, 6.5, 7.0, 100.0, 3e38):
+        assert oracle.e2m1_rtn(v) == 7
+        assert oracle.e2m1_rtn(-v) == 15
+    # one ulp either side of a tie goes to the nearer neighbour
+    for t, (below, above) in {0.25: (0.0, 0.5), 2.5: (2.0, 3.0), 5.0: (4.0, 6.0)}.items():
+        assert GRID[oracle.e2m1_rtn(np.nextafter(f32(t), f32(0)))] == below
+        assert GRID[oracle.e2m1_rtn(np.nextafter(f32(t), f32(10)))] == above
+
+
+def test_rtn_brute_force_all_bf16():
+    # independent formulation: interval thresholds at the midpoints, ties by the explicit table
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = synth.bf16_to_f32(bits)
+    finite = np.isfinite(vals)
+    mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    tie_goes_up = np.array([False, True, False, True, False, True, False])  # to the even code
+    for b, v, ok in zip(bits, vals, finite):
+        if not ok:
+            continue
+        a = abs(float(v))
+        code = 0
+        for mid, up in zip(mids, tie_goes_up):
+            if a > mid or (a == mid and up):
+                code += 1
+        code |= (int(b) >> 15) << 3
+        assert oracle.e2m1_rtn(v) == code, (hex(int(b)), float(v))
+
+
+def test_rtn_is_nearest_random_fp32():
+    rng = np.random.default_rng(7)
+    vals = (rng.standard_normal(20000) * 3).astype(np.float32)
+    mags = np.array(sorted(set(abs(GRID))))
+    for v in vals:
+        got = abs(GRID[oracle.e2m1_rtn(v)])
+        assert abs(abs(float(v)) - got) == np.min(np.abs(abs(float(v)) - mags))
+
+
+# ------------------------------------------------------------------ Philox
+
+def test_philox_known_answers():
+    n = 0
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            w = [int(t, 16) for t in line.split()]
+            out = oracle.philox4x32_10(w[0:4], w[4:6])
+            assert [int(x) for x in out] == w[6:10]
+            n += 1
+    assert n == 3
+
+
+def test_sr_draws_tile_the_philox_output():
+    # the 8 draws of one call, concatenated, are exactly the 128 output bits; the next call's
+    # counter is q+1 in word 0/1, the stream id sits in word 2
+    seed, sid = 0x123456789ABCDEF0, 3
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    for q in (0, 1, 5, (1 << 32) + 7):
+        words = oracle.philox4x32_10([q & 0xFFFFFFFF, q >> 32, sid, 0], key)
+        big = sum(int(w) << (32 * i) for i, w in enumerate(words))
+        got = sum(oracle.sr_draw(seed, sid, 8 * q + j) << (16 * j) for j in range(8))
+        assert got == big
+    assert oracle.sign_word(seed) == int(oracle.philox4x32_10([0, 0, 0, 0xFFFFFFFF], key)[0])
+
+
+def test_sr_draws_look_uniform():
+    draws = np.array([oracle.sr_draw(42, 0, L) for L in range(40000)])
+    assert draws.min() >= 0 and draws.max() < 65536
+    assert abs(draws.mean() - 32767.5) < 5 * 65536 / np.sqrt(12 * draws.size)
+    hist = np.bincount(draws >> 12, minlength=16)
+    assert hist.min() > 0.9 * draws.size / 16
+
+
+# ------------------------------------------------------- stochastic rounding
+
+@pytest.mark.parametrize("v", [0.1, 0.26, 0.49, 0.5001, 0.9, 1.2, 1.74, 2.1, 2.9, 3.01, 4.5, 5.99, 1e-6])
+def test_sr_probability_enumerated(v):
+    v = f32(v)
+    mags = np.array(sorted(set(abs(GRID))))
+    lo = mags[mags <= float(v)].max()
+    hi = mags[mags > float(v)].min()
+    f = (float(v) - lo) / (hi - lo)
+    r = np.arange(65536)
+    out = np.array([GRID[oracle.e2m1_sr(v, int(x))] for x in r])
+    assert set(np.unique(out)) <= {lo, hi}
+    ups = int((out == hi).sum())
+    assert abs(ups - f * 65536) <= 1.0           # P(up) = f to within 2^-16
+    assert abs(out.mean() - float(v)) <= (hi - lo) * 2.0 ** -16
+    neg = np.array([GRID[oracle.e2m1_sr(-v, int(x))] for x in r[::97]])
+    assert np.array_equal(neg, -out[::97])       # sign symmetric
+
+
+def test_sr_monotone_in_draw():
+    # u < f: small draws round up, large draws round down
+    v = f32(2.4)
+    codes = [oracle.e2m1_sr(v, r) for r in (0, 1000, 26213, 26215, 65535)]
+    assert [GRID[c] for c in codes] == [3.0, 3.0, 3.0, 2.0, 2.0]
+
+
+# ----------------------------------------------------------------- Hadamard
+
+def test_hadamard_matrix_is_sylvester_and_orthogonal():
+    c = f32(1.0 / np.sqrt(32.0))
+    assert c.view(np.uint32) == 0x3E3504F3
+    cols = np.stack([oracle.hadamard32(np.eye(32, dtype=np.float32)[i]) for i in range(32)], axis=1)
+    M = cols / c
+    assert np.array_equal(M, H32)                       # +-1, Sylvester order (scipy)
+    assert np.array_equal(M @ M.T, 32 * np.eye(32))     # H H^T = 32 I
+    assert np.array_equal(M, M.T)
+    # Kronecker recursion H_32 = H_2 (x) H_16
+    H2 = np.array([[1.0, 1.0], [1.0, -1.0]])
+    K = H2
+    for _ in range(4):
+        K = np.kron(H2, K)
+    assert np.array_equal(M, K)
+
+
+def test_hadamard_matches_dense_fp64_and_is_involution():
+    rng = np.random.default_rng(3)
+    for sw in (0, 0xFFFFFFFF, 0x80000001, 0xDEADBEEF):
+        x = (rng.standard_normal(32) * 10).astype(np.float32)
+        h = oracle.hadamard32(x, sw)
+        ref = dense_hadamard_rows(x[None, :].astype(np.float64), sw)[0]
+        assert np.allclose(h, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+        assert abs(np.linalg.norm(h.astype(np.float64)) / np.linalg.norm(x.astype(np.float64)) - 1) < 1e-6
+    x = (rng.standard_normal(32)).astype(np.float32)
+    assert np.allclose(oracle.hadamard32(oracle.hadamard32(x)), x, atol=1e-6)
+    # exact small-integer case: sums of small integers are exact before the final multiply
+    xi = rng.integers(-8, 9, size=32).astype(np.float32)
+    want = (H32 @ xi.astype(np.float64)).astype(np.float32) * f32(1 / np.sqrt(32.0))
+    assert np.array_equal(oracle.hadamard32(xi), want)
+
+
+def test_randomized_hadamard_preserves_inner_products():
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal(32).astype(np.float32)
+    b = rng.standard_normal(32).astype(np.float32)
+    for sw in (0, 0x0F0F1234, oracle.sign_word(99)):
+        ha, hb = oracle.hadamard32(a, sw), oracle.hadamard32(b, sw)
+        assert abs(float(ha.astype(np.float64) @ hb) - float(a.astype(np.float64) @ b)) < 1e-5
+
+
+# -------------------------------------------------------- forward quantizer
+
+def _gauss_bf16(seed, rows, k, scale=1.0):
+    return synth.small_matrix(seed, rows, k, "normal", scale)
+
+
+def test_quant_fwd_against_fp64_recomputation():
+    x = _gauss_bf16(11, 64, 256)
+    codes, scales, mask = oracle.quant_fwd(x)
+    h = dense_hadamard_rows(synth.bf16_to_f32(x))
+    ss = (h.reshape(64, -1, 32) ** 2).sum(-1)
+    # group scale 2^floor(log2(sqrt(ss/64))): clip constant c^2 = 1/2
+    e = np.floor(np.log2(np.sqrt(ss / 64.0))).astype(np.int64)
+    frac = np.log2(np.sqrt(ss / 64.0)) - e
+    safe = (frac > 1e-5) & (frac < 1 - 1e-5)            # away from a power-of-two boundary
+    assert safe.mean() > 0.99
+    assert np.array_equal(scales[safe].astype(np.int64), (e + 127)[safe])
+    v = h / np.repeat(np.ldexp(1.0, scales.astype(np.int64) - 127), 32, axis=1)
+    nib = unpack_codes(codes)
+    mags = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    near = mags[np.argmin(np.abs(np.abs(v)[..., None] - mags), axis=-1)]
+    got = np.abs(GRID[nib])
+    dist_to_tie = np.min(np.abs(np.abs(v)[..., None] - np.array([.25, .75, 1.25, 1.75, 2.5, 3.5, 5.0])), -1)
+    clear = dist_to_tie > 1e-5
+    assert clear.mean() > 0.999
+    assert np.array_equal(got[clear], near[clear])
+    assert np.array_equal((nib >= 8)[np.abs(v) > 1e-9], (v < 0)[np.abs(v) > 1e-9])
+    bits = ((mask[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(64, 256).astype(bool)
+    edge = np.abs(np.abs(v) - 6.0) < 1e-5
+    assert np.array_equal(bits[~edge], (np.abs(v) <= 6.0)[~edge])
+    assert (~bits).sum() > 0                              # some elements do clip
+    assert np.all(got[~bits & ~edge] == 6.0)
+
+
+def test_quant_fwd_power_of_two_equivariance_and_zero_group():
+    x = _gauss_bf16(12, 8, 128)
+    c0, s0, m0 = oracle.quant_fwd(x)
+    for j in (-20, -3, 5, 30):
+        xj = synth.f32_to_bf16(synth.bf16_to_f32(x) * f32(2.0 ** j))
+        c, s, m = oracle.quant_fwd(xj)
+        assert np.array_equal(c, c0) and np.array_equal(m, m0)
+        assert np.array_equal(s.astype(int), s0.astype(int) + j)
+    z = np.zeros((2, 64), dtype=np.uint16)
+    z[1, :] = 0x8000                                    # all -0
+    c, s, m = oracle.quant_fwd(z)
+    assert np.all(s == 127) and np.all(m == 0xFFFFFFFF)
+    assert np.all(c[0] == 0x00)
+    # H(-0 vector): first output is a sum of -0 (= -0), the others are (-0) - (-0) = +0
+    assert np.all(np.abs(decode(c, s)) == 0)
+
+
+def test_quant_fwd_mse_in_table1_band():
+    paper, lo, hi = read_table1()["quest"]
+    x = _gauss_bf16(13, 512, 1024)
+    codes, scales, _ = oracle.quant_fwd(x)
+    h = dense_hadamard_rows(synth.bf16_to_f32(x))
+    mse = ((decode(codes, scales) - h) ** 2).sum() / (h ** 2).sum()
+    assert lo <= mse <= hi, mse
+
+
+def test_quant_fwd_transposed_equals_row_mode_on_transpose():
+    x = _gauss_bf16(14, 96, 160)            # stored [k=96, rows=160]
+    a = oracle.quant_fwd(x, transpose=True)
+    b = oracle.quant_fwd(np.ascontiguousarray(x.T))
+    for p, q in zip(a, b):
+        assert np.array_equal(p, q)
+    assert a[0].shape == (160, 48)
+
+
+# ------------------------------------------------------- backward quantizer
+
+def test_quant_bwd_scale_rule_and_no_saturation():
+    x = synth.small_matrix(21, 64, 256, "heavy")
+    for sw in (0, 0xA5A5F00F):
+        codes, scales = oracle.quant_bwd_sr(x, sw, seed=1, stream_id=0, rounding=1)
+        h = dense_hadamard_rows(synth.bf16_to_f32(x), sw)
+        m = np.abs(h).reshape(64, -1, 32).max(-1)
+        e = np.floor(np.log2(m)).astype(np.int64) - 2
+        frac = np.log2(m) - np.floor(np.log2(m))
+        safe = (frac > 1e-5) & (frac < 1 - 1e-5)
+        assert np.array_equal(scales[safe].astype(np.int64), (e + 127)[safe])
+        v = 0.75 * h / np.repeat(np.ldexp(1.0, scales.astype(np.int64) - 127), 32, axis=1)
+        assert np.abs(v).max() < 6.0
+        # the group maximum lands in [3, 6): the top of the grid is used, nothing clips
+        vmax = np.abs(v).reshape(64, -1, 32).max(-1)
+        assert np.all(vmax[safe] >= 3.0 - 1e-6)
+        nib = unpack_codes(codes)
+        mags = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+        near = mags[np.argmin(np.abs(np.abs(v)[..., None] - mags), axis=-1)]
+        tie = np.min(np.abs(np.abs(v)[..., None] - np.array([.25, .75, 1.25, 1.75, 2.5, 3.5, 5.0])), -1)
+        clear = tie > 1e-5
+        assert np.array_equal(np.abs(GRID[nib])[clear], near[clear])
+
+
+def test_quant_bwd_sr_neighbours_and_unbiased_over_seeds():
+    x = _gauss_bf16(22, 4, 64)
+    sw = 0x13579BDF
+    h = dense_hadamard_rows(synth.bf16_to_f32(x), sw)
+    n_seeds = 400
+    acc = np.zeros_like(h)
+    mags = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    for seed in range(n_seeds):
+        codes, scales = oracle.quant_bwd_sr(x, sw, seed=seed, stream_id=0, rounding=0)
+        d = decode(codes, scales)
+        acc += d
+        if seed < 3:
+            s = np.repeat(np.ldexp(1.0, scales.astype(np.int64) - 127), 32, axis=1)
+            v = 0.75 * h / s
+            lo = mags[(np.abs(v)[..., None] >= mags - 1e-7).sum(-1) - 1]
+            hi = mags[np.minimum((np.abs(v)[..., None] >= mags - 1e-7).sum(-1), 7)]
+            got = np.abs(d / s)
+            assert np.all((np.abs(got - lo) < 1e-12) | (np.abs(got - hi) < 1e-12))
+    mean = acc / n_seeds
+    s = np.repeat(np.ldexp(1.0, scales.astype(np.int64) - 127), 32, axis=1)
+    # per-element SR noise is at most (spacing/2) = 1 grid unit; 5 sigma over n_seeds
+    assert np.all(np.abs(mean - 0.75 * h) <= 5 * s * 1.0 / np.sqrt(n_seeds))
+    # and the aggregate bias is far smaller
+    assert abs((mean - 0.75 * h).sum()) / np.abs(0.75 * h).sum() < 5e-3
+
+
+def test_quant_bwd_streams_and_seeds_differ_and_rtn_ignores_them():
+    x = _gauss_bf16(23, 8, 128)
+    a = oracle.quant_bwd_sr(x, 0, seed=1, stream_id=0)
+    b = oracle.quant_bwd_sr(x, 0, seed=1, stream_id=1)
+    c = oracle.quant_bwd_sr(x, 0, seed=2, stream_id=0)
+    assert not np.array_equal(a[0], b[0]) and not np.array_equal(a[0], c[0])
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[1], c[1])   # scales do not depend on the draws
+    r1 = oracle.quant_bwd_sr(x, 0, seed=1, stream_id=0, rounding=1)
+    r2 = oracle.quant_bwd_sr(x, 0, seed=9, stream_id=5, rounding=1)
+    assert np.array_equal(r1[0], r2[0])
+
+
+def test_quant_bwd_mse_in_table1_bands():
+    t = read_table1()
+    x = _gauss_bf16(24, 512, 1024)
+    h = dense_hadamard_rows(synth.bf16_to_f32(x), 0)
+    for name, rounding in (("rtn_absmax", 1), ("sr_absmax", 0)):
+        codes, scales = oracle.quant_bwd_sr(x, 0, seed=5, stream_id=0, rounding=rounding)
+        d = decode(codes, scales) * (4.0 / 3.0)
+        mse = ((d - h) ** 2).sum() / (h ** 2).sum()
+        assert t[name][1] <= mse <= t[name][2], (name, mse)
+
+
+def test_quant_bwd_equivariance_and_transpose():
+    x = _gauss_bf16(25, 64, 96)
+    sw = 0xCAFEBABE
+    c0, s0 = oracle.quant_bwd_sr(x, sw, seed=7, stream_id=2)
+    xj = synth.f32_to_bf16(synth.bf16_to_f32(x) * f32(2.0 ** -9))
+    c1, s1 = oracle.quant_bwd_sr(xj, sw, seed=7, stream_id=2)
+    assert np.array_equal(c0, c1) and np.array_equal(s1.astype(int), s0.astype(int) - 9)
+    # transposed mode reads x stored [k, rows]; counters follow the output position, so the
+    # bytes equal row mode on the materialized transpose
+    ct, st = oracle.quant_bwd_sr(x, sw, seed=7, stream_id=2, transpose=True)
+    cr, sr = oracle.quant_bwd_sr(np.ascontiguousarray(x.T), sw, seed=7, stream_id=2)
+    assert np.array_equal(ct, cr) and np.array_equal(st, sr)
+    z = np.zeros((1, 32), dtype=np.uint16)
+    cz, sz = oracle.quant_bwd_sr(z, sw, seed=7, stream_id=2)
+    assert np.all(sz == 127) and np.all(np.abs(decode(cz, sz)) == 0)
+
+
+def test_requant_transpose_equals_quantizing_the_decoded_transpose():
+    x = _gauss_bf16(26, 64, 96)                       # [k=64 rows of the source, 96 columns]
+    src_c, src_s, _ = oracle.quant_fwd(x)             # MXFP4 [64, 96], groups along 96
+    dec_t = decode(src_c, src_s).T                    # [96, 64]; every value is exact in bf16
+    as_bf16 = synth.f32_to_bf16(dec_t.astype(np.float32))
+    assert np.array_equal(synth.bf16_to_f32(as_bf16).astype(np.float64), dec_t)
+    for rounding in (0, 1):
+        a = oracle.requant_transpose_sr(src_c, src_s, 0x600DF00D, seed=3, stream_id=1, rounding=rounding)
+        b = oracle.quant_bwd_sr(as_bf16, 0x600DF00D, seed=3, stream_id=1, rounding=rounding)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        assert a[0].shape == (96, 32) and a[1].shape == (96, 2)
+
+
+# --------------------------------------------------------------------- GEMM
+
+def test_dequant_matches_table_lookup():
+    rng = np.random.default_rng(31)
+    codes = rng.integers(0, 256, size=(5, 48), dtype=np.uint8)
+    scales = rng.integers(100, 150, size=(5, 3), dtype=np.uint8)
+    assert np.array_equal(oracle.mxfp4_dequant(codes, scales), decode(codes, scales))
+
+
+def test_gemm_exhaustive_single_group():
+    # M = N = 16, K = 32: row i of A holds code i in every slot, row j of B code j, so D[i,j] is
+    # 32 * value(i) * value(j) * 2^(sa+sb): all 256 code pairs, several scale pairs
+    a = np.array([[i | (i << 4)] * 16 for i in range(16)], dtype=np.uint8)
+    for sa, sb in ((127, 127), (120, 131), (0, 254), (140, 100)):
+        d = oracle.mxfp4_gemm(a, np.full((16, 1), sa, np.uint8), a, np.full((16, 1), sb, np.uint8))
+        want = 32.0 * np.outer(GRID, GRID) * 2.0 ** (sa + sb - 254)
+        assert np.array_equal(d, want)
+    # mixed codes inside the group: position-wise products, not products of sums
+    rng = np.random.default_rng(32)
+    ac = rng.integers(0, 256, size=(3, 16), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(4, 16), dtype=np.uint8)
+    one = np.full((3, 1), 127, np.uint8)
+    d = oracle.mxfp4_gemm(ac, one, bc, np.full((4, 1), 127, np.uint8))
+    va, vb = GRID[unpack_codes(ac)], GRID[unpack_codes(bc)]
+    assert np.array_equal(d, np.einsum("ik,jk->ij", va, vb))
+
+
+def test_gemm_matches_numpy_fp64_matmul():
+    rng = np.random.default_rng(33)
+    m, n, k = 37, 29, 160
+    ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    asc = rng.integers(110, 140, size=(m, k // 32), dtype=np.uint8)
+    bsc = rng.integers(110, 140, size=(n, k // 32), dtype=np.uint8)
+    d = oracle.mxfp4_gemm(ac, asc, bc, bsc, alpha=0.5)
+    want = 0.5 * decode(ac, asc) @ decode(bc, bsc).T
+    assert np.allclose(d, want, rtol=1e-13, atol=0)
+    slab = oracle.mxfp4_gemm(ac, asc, bc, bsc, alpha=0.5, rows=(5, 9))
+    assert np.array_equal(slab[5:9], d[5:9]) and np.all(slab[:5] == 0) and np.all(slab[9:] == 0)
+    # transposing operands transposes the result (A and B are not interchangeable by accident)
+    dt = oracle.mxfp4_gemm(bc, bsc, ac, asc, alpha=0.5)
+    assert np.array_equal(dt, d.T)
+
+
+# ----------------------------------------------------------------- epilogue
+
+def test_grad_epilogue_against_dense_hadamard():
+    rng = np.random.default_rng(41)
+    g = rng.standard_normal((6, 96)).astype(np.float32)
+    mask = rng.integers(0, 2 ** 32, size=(6, 3), dtype=np.uint32)
+    out = oracle.grad_epilogue(g, mask)
+    bits = ((mask[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(6, 96)
+    want = (16.0 / 9.0) * dense_hadamard_rows(g.astype(np.float64) * bits)
+    assert np.allclose(out, want, atol=3e-6 * np.abs(want).max())
+    ones = oracle.grad_epilogue(g, None, scale=1.0)
+    back = oracle.grad_epilogue(ones, None, scale=1.0)
+    assert np.allclose(back, g, atol=1e-6)              # H is its own inverse
+    zero = oracle.grad_epilogue(g, np.zeros((6, 3), np.uint32))
+    assert np.all(zero == 0)
+
+
+# ------------------------------------------------------------------- linear
+
+def test_linear_fwd_is_the_composition_and_close_to_the_exact_product():
+    L = synth.make_layer(1, 0)
+    x, w = L["x"][:64], L["w"][:96]
+    y, ctx = oracle.linear_fwd(x, w)
+    xc, xs, xm = oracle.quant_fwd(x)
+    wc, ws, wm = oracle.quant_fwd(w)
+    assert np.array_equal(ctx["xq_codes"], xc) and np.array_equal(ctx["w_mask"], wm)
+    want = decode(xc, xs) @ decode(wc, ws).T
+    assert np.array_equal(y, want.astype(np.float32))
+    # the Hadamard rotation cancels in the product: y approximates X W^T
+    exact = synth.bf16_to_f32(x).astype(np.float64) @ synth.bf16_to_f32(w).astype(np.float64).T
+    rel = np.linalg.norm(y - exact) / np.linalg.norm(exact)
+    assert 0.05 < rel < 0.25, rel
+
+
+def test_linear_bwd_composition_small():
+    x = _gauss_bf16(51, 32, 64)
+    w = _gauss_bf16(52, 96, 64, 0.02)
+    dy = _gauss_bf16(53, 32, 96, 1e-3)
+    _, ctx = oracle.linear_fwd(x, w)
+    seed = 77
+    sw = oracle.sign_word(seed)
+    for rounding in (0, 1):
+        dx, dw = oracle.linear_bwd(dy, ctx, seed, rounding)
+        gq = oracle.quant_bwd_sr(dy, sw, seed, 0, rounding)
+        wt = oracle.requant_transpose_sr(ctx["wq_codes"], ctx["wq_scales"], sw, seed, 1, rounding)
+        dxq = (decode(*gq) @ decode(*wt).T).astype(np.float32)
+        bits = ((ctx["x_mask"][:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(32, 64)
+        want = (16.0 / 9.0) * dense_hadamard_rows(dxq.astype(np.float64) * bits)
+        assert np.allclose(dx, want, atol=3e-6 * np.abs(want).max())
+        gt = oracle.quant_bwd_sr(dy, sw, seed, 2, rounding, transpose=True)
+        xt = oracle.requant_transpose_sr(ctx["xq_codes"], ctx["xq_scales"], sw, seed, 3, rounding)
+        dwq = (decode(*gt) @ decode(*xt).T).astype(np.float32)
+        bits = ((ctx["w_mask"][:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(96, 64)
+        want = (16.0 / 9.0) * dense_hadamard_rows(dwq.astype(np.float64) * bits)
+        assert np.allclose(dw, want, atol=3e-6 * np.abs(want).max())
+
+
+def test_linear_bwd_sr_mean_converges_to_the_unquantized_gradient():
+    # with all-ones masks, E over seeds of dx equals dy dec(W_q) rotated back, i.e. the gradient of
+    # the forward's own quantized product: the randomized rotation cancels and SR is unbiased
+    x = _gauss_bf16(61, 32, 64)
+    w = _gauss_bf16(62, 64, 64, 0.02)
+    dy = _gauss_bf16(63, 32, 64, 1e-3)
+    _, ctx = oracle.linear_fwd(x, w)
+    ctx = dict(ctx)
+    ctx["x_mask"] = np.full_like(ctx["x_mask"], 0xFFFFFFFF)
+    ctx["w_mask"] = np.full_like(ctx["w_mask"], 0xFFFFFFFF)
+    g = synth.bf16_to_f32(dy).astype(np.float64)
+    want_dx = dense_hadamard_rows(g @ decode(ctx["wq_codes"], ctx["wq_scales"]))
+    want_dw = dense_hadamard_rows(g.T @ decode(ctx["xq_codes"], ctx["xq_scales"]))
+    errs = {}
+    for n_seeds in (8, 128):
+        sx = np.zeros_like(want_dx)
+        sw_ = np.zeros_like(want_dw)
+        for seed in range(n_seeds):
+            dx, dw = oracle.linear_bwd(dy, ctx, seed, 0)
+            sx += dx
+            sw_ += dw
+        errs[n_seeds] = (np.linalg.norm(sx / n_seeds - want_dx) / np.linalg.norm(want_dx),
+                         np.linalg.norm(sw_ / n_seeds - want_dw) / np.linalg.norm(want_dw))
+    assert errs[128][0] < 0.05 and errs[128][1] < 0.05, errs
+    assert errs[128][0] < 0.45 * errs[8][0] and errs[128][1] < 0.45 * errs[8][1], errs   # ~ 1/sqrt(N)
