@@ -1,0 +1,164 @@
+/*
+ * quartet.h -- C ABI of the MI355X (gfx950) Quartet MXFP4 linear-layer library.
+ *
+ * The library implements the linear-layer hot path of "Quartet: Native FP4 Training Can Be
+ * Optimal for Large Language Models" (arXiv 2505.14669), Algorithm 1:
+ *   Forward : X_q,M_x = QuEST(H_g X);  W_q,M_w = QuEST(H_g W);  y = GEMM_LP(X_q, W_q)
+ *   Backward: G_q = Q(3/4 H^_g(dy, xi)), W'_q = Q(3/4 H^_g(W_q^T, xi)), dx = 16/9 H_g^-1((G_q W'_q^T) . M_x)
+ *             and the same with dy^T, X_q^T for dW.
+ * with g = 32 = the MXFP4 group size (Section 4.4).
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers owned by the caller (hipMalloc'ed or a torch CUDA/HIP
+ *    tensor's data_ptr).  The library never frees or keeps them.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on it
+ *    and the call returns without synchronizing; results are valid after the stream reaches that point.
+ *  - Matrices are row-major.  bf16 = upper 16 bits of an IEEE binary32.
+ *  - MXFP4 tensor [rows x k] (k % 32 == 0):
+ *      codes  uint8 [rows x k/2] : E2M1 element 2j in bits 3:0 of byte j, element 2j+1 in bits 7:4;
+ *                                  code = s e1 e0 m, magnitudes {0,.5,1,1.5,2,3,4,6}, bit 3 = sign;
+ *      scales uint8 [rows x k/32]: E8M0, value 2^(b-127), one per 32 consecutive elements of a row;
+ *      mask   uint32 [rows x k/32]: bit i of word j is 1 iff element 32j+i was NOT clipped.
+ *  - Return value: QUARTET_OK, or a negative error.  Arguments are validated on the host before
+ *    anything is launched; on QUARTET_EINVAL / QUARTET_ENOTSUP nothing has been enqueued.
+ *    QUARTET_EHIP: a HIP call failed; quartet_last_hip_error() returns its hipError_t.
+ *  - Pointers must be 16-byte aligned; leading dimensions are in elements and multiples of 8.
+ *  - Inputs are finite with magnitude below 2^60; group sums of squares / maxima that are zero or
+ *    subnormal are treated as zero (scale byte 127).
+ *  - Thread safety: calls are independent except for the last-error slot, which is per thread.
+ */
+#ifndef QUARTET_H
+#define QUARTET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QUARTET_OK 0
+#define QUARTET_EINVAL (-1)  /* null pointer, bad shape, misaligned pointer or leading dimension */
+#define QUARTET_ENOTSUP (-2) /* valid request this build does not support (size limit, dtype) */
+#define QUARTET_EHIP (-3)    /* a HIP runtime call failed */
+
+#define QUARTET_DTYPE_F32 0
+#define QUARTET_DTYPE_BF16 1
+
+#define QUARTET_ROUND_STOCHASTIC 0
+#define QUARTET_ROUND_NEAREST 1
+
+/* hipError_t of the last failed HIP call made by this thread through the library (0 if none). */
+int quartet_last_hip_error(void);
+
+/* Number of random bits each element consumes in stochastic rounding (16). */
+int quartet_sr_bits(void);
+
+/*
+ * Forward quantizer (Algorithm 1 Forward, lines H_g then QuEST; Section 4.4 "Stage 1").
+ * Logical input A[rows x k]:  transpose = 0: A = x, stored [rows x ldx];
+ *                             transpose = 1: A = x^T, x stored [k x ldx] (ldx >= rows).
+ * Per group of 32 along k: h = H_32 a (normalized Sylvester-Hadamard, butterflies of stride
+ * 1,2,4,8,16 in fp32, then one multiply by fl(1/sqrt 32)); ss = sum h_i^2 (pairwise tree);
+ * scale 2^e with e = floor((floor(log2 ss) - 6) / 2)  (= 2^floor(log2(RMS/sqrt 2)), the RMS-based
+ * clipping of QuEST snapped to a power of two); code_i = round-to-nearest-even E2M1 of h_i 2^-e,
+ * saturating at +-6; mask bit i = (|h_i 2^-e| <= 6).
+ * Outputs: codes [rows x k/2], scales [rows x k/32], mask [rows x k/32] (mask may be NULL).
+ * Requires k % 32 == 0; transpose = 1 also rows % 8 == 0.  rows*k/32 must be below 2^31.
+ */
+int quartet_quant_fwd(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                      uint8_t *codes, uint8_t *scales, uint32_t *mask, void *stream);
+
+/*
+ * Backward quantizer (Algorithm 1 Backward: H^_g(., xi) then Q(3/4 .); Section 3 "Rounding").
+ * Same logical input as quartet_quant_fwd.  Per group: h = H_32 (d . a), d_i = -1 iff bit i of
+ * sign_word (the same word for every group and for both operands of a GEMM, so the rotation
+ * cancels in the product); m = max |h_i|; scale 2^e with e = floor(log2 m) - 2 (AbsMax, power of
+ * two); v_i = fl((h_i 2^-e) * 3/4), so |v_i| < 6 and nothing clips; code_i = E2M1 of v_i by
+ *   rounding = QUARTET_ROUND_NEAREST   : round-to-nearest-even (Algorithm 1 as printed), or
+ *   rounding = QUARTET_ROUND_STOCHASTIC: with lo <= |v| < hi the neighbouring grid points and
+ *     f = (|v|-lo)/(hi-lo), round up iff (r + 1/2) / 2^16 < f, r = the element's 16-bit draw.
+ * Draws: Philox4x32-10 with key (seed & 0xFFFFFFFF, seed >> 32); the element at output position
+ * L = row*k + kk uses call q = L / 8 with counter (q_lo, q_hi, stream_id, 0) and takes bits
+ * [16 j, 16 j + 16) of the 128-bit output, j = L mod 8.  Row and transposed mode therefore give
+ * identical bytes for the same logical matrix.
+ * The stored scale is 2^e: the 3/4 is NOT folded in; consumers multiply the product of two such
+ * tensors by 16/9.
+ */
+int quartet_quant_bwd_sr(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                         uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
+                         uint8_t *codes, uint8_t *scales, void *stream);
+
+/*
+ * Re-quantization of a saved MXFP4 tensor along its other dimension (Algorithm 1 Backward:
+ * H^_g(W_q^T, xi), H^_g(X_q^T, xi) and their rounding).  src is an MXFP4 tensor stored [k x rows]
+ * (codes [k x rows/2], scales [k x rows/32], groups along `rows`).  The output is
+ * quartet_quant_bwd_sr applied to decode(src)^T, a [rows x k] matrix with groups along k
+ * (decoding is exact, so this step adds no rounding of its own).  rows % 32 == 0 and k % 32 == 0.
+ */
+int quartet_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_scales,
+                                 int64_t rows, int64_t k, uint32_t sign_word, uint64_t seed,
+                                 uint32_t stream_id, int rounding,
+                                 uint8_t *codes, uint8_t *scales, void *stream);
+
+/*
+ * GEMM_LP (Section 4.4 "Stage 2": D = (A x SFA)(B x SFB), scales along K, one per 32):
+ *   D[m x n] = alpha * sum_k dec(A)[m,k] * dec(B)[n,k]
+ * A = (a_codes [m x k/2], a_scales [m x k/32]), B = (b_codes [n x k/2], b_scales [n x k/32]), both
+ * K-contiguous.  Products are exact, accumulation is fp32 on the matrix cores.  d is fp32 or bf16
+ * (d_dtype), row-major with leading dimension ldd >= n.  k % 32 == 0; m, n arbitrary.
+ */
+int quartet_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
+                       const uint8_t *b_codes, const uint8_t *b_scales,
+                       int64_t m, int64_t n, int64_t k, float alpha,
+                       void *d, int d_dtype, int64_t ldd, void *stream);
+
+/*
+ * Gradient epilogue (Algorithm 1 Backward: 16/9 H_g^-1(G . M)):
+ *   out[m x n] = scale * H_32_along_n( g . mask ),  g fp32 [m x n], mask [m x n/32] or NULL (all ones).
+ * g . mask keeps g where the bit is set and is +0 elsewhere; H_32 is its own inverse; fp32 steps
+ * in the butterfly order of quartet_quant_fwd, the multiply by `scale` last.  out is fp32 or bf16
+ * (round-to-nearest-even) and may alias g only if out_dtype is fp32.  n % 32 == 0.
+ */
+int quartet_grad_epilogue(const float *g, const uint32_t *mask, int64_t m, int64_t n, float scale,
+                          void *out, int out_dtype, void *stream);
+
+/* fp32 values of an MXFP4 tensor: out[rows x k] = E2M1 value * 2^(scale-127).  Test/debug helper. */
+int quartet_mxfp4_dequant(const uint8_t *codes, const uint8_t *scales, int64_t rows, int64_t k,
+                          float *out, void *stream);
+
+/*
+ * Algorithm 1 Forward.  x [tokens x in], w [out x in] bf16 -> y [tokens x out] (y_dtype) and the
+ * context {X_q, W_q, M_x, M_w} written to caller buffers (shapes as for quartet_quant_fwd with
+ * k = in).  in % 32 == 0.
+ */
+int quartet_linear_fwd(const void *x_bf16, const void *w_bf16, int64_t tokens, int64_t in, int64_t out,
+                       void *y, int y_dtype,
+                       uint8_t *xq_codes, uint8_t *xq_scales, uint32_t *x_mask,
+                       uint8_t *wq_codes, uint8_t *wq_scales, uint32_t *w_mask,
+                       void *stream);
+
+/* Bytes of device workspace quartet_linear_bwd needs for these shapes (0 on invalid shapes). */
+size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out);
+
+/*
+ * Algorithm 1 Backward with seed xi.  dy [tokens x out] bf16 and the forward context ->
+ * dx [tokens x in], dw [out x in] (grad_dtype).  sign_word = first output word of Philox4x32-10 at
+ * counter (0,0,0,0xFFFFFFFF) under the seed's key; Philox stream ids 0,1,2,3 serve dy, W_q^T, dy^T,
+ * X_q^T.  tokens, in, out all % 32 == 0.  workspace: device memory of at least
+ * quartet_linear_workspace_bytes() bytes, 256-byte aligned, used only during the call's work.
+ */
+int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                       const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,
+                       const uint8_t *wq_codes, const uint8_t *wq_scales, const uint32_t *w_mask,
+                       uint64_t seed, int rounding,
+                       void *dx, void *dw, int grad_dtype,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* sign word quartet_linear_bwd derives from a seed (host computation, no GPU work). */
+uint32_t quartet_sign_word(uint64_t seed);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUARTET_H */

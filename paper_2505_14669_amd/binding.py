@@ -1,0 +1,151 @@
+"""ctypes binding of the HIP library's C ABI (include/quartet.h).
+
+Argument marshalling only: every function has the name and argument order of its C entry point,
+takes torch CUDA tensors (or raw device addresses) for the pointer arguments and returns the C
+return code.  `check()` turns a non-zero code into an exception.  PyTorch is used for device
+memory and streams only; there is no CPU fallback, and importing this module fails loudly if the
+library has not been built (python -m paper_2505_14669_amd.build, or __graft_entry__.build()).
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libquartet.so")
+
+QUARTET_OK = 0
+QUARTET_EINVAL = -1
+QUARTET_ENOTSUP = -2
+QUARTET_EHIP = -3
+QUARTET_DTYPE_F32 = 0
+QUARTET_DTYPE_BF16 = 1
+QUARTET_ROUND_STOCHASTIC = 0
+QUARTET_ROUND_NEAREST = 1
+
+EXPORTS = [
+    "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
+    "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr",
+    "quartet_mxfp4_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
+    "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
+]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build the HIP library first "
+                      "(python -m paper_2505_14669_amd.build); there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_i64, _u32, _u64, _p, _int, _f = (ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p,
+                                 ctypes.c_int, ctypes.c_float)
+_lib.quartet_last_hip_error.restype = _int
+_lib.quartet_sr_bits.restype = _int
+_lib.quartet_sign_word.restype = _u32
+_lib.quartet_sign_word.argtypes = [_u64]
+_lib.quartet_quant_fwd.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p]
+_lib.quartet_quant_bwd_sr.argtypes = [_p, _i64, _i64, _i64, _int, _u32, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_requant_transpose_sr.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_mxfp4_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
+_lib.quartet_grad_epilogue.argtypes = [_p, _p, _i64, _i64, _f, _p, _int, _p]
+_lib.quartet_mxfp4_dequant.argtypes = [_p, _p, _i64, _i64, _p, _p]
+_lib.quartet_linear_fwd.argtypes = [_p, _p, _i64, _i64, _i64, _p, _int, _p, _p, _p, _p, _p, _p, _p]
+_lib.quartet_linear_workspace_bytes.restype = ctypes.c_size_t
+_lib.quartet_linear_workspace_bytes.argtypes = [_i64, _i64, _i64]
+_lib.quartet_linear_bwd.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64, _int, _p, _p, _int,
+                                    _p, ctypes.c_size_t, _p]
+for _name in EXPORTS:
+    getattr(_lib, _name)  # AttributeError here = the library does not export what the header declares
+
+
+class QuartetError(RuntimeError):
+    pass
+
+
+def check(rc):
+    if rc != QUARTET_OK:
+        names = {QUARTET_EINVAL: "QUARTET_EINVAL", QUARTET_ENOTSUP: "QUARTET_ENOTSUP", QUARTET_EHIP: "QUARTET_EHIP"}
+        extra = f" (hipError_t {quartet_last_hip_error()})" if rc == QUARTET_EHIP else ""
+        raise QuartetError(f"{names.get(rc, rc)}{extra}")
+    return rc
+
+
+def _ptr(t):
+    """Device address of a torch tensor (must be a contiguous CUDA tensor), or a raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise QuartetError("pointer arguments must be CUDA (HIP) tensors: there is no CPU path")
+    if not t.is_contiguous():
+        raise QuartetError("tensor arguments must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def quartet_last_hip_error():
+    return _lib.quartet_last_hip_error()
+
+
+def quartet_sr_bits():
+    return _lib.quartet_sr_bits()
+
+
+def quartet_sign_word(seed):
+    return _lib.quartet_sign_word(seed)
+
+
+def quartet_quant_fwd(x_bf16, rows, k, ldx, transpose, codes, scales, mask, stream=None):
+    return _lib.quartet_quant_fwd(_ptr(x_bf16), rows, k, ldx, int(transpose), _ptr(codes), _ptr(scales),
+                                  _ptr(mask), _stream(stream))
+
+
+def quartet_quant_bwd_sr(x_bf16, rows, k, ldx, transpose, sign_word, seed, stream_id, rounding, codes, scales,
+                         stream=None):
+    return _lib.quartet_quant_bwd_sr(_ptr(x_bf16), rows, k, ldx, int(transpose), sign_word, seed, stream_id,
+                                     rounding, _ptr(codes), _ptr(scales), _stream(stream))
+
+
+def quartet_requant_transpose_sr(src_codes, src_scales, rows, k, sign_word, seed, stream_id, rounding, codes,
+                                 scales, stream=None):
+    return _lib.quartet_requant_transpose_sr(_ptr(src_codes), _ptr(src_scales), rows, k, sign_word, seed,
+                                             stream_id, rounding, _ptr(codes), _ptr(scales), _stream(stream))
+
+
+def quartet_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_dtype, ldd, stream=None):
+    return _lib.quartet_mxfp4_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
+                                   alpha, _ptr(d), d_dtype, ldd, _stream(stream))
+
+
+def quartet_grad_epilogue(g, mask, m, n, scale, out, out_dtype, stream=None):
+    return _lib.quartet_grad_epilogue(_ptr(g), _ptr(mask), m, n, scale, _ptr(out), out_dtype, _stream(stream))
+
+
+def quartet_mxfp4_dequant(codes, scales, rows, k, out, stream=None):
+    return _lib.quartet_mxfp4_dequant(_ptr(codes), _ptr(scales), rows, k, _ptr(out), _stream(stream))
+
+
+def quartet_linear_fwd(x_bf16, w_bf16, tokens, in_features, out_features, y, y_dtype, xq_codes, xq_scales,
+                       x_mask, wq_codes, wq_scales, w_mask, stream=None):
+    return _lib.quartet_linear_fwd(_ptr(x_bf16), _ptr(w_bf16), tokens, in_features, out_features, _ptr(y),
+                                   y_dtype, _ptr(xq_codes), _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes),
+                                   _ptr(wq_scales), _ptr(w_mask), _stream(stream))
+
+
+def quartet_linear_workspace_bytes(tokens, in_features, out_features):
+    return _lib.quartet_linear_workspace_bytes(tokens, in_features, out_features)
+
+
+def quartet_linear_bwd(dy_bf16, tokens, in_features, out_features, xq_codes, xq_scales, x_mask, wq_codes,
+                       wq_scales, w_mask, seed, rounding, dx, dw, grad_dtype, workspace, workspace_bytes,
+                       stream=None):
+    return _lib.quartet_linear_bwd(_ptr(dy_bf16), tokens, in_features, out_features, _ptr(xq_codes),
+                                   _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales),
+                                   _ptr(w_mask), seed, rounding, _ptr(dx), _ptr(dw), grad_dtype,
+                                   _ptr(workspace), workspace_bytes, _stream(stream))

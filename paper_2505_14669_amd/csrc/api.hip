@@ -1,0 +1,230 @@
+// C ABI of the Quartet MXFP4 library: argument validation and kernel sequencing only.
+// Declarations, argument meaning and citations are in include/quartet.h.
+#include "../../include/quartet.h"
+
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "launchers.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return QUARTET_EHIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Philox4x32-10 on the host (Salmon et al., SC'11), used only to derive the sign word.
+void philox_host(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+constexpr int64_t kMaxGroups = (int64_t)1 << 31;
+
+// shape checks shared by the quantizers; returns QUARTET_OK or an error
+int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
+    if (rows < 0 || k < 0 || (k % 32) != 0) return QUARTET_EINVAL;
+    if (transpose != 0 && transpose != 1) return QUARTET_EINVAL;
+    if ((ldx % 8) != 0 || ldx < (transpose ? rows : k)) return QUARTET_EINVAL;
+    if (transpose && (rows % 8) != 0) return QUARTET_EINVAL;
+    if (rows > 0 && (k / 32) > kMaxGroups / (rows > 0 ? rows : 1)) return QUARTET_ENOTSUP;
+    if (rows * (k / 32) >= kMaxGroups) return QUARTET_ENOTSUP;
+    if (transpose && k / 256 > 65535) return QUARTET_ENOTSUP;
+    return QUARTET_OK;
+}
+
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+struct BwdWorkspace {
+    size_t g_codes, g_scales, b_codes, b_scales, acc, total;
+};
+
+BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
+    BwdWorkspace w;
+    size_t to = (size_t)tokens * (size_t)out;
+    size_t bmax = (size_t)in * (size_t)(out > tokens ? out : tokens);
+    size_t amax = (size_t)in * (size_t)(tokens > out ? tokens : out);
+    size_t off = 0;
+    w.g_codes = off; off += align256(to / 2);
+    w.g_scales = off; off += align256(to / 32);
+    w.b_codes = off; off += align256(bmax / 2);
+    w.b_scales = off; off += align256(bmax / 32);
+    w.acc = off; off += align256(amax * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+using quartet::SrParams;
+
+extern "C" {
+
+int quartet_last_hip_error(void) { return g_last_hip_error; }
+
+int quartet_sr_bits(void) { return 16; }
+
+uint32_t quartet_sign_word(uint64_t seed) {
+    const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    philox_host(ctr, key, w);
+    return w[0];
+}
+
+int quartet_quant_fwd(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                      uint8_t* codes, uint8_t* scales, uint32_t* mask, void* stream) {
+    if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
+    if (!aligned16(x_bf16) || !aligned16(codes) || (mask && !aligned16(mask))) return QUARTET_EINVAL;
+    int rc = check_quant_shape(rows, k, ldx, transpose);
+    if (rc) return rc;
+    SrParams p = {0u, 0u, 0u, 0u};
+    hipError_t e = quartet::launch_quant(quartet::kFwd, x_bf16, rows, k, ldx, transpose, p, codes, scales,
+                                         mask, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_quant_bwd_sr(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                         uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
+                         uint8_t* codes, uint8_t* scales, void* stream) {
+    if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
+    if (!aligned16(x_bf16) || !aligned16(codes)) return QUARTET_EINVAL;
+    if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
+    int rc = check_quant_shape(rows, k, ldx, transpose);
+    if (rc) return rc;
+    SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+    hipError_t e = quartet::launch_quant(mode, x_bf16, rows, k, ldx, transpose, p, codes, scales, nullptr,
+                                         (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_scales,
+                                 int64_t rows, int64_t k, uint32_t sign_word, uint64_t seed,
+                                 uint32_t stream_id, int rounding,
+                                 uint8_t* codes, uint8_t* scales, void* stream) {
+    if (!src_codes || !src_scales || !codes || !scales) return QUARTET_EINVAL;
+    if (!aligned16(src_codes) || !aligned16(codes)) return QUARTET_EINVAL;
+    if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
+    if (rows < 0 || (rows % 32) != 0) return QUARTET_EINVAL;
+    int rc = check_quant_shape(rows, k, (rows + 7) / 8 * 8, 1);
+    if (rc) return rc;
+    SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+    hipError_t e = quartet::launch_requant_transpose(mode, src_codes, src_scales, rows, k, p, codes, scales,
+                                                     (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                       const uint8_t* b_codes, const uint8_t* b_scales,
+                       int64_t m, int64_t n, int64_t k, float alpha,
+                       void* d, int d_dtype, int64_t ldd, void* stream) {
+    if (!a_codes || !a_scales || !b_codes || !b_scales || !d) return QUARTET_EINVAL;
+    if (!aligned16(a_codes) || !aligned16(b_codes) || !aligned16(d)) return QUARTET_EINVAL;
+    if (m < 0 || n < 0 || k < 0 || (k % 32) != 0 || ldd < n) return QUARTET_EINVAL;
+    if (d_dtype != QUARTET_DTYPE_F32 && d_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
+    if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;
+    if (m / 128 > 65534) return QUARTET_ENOTSUP;
+    hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
+                                        d_dtype == QUARTET_DTYPE_BF16, ldd, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, float scale,
+                          void* out, int out_dtype, void* stream) {
+    if (!g || !out) return QUARTET_EINVAL;
+    if (!aligned16(g) || !aligned16(out)) return QUARTET_EINVAL;
+    if (m < 0 || n < 0 || (n % 32) != 0) return QUARTET_EINVAL;
+    if (out_dtype != QUARTET_DTYPE_F32 && out_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
+    if (out_dtype == QUARTET_DTYPE_BF16 && out == (const void*)g) return QUARTET_EINVAL;
+    if (m > 0 && (n / 32) >= kMaxGroups / m) return QUARTET_ENOTSUP;
+    hipError_t e = quartet::launch_grad_epilogue(g, mask, m, n, scale, out, out_dtype == QUARTET_DTYPE_BF16,
+                                                 (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_mxfp4_dequant(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t k,
+                          float* out, void* stream) {
+    if (!codes || !scales || !out) return QUARTET_EINVAL;
+    if (!aligned16(codes) || !aligned16(out)) return QUARTET_EINVAL;
+    if (rows < 0 || k < 0 || (k % 32) != 0) return QUARTET_EINVAL;
+    hipError_t e = quartet::launch_dequant(codes, scales, rows, k, out, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_linear_fwd(const void* x_bf16, const void* w_bf16, int64_t tokens, int64_t in, int64_t out,
+                       void* y, int y_dtype,
+                       uint8_t* xq_codes, uint8_t* xq_scales, uint32_t* x_mask,
+                       uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
+                       void* stream) {
+    if (!x_bf16 || !w_bf16 || !y || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask)
+        return QUARTET_EINVAL;
+    if (tokens < 0 || in < 0 || out < 0 || (in % 32) != 0) return QUARTET_EINVAL;
+    int rc = quartet_quant_fwd(x_bf16, tokens, in, in, 0, xq_codes, xq_scales, x_mask, stream);
+    if (rc) return rc;
+    rc = quartet_quant_fwd(w_bf16, out, in, in, 0, wq_codes, wq_scales, w_mask, stream);
+    if (rc) return rc;
+    return quartet_mxfp4_gemm(xq_codes, xq_scales, wq_codes, wq_scales, tokens, out, in, 1.0f, y, y_dtype,
+                              out, stream);
+}
+
+size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out) {
+    if (tokens < 0 || in < 0 || out < 0) return 0;
+    if ((tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return 0;
+    return plan_bwd(tokens, in, out).total;
+}
+
+int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                       const uint8_t* xq_codes, const uint8_t* xq_scales, const uint32_t* x_mask,
+                       const uint8_t* wq_codes, const uint8_t* wq_scales, const uint32_t* w_mask,
+                       uint64_t seed, int rounding,
+                       void* dx, void* dw, int grad_dtype,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (!dy_bf16 || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask || !dx || !dw)
+        return QUARTET_EINVAL;
+    if (tokens < 0 || in < 0 || out < 0) return QUARTET_EINVAL;
+    if ((tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return QUARTET_EINVAL;
+    if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
+    if (grad_dtype != QUARTET_DTYPE_F32 && grad_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
+    const BwdWorkspace w = plan_bwd(tokens, in, out);
+    if (w.total > 0 && (!workspace || workspace_bytes < w.total)) return QUARTET_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUARTET_EINVAL;
+    uint8_t* base = static_cast<uint8_t*>(workspace);
+    uint8_t *g_codes = base + w.g_codes, *g_scales = base + w.g_scales;
+    uint8_t *b_codes = base + w.b_codes, *b_scales = base + w.b_scales;
+    float* acc = reinterpret_cast<float*>(base + w.acc);
+    const uint32_t sw = quartet_sign_word(seed);
+    const float c169 = 16.0f / 9.0f;
+    int rc;
+    // dx = 16/9 H( (Q(dy) Q(W_q^T)^T) . M_x ), inner dimension = out
+    rc = quartet_quant_bwd_sr(dy_bf16, tokens, out, out, 0, sw, seed, 0u, rounding, g_codes, g_scales, stream);
+    if (rc) return rc;
+    rc = quartet_requant_transpose_sr(wq_codes, wq_scales, in, out, sw, seed, 1u, rounding, b_codes, b_scales, stream);
+    if (rc) return rc;
+    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+    if (rc) return rc;
+    rc = quartet_grad_epilogue(acc, x_mask, tokens, in, c169, dx, grad_dtype, stream);
+    if (rc) return rc;
+    // dW = 16/9 H( (Q(dy^T) Q(X_q^T)^T) . M_w ), inner dimension = tokens
+    rc = quartet_quant_bwd_sr(dy_bf16, out, tokens, out, 1, sw, seed, 2u, rounding, g_codes, g_scales, stream);
+    if (rc) return rc;
+    rc = quartet_requant_transpose_sr(xq_codes, xq_scales, in, tokens, sw, seed, 3u, rounding, b_codes, b_scales, stream);
+    if (rc) return rc;
+    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+    if (rc) return rc;
+    return quartet_grad_epilogue(acc, w_mask, out, in, c169, dw, grad_dtype, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,352 @@
+// Fused Hadamard + MXFP4 quantizer kernels for gfx950 (Algorithm 1, "Stage 1" of Section 4.4).
+//
+// One lane owns one group of 32 values end to end: the five butterfly stages, the group
+// reduction (sum of squares or absmax), the scale and the 32 codes all stay in that lane's
+// registers, so nothing crosses lanes and the fp32 operation order is fixed.  HBM traffic is
+// made wave-coalesced on both sides by staging through LDS:
+//   row mode        : a wave loads 4 KB (64 groups) with 16-byte lane-contiguous loads, swizzles it
+//                     through LDS so each lane gets its own 64 bytes; codes leave as one 16-byte
+//                     store per lane.
+//   transposed mode : a block owns 256 source rows x 128 source columns; lanes read 2 adjacent
+//                     columns per row (4-byte loads, 256 B per wave row), and the 8 groups of codes
+//                     of each output row are gathered in LDS and written as full 128-byte lines.
+#include "device_common.h"
+#include "launchers.h"
+
+namespace quartet {
+
+// Eight values -> eight E2M1 codes in one dword: round-to-nearest-even of v/scale (scale a power
+// of two), saturating at +-6, element j in bits [4j, 4j+4).
+__device__ __forceinline__ uint32_t rtn_pack8(const float* v, float scale) {
+    uint32_t w = 0u;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[0], v[1], scale, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[2], v[3], scale, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[4], v[5], scale, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[6], v[7], scale, 3);
+    return w;
+}
+
+// Quantize one group held in v[] (not yet rotated).  q_base = (linear output position of element 0)/8
+// is the Philox call index of the group's first 8 elements.
+template <int MODE>
+__device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p, uint64_t q_base,
+                                               uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
+    if (MODE != kFwd) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = u2f(f2u(v[i]) ^ (((p.sign_word >> i) & 1u) << 31));
+    }
+    fwht32(v);
+    uint32_t c[4] = {0u, 0u, 0u, 0u};
+    if (MODE == kFwd) {
+        // QuEST: scale from the group RMS, round to nearest, remember what clipped
+        float t[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) t[i] = v[i] * v[i];
+#pragma unroll
+        for (int n = 16; n >= 1; n >>= 1) {
+#pragma unroll
+            for (int i = 0; i < n; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+        }
+        uint32_t E = (f2u(t[0]) >> 23) & 0xFFu;
+        int e = (E == 0u) ? 0 : (((int)E - 133) >> 1);   // floor((log2 ss - 6) / 2)
+        uint32_t b = (uint32_t)(e + 127);
+        float scale = u2f(b << 23);                        // 2^e
+        float thr = u2f(0x40C00000u + ((uint32_t)e << 23)); // 6 * 2^e
+        uint32_t m = 0u;
+#pragma unroll
+        for (int i = 31; i >= 0; --i) m = (m << 1) | (__builtin_fabsf(v[i]) <= thr ? 1u : 0u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = rtn_pack8(&v[8 * i], scale);
+        scale_byte = b;
+        mask_word = m;
+    } else {
+        // AbsMax power-of-two scale, 3/4 range matching, RTN or SR (nothing clips)
+        float mx = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) mx = __builtin_fmaxf(mx, __builtin_fabsf(v[i]));
+        uint32_t E = (f2u(mx) >> 23) & 0xFFu;
+        uint32_t b = (E == 0u) ? 127u : (E >= 2u ? E - 2u : 0u);
+        float mult = u2f((254u - b) << 23) * 0.75f;        // 3/4 * 2^-e, exact
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * mult;
+        if (MODE == kBwdRtn) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c[i] = rtn_pack8(&v[8 * i], 1.0f);
+        } else {
+#pragma unroll
+            for (int call = 0; call < 4; ++call) {
+                uint64_t q = q_base + (uint64_t)call;
+                uint32_t w[4];
+                philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), p.stream_id, 0u, p.key0, p.key1, w);
+                uint32_t word = 0u;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    uint32_t r = (w[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                    word |= sr_e2m1(v[8 * call + j], r) << (4 * j);
+                }
+                c[call] = word;
+            }
+        }
+        scale_byte = b;
+        mask_word = 0xFFFFFFFFu;
+    }
+    codes = make_uint4(c[0], c[1], c[2], c[3]);
+}
+
+__device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
+    v[0] = u2f(q.x << 16); v[1] = u2f(q.x & 0xFFFF0000u);
+    v[2] = u2f(q.y << 16); v[3] = u2f(q.y & 0xFFFF0000u);
+    v[4] = u2f(q.z << 16); v[5] = u2f(q.z & 0xFFFF0000u);
+    v[6] = u2f(q.w << 16); v[7] = u2f(q.w & 0xFFFF0000u);
+}
+
+// ------------------------------------------------------------------ row mode, contiguous input
+// x is a flat array of n_groups groups (rows*k/32, ldx == k).  Block = 4 waves, a wave per 64 groups.
+template <int MODE, bool MASK>
+__global__ void __launch_bounds__(256)
+quant_row_flat_kernel(const uint4* __restrict__ x, uint32_t n_groups, uint4* __restrict__ codes,
+                      uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
+    __shared__ uint4 stage[4][256];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t base_group = (blockIdx.x * 4u + wave) * 64u;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        uint32_t c = 64u * j + lane;                       // 16-byte chunk inside the wave's 4 KB
+        uint32_t g = base_group + (c >> 2);
+        uint4 q = (g < n_groups) ? x[(size_t)base_group * 4u + c] : zero;
+        uint32_t pos = (c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u));
+        stage[wave][pos] = q;
+    }
+    __syncthreads();
+    float v[32];
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        uint32_t pos = 4u * lane + (j ^ ((lane >> 1) & 3u));
+        uint4 q = stage[wave][pos];
+        unpack_bf16x8(q, &v[8 * j]);
+    }
+    const uint32_t g = base_group + lane;
+    uint4 out;
+    uint32_t sb, mw;
+    quantize_group<MODE>(v, p, (uint64_t)g * 4u, out, sb, mw);
+    if (g < n_groups) {
+        codes[g] = out;
+        scales[g] = (uint8_t)sb;
+        if (MASK) mask[g] = mw;
+    }
+}
+
+// ------------------------------------------------------------------ row mode, strided rows
+template <int MODE, bool MASK>
+__global__ void __launch_bounds__(256)
+quant_row_strided_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
+                         uint4* __restrict__ codes, uint8_t* __restrict__ scales,
+                         uint32_t* __restrict__ mask, SrParams p) {
+    const uint32_t g = blockIdx.x * 256u + threadIdx.x;   // group inside the row
+    if (g >= gk) return;
+    for (uint32_t row = blockIdx.y; row < rows; row += gridDim.y) {
+        const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)row * ldx + (size_t)g * 32u);
+        float v[32];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) unpack_bf16x8(src[j], &v[8 * j]);
+        const uint64_t gi = (uint64_t)row * gk + g;
+        uint4 out;
+        uint32_t sb, mw;
+        quantize_group<MODE>(v, p, gi * 4u, out, sb, mw);
+        codes[gi] = out;
+        scales[gi] = (uint8_t)sb;
+        if (MASK) mask[gi] = mw;
+    }
+}
+
+// ------------------------------------------------------------------ transposed sources
+// Logical A[rows x k] = S^T where the source S has k rows.  SRC = 0: S is bf16 [k x ldx];
+// SRC = 1: S is MXFP4 [k x rows] (codes [k x rows/2], scales [k x rows/32]), decoded exactly.
+// Block tile: 8 groups (256 source rows) x 128 source columns; wave w owns groups 2w, 2w+1;
+// lane l owns columns 2l, 2l+1.
+template <int MODE, bool MASK, int SRC>
+__global__ void __launch_bounds__(256)
+quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict__ src_scales,
+                        uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
+                        uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
+    __shared__ uint4 s_codes[128 * 8];
+    __shared__ uint8_t s_scales[128 * 8];
+    __shared__ uint32_t s_mask[128 * 8];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t gk = k >> 5;
+    const uint32_t col0 = blockIdx.x * 128u;
+    const uint32_t grp0 = blockIdx.y * 8u;
+    const uint32_t col = col0 + 2u * lane;                // even; rows is even, so col+1 < rows too
+    const bool col_ok = col < rows;
+
+#pragma unroll 1
+    for (uint32_t rb = 0; rb < 2; ++rb) {
+        const uint32_t gl = 2u * wave + rb;               // group inside the block tile
+        const uint32_t grp = grp0 + gl;
+        const bool ok = col_ok && grp < gk;
+        float v0[32], v1[32];
+        if (SRC == 0) {
+            const uint16_t* x = static_cast<const uint16_t*>(src);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                uint32_t w = 0u;
+                if (ok) w = *reinterpret_cast<const uint32_t*>(x + (size_t)(grp * 32u + i) * ldx + col);
+                v0[i] = u2f(w << 16);
+                v1[i] = u2f(w & 0xFFFF0000u);
+            }
+        } else {
+            const uint8_t* sc = static_cast<const uint8_t*>(src);
+            const uint32_t half = rows >> 1, sgk = rows >> 5;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                uint32_t byte = 0u, sb = 127u;
+                if (ok) {
+                    size_t r = (size_t)(grp * 32u + i);
+                    byte = sc[r * half + (col >> 1)];
+                    sb = src_scales[r * sgk + (col >> 5)];
+                }
+                v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, u2f(sb << 23), 0);
+                v0[i] = d[0];
+                v1[i] = d[1];
+            }
+        }
+        uint4 c0, c1;
+        uint32_t sb0, sb1, m0, m1;
+        // output position of element 0 of the group: row*k + grp*32, divided by 8
+        quantize_group<MODE>(v0, p, ((uint64_t)col * k + grp * 32u) >> 3, c0, sb0, m0);
+        quantize_group<MODE>(v1, p, ((uint64_t)(col + 1u) * k + grp * 32u) >> 3, c1, sb1, m1);
+        const uint32_t lc = 2u * lane;                    // local column
+        const uint32_t sw = lane & 7u;                    // 16-byte slot swizzle against bank conflicts
+        s_codes[lc * 8u + (gl ^ sw)] = c0;
+        s_codes[(lc + 1u) * 8u + (gl ^ sw)] = c1;
+        s_scales[lc * 8u + gl] = (uint8_t)sb0;
+        s_scales[(lc + 1u) * 8u + gl] = (uint8_t)sb1;
+        if (MASK) {
+            s_mask[lc * 8u + gl] = m0;
+            s_mask[(lc + 1u) * 8u + gl] = m1;
+        }
+    }
+    __syncthreads();
+    // full 128-byte lines of codes: 8 lanes per output row
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        uint32_t id = threadIdx.x + 256u * j;
+        uint32_t lc = id >> 3, part = id & 7u;
+        uint32_t r = col0 + lc, grp = grp0 + part;
+        if (r < rows && grp < gk) {
+            uint4 q = s_codes[lc * 8u + (part ^ ((lc >> 1) & 7u))];
+            *reinterpret_cast<uint4*>(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u) = q;
+        }
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        uint32_t id = threadIdx.x + 256u * j;
+        uint32_t lc = id >> 3, part = id & 7u;
+        uint32_t r = col0 + lc, grp = grp0 + part;
+        if (r < rows && grp < gk) {
+            scales[(size_t)r * gk + grp] = s_scales[lc * 8u + part];
+            if (MASK) mask[(size_t)r * gk + grp] = s_mask[lc * 8u + part];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ MXFP4 -> fp32
+__global__ void __launch_bounds__(256)
+dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, uint64_t n_groups,
+               float* __restrict__ out) {
+    uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (g >= n_groups) return;
+    uint4 q = reinterpret_cast<const uint4*>(codes)[g];
+    float s = u2f((uint32_t)scales[g] << 23);
+    uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    float4* dst = reinterpret_cast<float4*>(out + g * 32u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], s, 0);
+        v2f b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], s, 1);
+        v2f c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], s, 2);
+        v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], s, 3);
+        dst[2 * i] = make_float4(a[0], a[1], b[0], b[1]);
+        dst[2 * i + 1] = make_float4(c[0], c[1], d[0], d[1]);
+    }
+}
+
+// ------------------------------------------------------------------ host-side launchers
+
+template <int MODE>
+static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
+                             uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
+    const uint64_t n_groups = (uint64_t)rows * (uint64_t)(k / 32);
+    if (n_groups == 0) return hipSuccess;
+    if (ldx == k) {
+        uint32_t tiles = (uint32_t)((n_groups + 63) / 64);
+        dim3 grid((tiles + 3) / 4), block(256);
+        if (mask)
+            hipLaunchKernelGGL((quant_row_flat_kernel<MODE, true>), grid, block, 0, st, (const uint4*)x,
+                               (uint32_t)n_groups, (uint4*)codes, scales, mask, p);
+        else
+            hipLaunchKernelGGL((quant_row_flat_kernel<MODE, false>), grid, block, 0, st, (const uint4*)x,
+                               (uint32_t)n_groups, (uint4*)codes, scales, mask, p);
+    } else {
+        uint32_t gk = (uint32_t)(k / 32);
+        dim3 grid((gk + 255) / 256, (uint32_t)(rows < 65535 ? rows : 65535)), block(256);
+        if (mask)
+            hipLaunchKernelGGL((quant_row_strided_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)x,
+                               (uint32_t)rows, gk, ldx, (uint4*)codes, scales, mask, p);
+        else
+            hipLaunchKernelGGL((quant_row_strided_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)x,
+                               (uint32_t)rows, gk, ldx, (uint4*)codes, scales, mask, p);
+    }
+    return hipGetLastError();
+}
+
+template <int MODE, int SRC>
+static hipError_t launch_transposed(const void* src, const uint8_t* src_scales, int64_t rows, int64_t k,
+                                    int64_t ldx, uint8_t* codes, uint8_t* scales, uint32_t* mask,
+                                    const SrParams& p, hipStream_t st) {
+    if (rows == 0 || k == 0) return hipSuccess;
+    dim3 grid((uint32_t)((rows + 127) / 128), (uint32_t)((k / 32 + 7) / 8)), block(256);
+    if (mask)
+        hipLaunchKernelGGL((quant_transposed_kernel<MODE, true, SRC>), grid, block, 0, st, src, src_scales,
+                           (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
+    else
+        hipLaunchKernelGGL((quant_transposed_kernel<MODE, false, SRC>), grid, block, 0, st, src, src_scales,
+                           (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                        const SrParams& p, uint8_t* codes, uint8_t* scales, uint32_t* mask, hipStream_t st) {
+    if (!transpose) {
+        switch (mode) {
+        case kFwd: return launch_row<kFwd>(x, rows, k, ldx, codes, scales, mask, p, st);
+        case kBwdRtn: return launch_row<kBwdRtn>(x, rows, k, ldx, codes, scales, nullptr, p, st);
+        default: return launch_row<kBwdSr>(x, rows, k, ldx, codes, scales, nullptr, p, st);
+        }
+    }
+    switch (mode) {
+    case kFwd: return launch_transposed<kFwd, 0>(x, nullptr, rows, k, ldx, codes, scales, mask, p, st);
+    case kBwdRtn: return launch_transposed<kBwdRtn, 0>(x, nullptr, rows, k, ldx, codes, scales, nullptr, p, st);
+    default: return launch_transposed<kBwdSr, 0>(x, nullptr, rows, k, ldx, codes, scales, nullptr, p, st);
+    }
+}
+
+hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const uint8_t* src_scales,
+                                    int64_t rows, int64_t k, const SrParams& p, uint8_t* codes,
+                                    uint8_t* scales, hipStream_t st) {
+    if (mode == kBwdRtn)
+        return launch_transposed<kBwdRtn, 1>(src_codes, src_scales, rows, k, 0, codes, scales, nullptr, p, st);
+    return launch_transposed<kBwdSr, 1>(src_codes, src_scales, rows, k, 0, codes, scales, nullptr, p, st);
+}
+
+hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t k, float* out,
+                          hipStream_t st) {
+    uint64_t n_groups = (uint64_t)rows * (uint64_t)(k / 32);
+    if (n_groups == 0) return hipSuccess;
+    dim3 grid((uint32_t)((n_groups + 255) / 256)), block(256);
+    hipLaunchKernelGGL(dequant_kernel, grid, block, 0, st, codes, scales, n_groups, out);
+    return hipGetLastError();
+}
+
+}  // namespace quartet

@@ -1,0 +1,84 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "quartet.h")
+LIB = os.path.join(ROOT, "paper_2505_14669_amd", "libquartet.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="HIP library not built (run __graft_entry__.build())")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(quartet_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(LIB)
+    names = declared_symbols()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_mirrors_the_header():
+    from paper_2505_14669_amd import binding
+    for name in declared_symbols():
+        assert callable(getattr(binding, name)), name
+    assert sorted(binding.EXPORTS) == declared_symbols()
+    assert binding.quartet_sr_bits() == 16
+
+
+def test_sign_word_is_philox_of_the_seed():
+    # counter (0,0,0,0xFFFFFFFF), key = seed words; checked against the oracle's generator, which is
+    # itself pinned to the published known-answer vectors
+    import oracle
+    from paper_2505_14669_amd import binding
+    for seed in (0, 1, 77, 0x123456789ABCDEF0, 2 ** 64 - 1):
+        assert binding.quartet_sign_word(seed) == oracle.sign_word(seed)
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    from paper_2505_14669_amd import binding as q
+    P = 0x10000  # fake, aligned, never dereferenced: validation fails first
+    E = q.QUARTET_EINVAL
+    assert q.quartet_quant_fwd(None, 4, 32, 32, 0, P, P, P, 0) == E
+    assert q.quartet_quant_fwd(P, 4, 48, 48, 0, P, P, P, 0) == E          # k % 32
+    assert q.quartet_quant_fwd(P, 4, 64, 32, 0, P, P, P, 0) == E          # ldx < k
+    assert q.quartet_quant_fwd(P, 4, 64, 68, 0, P, P, P, 0) == E          # ldx % 8
+    assert q.quartet_quant_fwd(P + 2, 4, 64, 64, 0, P, P, P, 0) == E      # alignment
+    assert q.quartet_quant_fwd(P, -1, 64, 64, 0, P, P, P, 0) == E
+    assert q.quartet_quant_fwd(P, 12, 64, 16, 1, P, P, P, 0) == E         # transposed: rows % 8
+    assert q.quartet_quant_fwd(P, 2 ** 40, 2 ** 20, 2 ** 20, 0, P, P, P, 0) == q.QUARTET_ENOTSUP
+    assert q.quartet_quant_bwd_sr(P, 4, 64, 64, 0, 0, 0, 0, 2, P, P, 0) == E  # rounding
+    assert q.quartet_quant_bwd_sr(P, 4, 64, 64, 0, 0, 0, 0, 0, None, P, 0) == E
+    assert q.quartet_requant_transpose_sr(P, P, 48, 64, 0, 0, 0, 0, P, P, 0) == E  # rows % 32
+    assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 4, 40, 1.0, P, 0, 4, 0) == E
+    assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 8, 64, 1.0, P, 0, 4, 0) == E    # ldd < n
+    assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 8, 64, 1.0, P, 7, 8, 0) == E    # dtype
+    assert q.quartet_grad_epilogue(P, None, 4, 40, 1.0, P, 0, 0) == E
+    assert q.quartet_grad_epilogue(P, None, 4, 64, 1.0, P, 1, 0) == E          # bf16 in place
+    assert q.quartet_mxfp4_dequant(P, None, 4, 64, P, 0) == E
+    assert q.quartet_linear_fwd(P, P, 4, 48, 8, P, 0, P, P, P, P, P, P, 0) == E
+    assert q.quartet_linear_workspace_bytes(100, 64, 64) == 0
+    need = q.quartet_linear_workspace_bytes(64, 64, 96)
+    assert need > 0 and need % 256 == 0
+    assert q.quartet_linear_bwd(P, 64, 64, 96, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need - 1, 0) == E
+    assert q.quartet_linear_bwd(P, 64, 64, 96, P, P, P, P, P, P, 0, 0, P, P, 0, None, need, 0) == E
+    assert q.quartet_linear_bwd(P, 64, 60, 96, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need, 0) == E
+    assert q.quartet_last_hip_error() == 0
+
+
+def test_empty_problems_are_accepted_without_a_gpu():
+    from paper_2505_14669_amd import binding as q
+    P = 0x10000
+    assert q.quartet_quant_fwd(P, 0, 64, 64, 0, P, P, P, 0) == 0
+    assert q.quartet_quant_bwd_sr(P, 0, 64, 64, 0, 0, 0, 0, 0, P, P, 0) == 0
+    assert q.quartet_mxfp4_gemm(P, P, P, P, 0, 8, 64, 1.0, P, 0, 8, 0) == 0
+    assert q.quartet_grad_epilogue(P, None, 0, 64, 1.0, P, 0, 0) == 0

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: packed FP4 codes, scale bytes and mask words bit-exact; GEMM and gradient outputs within a
+relative Frobenius error of 1e-5 (fp32 accumulation on the matrix cores against the oracle's fp64;
+the bound sqrt(K/32) * 2^-24 is far below it)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_14669_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+FRO_TOL = 1e-5
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a)
+
+
+def same(a, b, what):
+    a, b = np.asarray(a), np.asarray(b)
+    assert a.shape == b.shape, (what, a.shape, b.shape)
+    bad = np.argwhere(a != b)
+    assert bad.size == 0, f"{what}: {len(bad)} mismatches, first at {bad[0]}: got {a[tuple(bad[0])]:#x} want {b[tuple(bad[0])]:#x}"
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+SHAPES = [(1, 32), (3, 64), (64, 256), (37, 96), (129, 2080), (256, 512), (700, 160)]
+KINDS = ["normal", "outliers", "heavy", "tiny", "zeros"]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_quant_fwd_row(G, shape):
+    for j, kind in enumerate(KINDS):
+        x = synth.small_matrix(100 + j, shape[0], shape[1], kind)
+        got = G.quant_fwd(x)
+        want = oracle.quant_fwd(x)
+        for g, w, name in zip(got, want, ("codes", "scales", "mask")):
+            same(g, w, f"fwd row {shape} {kind} {name}")
+    got = G.quant_fwd(x, want_mask=False)
+    same(got[0], want[0], "codes without mask")
+
+
+def test_quant_fwd_row_strided(G):
+    full = synth.small_matrix(7, 50, 256, "outliers")
+    x = full[:, :160]
+    import torch
+    xd = G.to_dev(full)
+    codes = G.dev_empty((50, 80), np.uint8, 0)
+    scales = G.dev_empty((50, 5), np.uint8, 0)
+    mask = G.dev_empty((50, 5), np.uint32, 0)
+    from paper_2505_14669_amd import binding as q
+    q.check(q.quartet_quant_fwd(xd, 50, 160, 256, 0, codes, scales, mask))
+    want = oracle.quant_fwd(np.ascontiguousarray(x))
+    same(G.to_host(codes, np.uint8), want[0], "strided codes")
+    same(G.to_host(scales, np.uint8), want[1], "strided scales")
+    same(G.to_host(mask, np.uint32), want[2], "strided mask")
+
+
+@pytest.mark.parametrize("shape", [(32, 8), (64, 128), (96, 40), (256, 136), (288, 264), (1056, 72)])
+def test_quant_fwd_transposed(G, shape):
+    # source stored [k, rows]
+    for j, kind in enumerate(("normal", "outliers", "heavy")):
+        x = synth.small_matrix(200 + j, shape[0], shape[1], kind)
+        got = G.quant_fwd(x, transpose=True)
+        want = oracle.quant_fwd(x, transpose=True)
+        for g, w, name in zip(got, want, ("codes", "scales", "mask")):
+            same(g, w, f"fwd transposed {shape} {kind} {name}")
+
+
+@pytest.mark.parametrize("rounding", [1, 0])
+@pytest.mark.parametrize("shape", [(1, 32), (64, 256), (37, 96), (129, 2080), (700, 160)])
+def test_quant_bwd_row(G, shape, rounding):
+    for j, (kind, sw, seed, sid) in enumerate([("normal", 0, 0, 0), ("outliers", 0xDEADBEEF, 12345, 1),
+                                               ("heavy", 0xFFFFFFFF, 2 ** 63 + 5, 3), ("tiny", 0x1, 7, 2),
+                                               ("zeros", 0xF0F0F0F0, 9, 0)]):
+        x = synth.small_matrix(300 + j, shape[0], shape[1], kind, scale=1e-3)
+        got = G.quant_bwd_sr(x, sw, seed, sid, rounding)
+        want = oracle.quant_bwd_sr(x, sw, seed, sid, rounding)
+        same(got[1], want[1], f"bwd row {shape} {kind} r={rounding} scales")
+        same(got[0], want[0], f"bwd row {shape} {kind} r={rounding} codes")
+
+
+@pytest.mark.parametrize("rounding", [1, 0])
+@pytest.mark.parametrize("shape", [(32, 8), (64, 128), (96, 40), (288, 264), (1056, 72)])
+def test_quant_bwd_transposed(G, shape, rounding):
+    for j, (kind, sw, seed, sid) in enumerate([("normal", 0x13572468, 5, 2), ("heavy", 0x80000001, 2 ** 40 + 3, 0)]):
+        x = synth.small_matrix(400 + j, shape[0], shape[1], kind, scale=1e-3)
+        got = G.quant_bwd_sr(x, sw, seed, sid, rounding, transpose=True)
+        want = oracle.quant_bwd_sr(x, sw, seed, sid, rounding, transpose=True)
+        same(got[1], want[1], f"bwd transposed {shape} {kind} r={rounding} scales")
+        same(got[0], want[0], f"bwd transposed {shape} {kind} r={rounding} codes")
+
+
+@pytest.mark.parametrize("rounding", [1, 0])
+@pytest.mark.parametrize("shape", [(32, 32), (64, 128), (96, 160), (288, 256), (1056, 96)])
+def test_requant_transpose(G, shape, rounding):
+    # source MXFP4 [k, rows] made by the oracle's forward quantizer
+    x = synth.small_matrix(500, shape[0], shape[1], "outliers")
+    sc, ss, _ = oracle.quant_fwd(x)
+    got = G.requant_transpose_sr(sc, ss, 0xA5A5A5A5, 99, 1, rounding)
+    want = oracle.requant_transpose_sr(sc, ss, 0xA5A5A5A5, 99, 1, rounding)
+    same(got[1], want[1], f"requant {shape} r={rounding} scales")
+    same(got[0], want[0], f"requant {shape} r={rounding} codes")
+
+
+def test_dequant(G):
+    rng = np.random.default_rng(1)
+    codes = rng.integers(0, 256, size=(33, 48), dtype=np.uint8)
+    scales = rng.integers(1, 250, size=(33, 3), dtype=np.uint8)
+    got = G.dequant(codes, scales)
+    want = oracle.mxfp4_dequant(codes, scales).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_gemm_exhaustive_code_pairs_bit_exact(G):
+    # single group, every code pair, several scale pairs: sums of 32 multiples of 1/4 are exact in fp32
+    a = np.array([[i | (i << 4)] * 16 for i in range(16)], dtype=np.uint8)
+    for sa, sb in ((127, 127), (120, 131), (100, 150), (140, 100)):
+        got = G.gemm(a, np.full((16, 1), sa, np.uint8), a, np.full((16, 1), sb, np.uint8))
+        want = oracle.mxfp4_gemm(a, np.full((16, 1), sa, np.uint8), a, np.full((16, 1), sb, np.uint8))
+        assert np.array_equal(got.astype(np.float64), want)
+    # mixed codes, equal scales, several groups: still exact
+    rng = np.random.default_rng(2)
+    ac = rng.integers(0, 256, size=(40, 64), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(24, 64), dtype=np.uint8)
+    one_a, one_b = np.full((40, 4), 127, np.uint8), np.full((24, 4), 127, np.uint8)
+    got = G.gemm(ac, one_a, bc, one_b)
+    assert np.array_equal(got.astype(np.float64), oracle.mxfp4_gemm(ac, one_a, bc, one_b))
+
+
+@pytest.mark.parametrize("mnk", [(1, 1, 32), (32, 32, 64), (128, 128, 128), (130, 70, 96), (257, 129, 160),
+                                 (64, 300, 1024), (384, 256, 2048)])
+def test_gemm_random(G, mnk):
+    m, n, k = mnk
+    rng = np.random.default_rng(m * 1000 + n)
+    ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    asc = rng.integers(117, 137, size=(m, k // 32), dtype=np.uint8)
+    bsc = rng.integers(117, 137, size=(n, k // 32), dtype=np.uint8)
+    want = oracle.mxfp4_gemm(ac, asc, bc, bsc, alpha=0.75)
+    got = G.gemm(ac, asc, bc, bsc, alpha=0.75)
+    assert rel_fro(got, want) < FRO_TOL
+    got_ld = G.gemm(ac, asc, bc, bsc, alpha=0.75, ldd=n + 5)
+    assert np.array_equal(got_ld[:, :n], got) and np.all(np.isnan(got_ld[:, n:]))
+    got_bf = synth.bf16_to_f32(G.gemm(ac, asc, bc, bsc, alpha=0.75, bf16=True))
+    assert np.array_equal(got_bf, synth.bf16_to_f32(synth.f32_to_bf16(got)))
+
+
+@pytest.mark.parametrize("shape", [(1, 32), (6, 96), (77, 160), (256, 512)])
+def test_grad_epilogue(G, shape):
+    rng = np.random.default_rng(shape[0])
+    g = rng.standard_normal(shape).astype(np.float32)
+    mask = rng.integers(0, 2 ** 32, size=(shape[0], shape[1] // 32), dtype=np.uint32)
+    want = oracle.grad_epilogue(g, mask)
+    got = G.grad_epilogue(g, mask, oracle.FL_16_9)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    got2 = G.grad_epilogue(g, mask, oracle.FL_16_9, in_place=True)
+    assert np.array_equal(got2.view(np.uint32), want.view(np.uint32))
+    got3 = G.grad_epilogue(g, None, 1.0)
+    assert np.array_equal(got3.view(np.uint32), oracle.grad_epilogue(g, None, 1.0).view(np.uint32))
+    got4 = G.grad_epilogue(g, mask, oracle.FL_16_9, bf16=True)
+    assert np.array_equal(got4, synth.f32_to_bf16(want))
+
+
+def _check_linear(G, L, seed, roundings=(0, 1)):
+    lin = G.Linear(L["x"], L["w"])
+    lin.fwd()
+    y_ref, ctx_ref = oracle.linear_fwd(L["x"], L["w"])
+    ctx = lin.ctx_host()
+    for key in ctx_ref:
+        same(ctx[key], ctx_ref[key], f"ctx {key}")
+    assert rel_fro(G.to_host(lin.y, np.float32), y_ref) < FRO_TOL
+    dy = G.to_dev(L["dy"])
+    for rounding in roundings:
+        lin.bwd(dy, seed, rounding)
+        dx_ref, dw_ref = oracle.linear_bwd(L["dy"], ctx_ref, seed, rounding)
+        assert rel_fro(G.to_host(lin.dx, np.float32), dx_ref) < FRO_TOL
+        assert rel_fro(G.to_host(lin.dw, np.float32), dw_ref) < FRO_TOL
+
+
+def test_linear_config1_full(G):
+    # configuration 1: tokens 256, in 512, out 512, outlier channels, SR seed 0
+    _check_linear(G, synth.make_layer(1, 0), seed=0)
+
+
+def test_linear_ragged_small(G):
+    L = dict(x=synth.small_matrix(1, 96, 160, "heavy"), w=synth.small_matrix(2, 224, 160, "normal", 0.02),
+             dy=synth.small_matrix(3, 96, 224, "normal", 1e-3))
+    _check_linear(G, L, seed=2 ** 33 + 17)
