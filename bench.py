@@ -1,0 +1,201 @@
+"""Benchmark of the Quartet MXFP4 linear-layer path on one MI355X.
+
+One step = forward + backward (Algorithm 1) of every linear layer of the workload, through
+quartet_linear_fwd / quartet_linear_bwd, with inputs already resident in HBM.  Prints ONE JSON
+line: whole-job TFLOP/s (6*T*I*O flops per layer), the roofline of the dominant kernel (the FP4
+MFMA GEMM, timed by the library's per-launch HIP events inside the timed region) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP4_TFLOPS = 10100.0   # MI355X dense MXFP4 MFMA peak (256 CU x 2.4 GHz x 16384 flop/clk/CU)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="workload: configuration 1..4")
+    ap.add_argument("--rounding", type=int, default=0, help="backward rounding: 0 = stochastic, 1 = nearest")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-kind time breakdown to stderr")
+    return ap.parse_args()
+
+
+class Layer:
+    def __init__(self, q, torch, L):
+        t, i, o = L["tokens"], L["in_features"], L["out_features"]
+        self.t, self.i, self.o, self.name = t, i, o, L["name"]
+        dev = L["x"].device
+        u8 = dict(dtype=torch.uint8, device=dev)
+        i32 = dict(dtype=torch.int32, device=dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.x, self.w, self.dy = L["x"], L["w"], L["dy"]
+        self.y = torch.empty((t, o), **f32)
+        self.xq_codes, self.xq_scales, self.x_mask = (torch.empty((t, i // 2), **u8), torch.empty((t, i // 32), **u8),
+                                                      torch.empty((t, i // 32), **i32))
+        self.wq_codes, self.wq_scales, self.w_mask = (torch.empty((o, i // 2), **u8), torch.empty((o, i // 32), **u8),
+                                                      torch.empty((o, i // 32), **i32))
+        self.dx = torch.empty((t, i), **f32)
+        self.dw = torch.empty((o, i), **f32)
+        self.ws_bytes = q.quartet_linear_workspace_bytes(t, i, o)
+        self.flops = 6.0 * t * i * o
+
+    def step(self, q, ws, seed, rounding):
+        q.check(q.quartet_linear_fwd(self.x, self.w, self.t, self.i, self.o, self.y, q.QUARTET_DTYPE_F32,
+                                     self.xq_codes, self.xq_scales, self.x_mask,
+                                     self.wq_codes, self.wq_scales, self.w_mask))
+        q.check(q.quartet_linear_bwd(self.dy, self.t, self.i, self.o, self.xq_codes, self.xq_scales, self.x_mask,
+                                     self.wq_codes, self.wq_scales, self.w_mask, seed, rounding,
+                                     self.dx, self.dw, q.QUARTET_DTYPE_F32, ws, self.ws_bytes))
+
+
+def cpu_baseline(config):
+    """The oracle, as it stands, on a bounded sample: the first layer of the workload with the token
+    count cut so that the run takes roughly 10-30 s of CPU work."""
+    import numpy as np
+    import oracle
+    from paper_2505_14669_amd import synth
+    name, t, i, o = synth.CONFIGS[config]["layers"][0]
+    budget = 1.2e11                       # MACs-ish the plain fp64 loops get through in ~15 s on a few cores
+    ts = int(min(t, max(32, (budget / (3.0 * i * o)) // 32 * 32)))
+    rng = np.random.Generator(np.random.PCG64(4242))
+    x = synth.f32_to_bf16(rng.standard_t(3.0, size=(ts, i)).astype(np.float32))
+    w = synth.f32_to_bf16(rng.standard_normal((o, i), dtype=np.float32) * np.float32(0.02))
+    dy = synth.f32_to_bf16(rng.standard_normal((ts, o), dtype=np.float32) * np.float32(1e-3))
+    t0 = time.perf_counter()
+    _, ctx = oracle.linear_fwd(x, w)
+    oracle.linear_bwd(dy, ctx, 0, 0)
+    dt = time.perf_counter() - t0
+    return dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s")
+
+
+def quant_sweep(q, torch, synth):
+    out = []
+    for idx, (r, c) in enumerate(synth.QUANT_SWEEP):
+        x = synth.device_quant_sweep_matrix(idx)
+        xs = [x] + [x.clone() for _ in range(2)]   # rotate buffers: every pass streams from HBM, not cache
+        codes = [torch.empty((r, c // 2), dtype=torch.uint8, device=x.device) for _ in xs]
+        scales = [torch.empty((r, c // 32), dtype=torch.uint8, device=x.device) for _ in xs]
+        mask = [torch.empty((r, c // 32), dtype=torch.int32, device=x.device) for _ in xs]
+        cases = [("fwd_rtn_row", 2.65625, lambda j: q.quartet_quant_fwd(xs[j], r, c, c, 0, codes[j], scales[j], mask[j])),
+                 ("bwd_sr_row", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], r, c, c, 0, 0x1234ABCD, 7, 0, 0, codes[j], scales[j])),
+                 ("bwd_rtn_row", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], r, c, c, 0, 0x1234ABCD, 7, 0, 1, codes[j], scales[j])),
+                 ("bwd_sr_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 0, codes[j], scales[j])),
+                 ("bwd_rtn_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 1, codes[j], scales[j]))]
+        for name, bpe, fn in cases:
+            for j in range(3):
+                q.check(fn(j))
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 12
+            e0.record()
+            for it in range(reps):
+                q.check(fn(it % 3))
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            gbs = bpe * r * c / ms / 1e6
+            out.append(dict(shape=[r, c], mode=name, ms=round(ms, 4), GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
+        del xs, codes, scales, mask
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    from paper_2505_14669_amd import binding as q
+    from paper_2505_14669_amd import synth
+
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    layers = [Layer(q, torch, synth.device_layer(args.config, li)) for li in range(len(cfg["layers"]))]
+    ws_bytes = max(l.ws_bytes for l in layers)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+    flops_step = sum(l.flops for l in layers)
+    launches_per_step = 11 * len(layers)
+
+    def one_step(step):
+        for l in layers:
+            l.step(q, ws, step, args.rounding)
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+
+    q.check(q.quartet_profile_enable(launches_per_step * args.steps))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(1000 + s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    cap = launches_per_step * args.steps
+    kinds = (ctypes.c_int * cap)()
+    ms = (ctypes.c_float * cap)()
+    n = q.quartet_profile_read(kinds, ms, cap)
+    if n < 0:
+        q.check(n)
+    q.quartet_profile_enable(0)
+    per_kind = {}
+    for kk, m in zip(kinds[:n], ms[:n]):
+        per_kind.setdefault(q.KIND_NAMES[kk], []).append(m)
+    gemm_ms = per_kind.get("gemm", [])
+    gemm_flops_step = flops_step               # three GEMMs of 2*T*I*O each = 6*T*I*O
+    gemm_total_ms = sum(gemm_ms)
+    achieved = gemm_flops_step * args.steps / (gemm_total_ms * 1e-3) / 1e12 if gemm_total_ms > 0 else 0.0
+
+    ms_per_step = dt * 1e3 / args.steps
+    result = {
+        "metric": "Quartet linear fwd+bwd TFLOP/s at 1 GPU",
+        "value": round(flops_step / (ms_per_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (E2M1 x E8M0/32) operands, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg['name']}, {len(layers)} linear layers fwd+bwd, "
+                               f"backward rounding {'stochastic' if args.rounding == 0 else 'nearest'}",
+                   "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_kernel (all three GEMMs of every layer)",
+                     "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_FP4_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms)},
+        "kernel_time_share": {k: round(sum(v) / (dt * 1e3), 4) for k, v in sorted(per_kind.items())},
+    }
+    if args.breakdown:
+        for k, v in sorted(per_kind.items()):
+            print(f"  {k:10s} launches {len(v):4d} total {sum(v):9.3f} ms  ({sum(v) / (dt * 1e3) * 100:5.1f} % of wall)",
+                  file=sys.stderr)
+    if args.quant_sweep:
+        del layers, ws
+        torch.cuda.empty_cache()
+        result["quantizer_sweep"] = quant_sweep(q, torch, synth)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -55,6 +55,24 @@ int quartet_last_hip_error(void);
 int quartet_sr_bits(void);
 
 /*
+ * Launch profiling (measurement support; the paper reports a per-stage runtime breakdown in its
+ * appendix "Performance breakdown").  quartet_profile_enable(n > 0) makes the library bracket each
+ * of its next kernel launches, up to n, with a pair of hipEvents recorded on the caller's stream;
+ * n = 0 disables it and frees the events.  quartet_profile_read() waits for the recorded launches,
+ * writes kind (QUARTET_KIND_*) and duration in milliseconds of each, in launch order, returns how
+ * many it wrote (or a negative error) and restarts the record.  The record is process-global:
+ * use it from one thread, with profiling calls and launches on the same device.
+ */
+#define QUARTET_KIND_QUANT_FWD 0
+#define QUARTET_KIND_QUANT_BWD 1
+#define QUARTET_KIND_REQUANT 2
+#define QUARTET_KIND_GEMM 3
+#define QUARTET_KIND_EPILOGUE 4
+#define QUARTET_KIND_DEQUANT 5
+int quartet_profile_enable(int max_records);
+int quartet_profile_read(int *kinds, float *ms, int capacity);
+
+/*
  * Forward quantizer (Algorithm 1 Forward, lines H_g then QuEST; Section 4.4 "Stage 1").
  * Logical input A[rows x k]:  transpose = 0: A = x, stored [rows x ldx];
  *                             transpose = 1: A = x^T, x stored [k x ldx] (ldx >= rows).

@@ -44,6 +44,40 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
     return QUARTET_OK;
 }
 
+// ---- optional launch profiling: a pair of events around every kernel launch of the library
+struct ProfileState {
+    bool enabled = false;
+    int capacity = 0, count = 0;
+    hipEvent_t* start = nullptr;
+    hipEvent_t* stop = nullptr;
+    int* kind = nullptr;
+};
+ProfileState g_prof;
+
+struct ProfileScope {
+    int slot = -1;
+    hipStream_t st;
+    ProfileScope(int kind, hipStream_t s) : st(s) {
+        if (g_prof.enabled && g_prof.count < g_prof.capacity) {
+            slot = g_prof.count++;
+            g_prof.kind[slot] = kind;
+            (void)hipEventRecord(g_prof.start[slot], st);
+        }
+    }
+    ~ProfileScope() {
+        if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], st);
+    }
+};
+
+void profile_free() {
+    for (int i = 0; i < g_prof.capacity; ++i) {
+        (void)hipEventDestroy(g_prof.start[i]);
+        (void)hipEventDestroy(g_prof.stop[i]);
+    }
+    delete[] g_prof.start; delete[] g_prof.stop; delete[] g_prof.kind;
+    g_prof = ProfileState();
+}
+
 size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
 
 struct BwdWorkspace {
@@ -75,6 +109,40 @@ int quartet_last_hip_error(void) { return g_last_hip_error; }
 
 int quartet_sr_bits(void) { return 16; }
 
+int quartet_profile_enable(int max_records) {
+    profile_free();
+    if (max_records < 0) return QUARTET_EINVAL;
+    if (max_records == 0) return QUARTET_OK;
+    g_prof.start = new hipEvent_t[max_records];
+    g_prof.stop = new hipEvent_t[max_records];
+    g_prof.kind = new int[max_records];
+    for (int i = 0; i < max_records; ++i) {
+        hipError_t e = hipEventCreate(&g_prof.start[i]);
+        if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
+        if (e != hipSuccess) {
+            g_prof.capacity = i;
+            profile_free();
+            return hip_fail(e);
+        }
+        g_prof.capacity = i + 1;
+    }
+    g_prof.enabled = true;
+    return QUARTET_OK;
+}
+
+int quartet_profile_read(int* kinds, float* ms, int capacity) {
+    if (capacity < 0 || (capacity > 0 && (!kinds || !ms))) return QUARTET_EINVAL;
+    int n = g_prof.count < capacity ? g_prof.count : capacity;
+    for (int i = 0; i < n; ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.stop[i]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms[i], g_prof.start[i], g_prof.stop[i]);
+        if (e != hipSuccess) return hip_fail(e);
+        kinds[i] = g_prof.kind[i];
+    }
+    g_prof.count = 0;
+    return n;
+}
+
 uint32_t quartet_sign_word(uint64_t seed) {
     const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
     const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
@@ -90,6 +158,7 @@ int quartet_quant_fwd(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, 
     int rc = check_quant_shape(rows, k, ldx, transpose);
     if (rc) return rc;
     SrParams p = {0u, 0u, 0u, 0u};
+    ProfileScope prof(QUARTET_KIND_QUANT_FWD, (hipStream_t)stream);
     hipError_t e = quartet::launch_quant(quartet::kFwd, x_bf16, rows, k, ldx, transpose, p, codes, scales,
                                          mask, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
@@ -105,6 +174,7 @@ int quartet_quant_bwd_sr(const void* x_bf16, int64_t rows, int64_t k, int64_t ld
     if (rc) return rc;
     SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+    ProfileScope prof(QUARTET_KIND_QUANT_BWD, (hipStream_t)stream);
     hipError_t e = quartet::launch_quant(mode, x_bf16, rows, k, ldx, transpose, p, codes, scales, nullptr,
                                          (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
@@ -122,6 +192,7 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
     if (rc) return rc;
     SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+    ProfileScope prof(QUARTET_KIND_REQUANT, (hipStream_t)stream);
     hipError_t e = quartet::launch_requant_transpose(mode, src_codes, src_scales, rows, k, p, codes, scales,
                                                      (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
@@ -137,6 +208,7 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     if (d_dtype != QUARTET_DTYPE_F32 && d_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
     if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;
     if (m / 128 > 65534) return QUARTET_ENOTSUP;
+    ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
     hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
                                         d_dtype == QUARTET_DTYPE_BF16, ldd, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
@@ -150,6 +222,7 @@ int quartet_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64
     if (out_dtype != QUARTET_DTYPE_F32 && out_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
     if (out_dtype == QUARTET_DTYPE_BF16 && out == (const void*)g) return QUARTET_EINVAL;
     if (m > 0 && (n / 32) >= kMaxGroups / m) return QUARTET_ENOTSUP;
+    ProfileScope prof(QUARTET_KIND_EPILOGUE, (hipStream_t)stream);
     hipError_t e = quartet::launch_grad_epilogue(g, mask, m, n, scale, out, out_dtype == QUARTET_DTYPE_BF16,
                                                  (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
@@ -160,6 +233,7 @@ int quartet_mxfp4_dequant(const uint8_t* codes, const uint8_t* scales, int64_t r
     if (!codes || !scales || !out) return QUARTET_EINVAL;
     if (!aligned16(codes) || !aligned16(out)) return QUARTET_EINVAL;
     if (rows < 0 || k < 0 || (k % 32) != 0) return QUARTET_EINVAL;
+    ProfileScope prof(QUARTET_KIND_DEQUANT, (hipStream_t)stream);
     hipError_t e = quartet::launch_dequant(codes, scales, rows, k, out, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }

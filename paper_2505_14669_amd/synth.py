@@ -108,3 +108,52 @@ def small_matrix(seed, rows, cols, kind="normal", scale=1.0):
     if kind == "tiny":
         x *= np.float32(2.0 ** -40)
     return f32_to_bf16(x * np.float32(scale))
+
+
+# ------------------------------------------------------------------ device-side generation
+# The same recipes drawn with torch's seeded generator on the GPU, for full-size benchmark tensors
+# (hundreds of MiB each) that would take tens of seconds to draw on the host.  Different bytes than
+# the numpy versions above, same shapes and distributions.
+
+def _torch_gen(device, config, tensor_id, layer):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(1000 * config + tensor_id + 10 * layer)
+    return g
+
+
+def device_layer(config, layer, device="cuda:0"):
+    """bf16 torch tensors X [T,I], W [O,I], dY [T,O] of one layer of configuration 1..4."""
+    import torch
+    name, t, i, o = CONFIGS[config]["layers"][layer]
+    g = _torch_gen(device, config, 0, layer)
+    if config == 1:
+        x = torch.randn((t, i), generator=g, device=device)
+        cols = torch.randperm(i, generator=g, device=device)[: -(-i // 100)]
+        x[:, cols] *= 20.0
+    else:
+        # Student-t(3) = N(0,1) / sqrt(chi2(3)/3)
+        z = torch.randn((t, i), generator=g, device=device)
+        chi = torch.zeros((t, i), device=device)
+        for _ in range(3):
+            chi += torch.randn((t, i), generator=g, device=device) ** 2
+        x = z / torch.sqrt(chi / 3.0)
+        del z, chi
+        x /= torch.sqrt(torch.mean(x * x, dim=1, keepdim=True))
+        if config >= 3:
+            x *= torch.exp(torch.randn((i,), generator=g, device=device))[None, :]
+    w = torch.randn((o, i), generator=_torch_gen(device, config, 1, layer), device=device) * 0.02
+    dy = torch.randn((t, o), generator=_torch_gen(device, config, 2, layer), device=device) * 1e-3
+    return dict(name=name, tokens=t, in_features=i, out_features=o,
+                x=x.to(torch.bfloat16).contiguous(), w=w.to(torch.bfloat16).contiguous(),
+                dy=dy.to(torch.bfloat16).contiguous())
+
+
+def device_quant_sweep_matrix(index, device="cuda:0"):
+    import torch
+    r, c = QUANT_SWEEP[index]
+    g = _torch_gen(device, 5, 0, index)
+    x = torch.randn((r, c), generator=g, device=device)
+    hit = torch.rand((r, c), generator=g, device=device) < 0.001
+    x = torch.where(hit, x * 50.0, x)
+    return x.to(torch.bfloat16).contiguous()
