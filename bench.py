@@ -44,9 +44,11 @@ class Layer:
         f32 = dict(dtype=torch.float32, device=dev)
         self.x, self.w, self.dy = L["x"], L["w"], L["dy"]
         self.y = torch.empty((t, o), **f32)
-        self.xq_codes, self.xq_scales, self.x_mask = (torch.empty((t, i // 2), **u8), torch.empty((t, i // 32), **u8),
+        self.xq_codes, self.xq_scales, self.x_mask = (torch.empty((t, i // 2), **u8),
+                                                      torch.empty((q.quartet_scale_bytes(t, i),), **u8),
                                                       torch.empty((t, i // 32), **i32))
-        self.wq_codes, self.wq_scales, self.w_mask = (torch.empty((o, i // 2), **u8), torch.empty((o, i // 32), **u8),
+        self.wq_codes, self.wq_scales, self.w_mask = (torch.empty((o, i // 2), **u8),
+                                                      torch.empty((q.quartet_scale_bytes(o, i),), **u8),
                                                       torch.empty((o, i // 32), **i32))
         self.dx = torch.empty((t, i), **f32)
         self.dw = torch.empty((o, i), **f32)
@@ -89,7 +91,7 @@ def quant_sweep(q, torch, synth):
         x = synth.device_quant_sweep_matrix(idx)
         xs = [x] + [x.clone() for _ in range(2)]   # rotate buffers: every pass streams from HBM, not cache
         codes = [torch.empty((r, c // 2), dtype=torch.uint8, device=x.device) for _ in xs]
-        scales = [torch.empty((r, c // 32), dtype=torch.uint8, device=x.device) for _ in xs]
+        scales = [torch.empty((max(q.quartet_scale_bytes(r, c), q.quartet_scale_bytes(c, r)),), dtype=torch.uint8, device=x.device) for _ in xs]
         mask = [torch.empty((r, c // 32), dtype=torch.int32, device=x.device) for _ in xs]
         cases = [("fwd_rtn_row", 2.65625, lambda j: q.quartet_quant_fwd(xs[j], r, c, c, 0, codes[j], scales[j], mask[j])),
                  ("bwd_sr_row", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], r, c, c, 0, 0x1234ABCD, 7, 0, 0, codes[j], scales[j])),

@@ -17,8 +17,16 @@
  *  - MXFP4 tensor [rows x k] (k % 32 == 0):
  *      codes  uint8 [rows x k/2] : E2M1 element 2j in bits 3:0 of byte j, element 2j+1 in bits 7:4;
  *                                  code = s e1 e0 m, magnitudes {0,.5,1,1.5,2,3,4,6}, bit 3 = sign;
- *      scales uint8 [rows x k/32]: E8M0, value 2^(b-127), one per 32 consecutive elements of a row;
- *      mask   uint32 [rows x k/32]: bit i of word j is 1 iff element 32j+i was NOT clipped.
+ *      scales uint8, E8M0, value 2^(b-127), one per group of 32 consecutive elements of a row,
+ *             stored TILED so that they are already in matrix-core lane order (on CDNA4 a scale is
+ *             a per-lane register byte, so the scale-rearrangement pass of the paper's Section 4.4
+ *             is folded into this layout): tiles of 32 rows x 8 groups, 256 bytes each, ordered
+ *             [row/32][group/8]; the scale of (row, group g) is byte
+ *               ((row/32) * ceil(k/256) + g/8) * 256 + ((g%2)*32 + row%32) * 4 + (g%8)/2.
+ *             The buffer holds quartet_scale_bytes(rows, k) = ceil(rows/32) * ceil(k/256) * 256
+ *             bytes, 4-byte aligned; bytes of rows >= rows or groups >= k/32 are never written
+ *             and never used.
+ *      mask   uint32 [rows x k/32] row-major: bit i of word j is 1 iff element 32j+i was NOT clipped.
  *  - Return value: QUARTET_OK, or a negative error.  Arguments are validated on the host before
  *    anything is launched; on QUARTET_EINVAL / QUARTET_ENOTSUP nothing has been enqueued.
  *    QUARTET_EHIP: a HIP call failed; quartet_last_hip_error() returns its hipError_t.
@@ -54,6 +62,9 @@ int quartet_last_hip_error(void);
 /* Number of random bits each element consumes in stochastic rounding (16). */
 int quartet_sr_bits(void);
 
+/* Size in bytes of the tiled scale buffer of an MXFP4 tensor [rows x k] (0 if an argument is negative). */
+size_t quartet_scale_bytes(int64_t rows, int64_t k);
+
 /*
  * Launch profiling (measurement support; the paper reports a per-stage runtime breakdown in its
  * appendix "Performance breakdown").  quartet_profile_enable(n > 0) makes the library bracket each
@@ -81,7 +92,8 @@ int quartet_profile_read(int *kinds, float *ms, int capacity);
  * scale 2^e with e = floor((floor(log2 ss) - 6) / 2)  (= 2^floor(log2(RMS/sqrt 2)), the RMS-based
  * clipping of QuEST snapped to a power of two); code_i = round-to-nearest-even E2M1 of h_i 2^-e,
  * saturating at +-6; mask bit i = (|h_i 2^-e| <= 6).
- * Outputs: codes [rows x k/2], scales [rows x k/32], mask [rows x k/32] (mask may be NULL).
+ * Outputs: codes [rows x k/2], scales (tiled, quartet_scale_bytes(rows, k)), mask [rows x k/32]
+ * (mask may be NULL).
  * Requires k % 32 == 0; transpose = 1 also rows % 8 == 0.  rows*k/32 must be below 2^31.
  */
 int quartet_quant_fwd(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
@@ -110,7 +122,7 @@ int quartet_quant_bwd_sr(const void *x_bf16, int64_t rows, int64_t k, int64_t ld
 /*
  * Re-quantization of a saved MXFP4 tensor along its other dimension (Algorithm 1 Backward:
  * H^_g(W_q^T, xi), H^_g(X_q^T, xi) and their rounding).  src is an MXFP4 tensor stored [k x rows]
- * (codes [k x rows/2], scales [k x rows/32], groups along `rows`).  The output is
+ * (codes [k x rows/2], tiled scales of a [k x rows] tensor, groups along `rows`).  The output is
  * quartet_quant_bwd_sr applied to decode(src)^T, a [rows x k] matrix with groups along k
  * (decoding is exact, so this step adds no rounding of its own).  rows % 32 == 0 and k % 32 == 0.
  */
@@ -122,9 +134,9 @@ int quartet_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_sc
 /*
  * GEMM_LP (Section 4.4 "Stage 2": D = (A x SFA)(B x SFB), scales along K, one per 32):
  *   D[m x n] = alpha * sum_k dec(A)[m,k] * dec(B)[n,k]
- * A = (a_codes [m x k/2], a_scales [m x k/32]), B = (b_codes [n x k/2], b_scales [n x k/32]), both
- * K-contiguous.  Products are exact, accumulation is fp32 on the matrix cores.  d is fp32 or bf16
- * (d_dtype), row-major with leading dimension ldd >= n.  k % 32 == 0; m, n arbitrary.
+ * A = (a_codes [m x k/2], a_scales tiled for [m x k]), B = (b_codes [n x k/2], b_scales tiled for
+ * [n x k]), both K-contiguous.  Products are exact, accumulation is fp32 on the matrix cores.  d is fp32 or bf16
+ * (d_dtype), row-major with leading dimension ldd >= n.  k % 32 == 0, k <= 2^23; m, n arbitrary.
  */
 int quartet_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
                        const uint8_t *b_codes, const uint8_t *b_scales,

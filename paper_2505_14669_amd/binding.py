@@ -23,7 +23,7 @@ QUARTET_ROUND_NEAREST = 1
 
 EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
-    "quartet_profile_enable", "quartet_profile_read",
+    "quartet_profile_enable", "quartet_profile_read", "quartet_scale_bytes",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr",
     "quartet_mxfp4_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
@@ -41,6 +41,8 @@ _lib.quartet_last_hip_error.restype = _int
 _lib.quartet_sr_bits.restype = _int
 _lib.quartet_profile_enable.argtypes = [_int]
 _lib.quartet_profile_read.argtypes = [_p, _p, _int]
+_lib.quartet_scale_bytes.restype = ctypes.c_size_t
+_lib.quartet_scale_bytes.argtypes = [_i64, _i64]
 _lib.quartet_sign_word.restype = _u32
 _lib.quartet_sign_word.argtypes = [_u64]
 _lib.quartet_quant_fwd.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p]
@@ -110,6 +112,10 @@ def quartet_profile_enable(max_records):
 def quartet_profile_read(kinds, ms, capacity):
     """kinds: ctypes int array, ms: ctypes float array, both of length >= capacity."""
     return _lib.quartet_profile_read(ctypes.cast(kinds, _p), ctypes.cast(ms, _p), capacity)
+
+
+def quartet_scale_bytes(rows, k):
+    return _lib.quartet_scale_bytes(rows, k)
 
 
 def quartet_sign_word(seed):

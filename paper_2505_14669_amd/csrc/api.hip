@@ -80,6 +80,10 @@ void profile_free() {
 
 size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
 
+size_t scale_bytes(int64_t rows, int64_t k) {
+    return (size_t)((rows + 31) / 32) * (size_t)((k + 255) / 256) * 256u;
+}
+
 struct BwdWorkspace {
     size_t g_codes, g_scales, b_codes, b_scales, acc, total;
 };
@@ -89,11 +93,13 @@ BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
     size_t to = (size_t)tokens * (size_t)out;
     size_t bmax = (size_t)in * (size_t)(out > tokens ? out : tokens);
     size_t amax = (size_t)in * (size_t)(tokens > out ? tokens : out);
+    size_t gs = scale_bytes(tokens, out), gts = scale_bytes(out, tokens);
+    size_t bs = scale_bytes(in, out), bts = scale_bytes(in, tokens);
     size_t off = 0;
     w.g_codes = off; off += align256(to / 2);
-    w.g_scales = off; off += align256(to / 32);
+    w.g_scales = off; off += align256(gs > gts ? gs : gts);
     w.b_codes = off; off += align256(bmax / 2);
-    w.b_scales = off; off += align256(bmax / 32);
+    w.b_scales = off; off += align256(bs > bts ? bs : bts);
     w.acc = off; off += align256(amax * 4);
     w.total = off;
     return w;
@@ -108,6 +114,11 @@ extern "C" {
 int quartet_last_hip_error(void) { return g_last_hip_error; }
 
 int quartet_sr_bits(void) { return 16; }
+
+size_t quartet_scale_bytes(int64_t rows, int64_t k) {
+    if (rows < 0 || k < 0) return 0;
+    return scale_bytes(rows, k);
+}
 
 int quartet_profile_enable(int max_records) {
     profile_free();
@@ -155,6 +166,7 @@ int quartet_quant_fwd(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, 
                       uint8_t* codes, uint8_t* scales, uint32_t* mask, void* stream) {
     if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
     if (!aligned16(x_bf16) || !aligned16(codes) || (mask && !aligned16(mask))) return QUARTET_EINVAL;
+    if (reinterpret_cast<uintptr_t>(scales) & 3u) return QUARTET_EINVAL;
     int rc = check_quant_shape(rows, k, ldx, transpose);
     if (rc) return rc;
     SrParams p = {0u, 0u, 0u, 0u};
@@ -168,7 +180,7 @@ int quartet_quant_bwd_sr(const void* x_bf16, int64_t rows, int64_t k, int64_t ld
                          uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
                          uint8_t* codes, uint8_t* scales, void* stream) {
     if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
-    if (!aligned16(x_bf16) || !aligned16(codes)) return QUARTET_EINVAL;
+    if (!aligned16(x_bf16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     int rc = check_quant_shape(rows, k, ldx, transpose);
     if (rc) return rc;
@@ -185,7 +197,7 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
                                  uint32_t stream_id, int rounding,
                                  uint8_t* codes, uint8_t* scales, void* stream) {
     if (!src_codes || !src_scales || !codes || !scales) return QUARTET_EINVAL;
-    if (!aligned16(src_codes) || !aligned16(codes)) return QUARTET_EINVAL;
+    if (!aligned16(src_codes) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     if (rows < 0 || (rows % 32) != 0) return QUARTET_EINVAL;
     int rc = check_quant_shape(rows, k, (rows + 7) / 8 * 8, 1);
@@ -206,8 +218,9 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     if (!aligned16(a_codes) || !aligned16(b_codes) || !aligned16(d)) return QUARTET_EINVAL;
     if (m < 0 || n < 0 || k < 0 || (k % 32) != 0 || ldd < n) return QUARTET_EINVAL;
     if (d_dtype != QUARTET_DTYPE_F32 && d_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
-    if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;
-    if (m / 128 > 65534) return QUARTET_ENOTSUP;
+    if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k > ((int64_t)1 << 23)) return QUARTET_ENOTSUP;
+    if (((m + 127) / 128) * ((n + 127) / 128) >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;
+    if ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(b_scales)) & 3u) return QUARTET_EINVAL;
     ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
     hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
                                         d_dtype == QUARTET_DTYPE_BF16, ldd, (hipStream_t)stream);

@@ -16,6 +16,20 @@ constexpr float kInvSqrt32 = 0.17677669529663687f;  // fl(1/sqrt 32) = 0x3E3504F
 
 enum QuantMode { kFwd = 0, kBwdRtn = 1, kBwdSr = 2 };
 
+// Byte offset of the E8M0 scale of (row, group g = k/32) in the tiled scale layout: tiles of
+// 32 rows x 8 groups (256 K-elements), 256 bytes each, ordered [row block][K-quad]; inside a tile
+// byte ((g&1)*32 + row%32)*4 + (g%8)/2.  Lane l of a wave that owns a 32-row block of an MFMA
+// operand therefore finds its four K=64-step scales in dword l of the tile.  kq = ceil(k/256).
+__host__ __device__ __forceinline__ uint64_t scale_tile_offset(uint32_t row, uint32_t g, uint32_t kq) {
+    return ((uint64_t)(row >> 5) * kq + (g >> 3)) * 256u + (((g & 1u) << 5) + (row & 31u)) * 4u + ((g & 7u) >> 1);
+}
+
+// n / d for n < 2^31 by multiply-high with a host-computed magic number (Granlund-Montgomery).
+struct FastDiv {
+    uint32_t mul, shift;
+};
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f) { return (__umulhi(n, f.mul) + n) >> f.shift; }
+
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 

@@ -104,8 +104,9 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
 // x is a flat array of n_groups groups (rows*k/32, ldx == k).  Block = 4 waves, a wave per 64 groups.
 template <int MODE, bool MASK>
 __global__ void __launch_bounds__(256)
-quant_row_flat_kernel(const uint4* __restrict__ x, uint32_t n_groups, uint4* __restrict__ codes,
-                      uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
+quant_row_flat_kernel(const uint4* __restrict__ x, uint32_t n_groups, uint32_t gk, FastDiv div_gk,
+                      uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
+                      SrParams p) {
     __shared__ uint4 stage[4][256];
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t base_group = (blockIdx.x * 4u + wave) * 64u;
@@ -131,8 +132,9 @@ quant_row_flat_kernel(const uint4* __restrict__ x, uint32_t n_groups, uint4* __r
     uint32_t sb, mw;
     quantize_group<MODE>(v, p, (uint64_t)g * 4u, out, sb, mw);
     if (g < n_groups) {
+        const uint32_t row = fast_div(g, div_gk), gi = g - row * gk;
         codes[g] = out;
-        scales[g] = (uint8_t)sb;
+        scales[scale_tile_offset(row, gi, (gk + 7u) >> 3)] = (uint8_t)sb;
         if (MASK) mask[g] = mw;
     }
 }
@@ -155,7 +157,7 @@ quant_row_strided_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t
         uint32_t sb, mw;
         quantize_group<MODE>(v, p, gi * 4u, out, sb, mw);
         codes[gi] = out;
-        scales[gi] = (uint8_t)sb;
+        scales[scale_tile_offset(row, g, (gk + 7u) >> 3)] = (uint8_t)sb;
         if (MASK) mask[gi] = mw;
     }
 }
@@ -197,14 +199,14 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
             }
         } else {
             const uint8_t* sc = static_cast<const uint8_t*>(src);
-            const uint32_t half = rows >> 1, sgk = rows >> 5;
+            const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;   // the source's own K-quads
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 uint32_t byte = 0u, sb = 127u;
                 if (ok) {
-                    size_t r = (size_t)(grp * 32u + i);
-                    byte = sc[r * half + (col >> 1)];
-                    sb = src_scales[r * sgk + (col >> 5)];
+                    uint32_t r = grp * 32u + i;
+                    byte = sc[(size_t)r * half + (col >> 1)];
+                    sb = src_scales[scale_tile_offset(r, col >> 5, skq)];
                 }
                 v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, u2f(sb << 23), 0);
                 v0[i] = d[0];
@@ -239,28 +241,48 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
             *reinterpret_cast<uint4*>(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u) = q;
         }
     }
+    if (MASK) {
 #pragma unroll
-    for (uint32_t j = 0; j < 4; ++j) {
-        uint32_t id = threadIdx.x + 256u * j;
-        uint32_t lc = id >> 3, part = id & 7u;
-        uint32_t r = col0 + lc, grp = grp0 + part;
-        if (r < rows && grp < gk) {
-            scales[(size_t)r * gk + grp] = s_scales[lc * 8u + part];
-            if (MASK) mask[(size_t)r * gk + grp] = s_mask[lc * 8u + part];
+        for (uint32_t j = 0; j < 4; ++j) {
+            uint32_t id = threadIdx.x + 256u * j;
+            uint32_t lc = id >> 3, part = id & 7u;
+            uint32_t r = col0 + lc, grp = grp0 + part;
+            if (r < rows && grp < gk) mask[(size_t)r * gk + grp] = s_mask[lc * 8u + part];
+        }
+    }
+    // scales: the block's 8 groups are one K-quad, so each 32-row block of the tile is one 256-byte
+    // scale tile; thread t writes dword t%64 of tile t/64 (bytes = groups h, 2+h, 4+h, 6+h of its row)
+    {
+        const uint32_t t = threadIdx.x, lc = (t >> 6) * 32u + (t & 31u), h = (t >> 5) & 1u;
+        const uint32_t r = col0 + lc;
+        if (r < rows) {
+            uint32_t w = 0u;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) w |= (uint32_t)s_scales[lc * 8u + 2u * q + h] << (8u * q);
+            const uint32_t kq = (gk + 7u) >> 3;
+            uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(r, grp0 + h, kq));
+            if (grp0 + 6u + h < gk) {
+                *dst = w;
+            } else {
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q)
+                    if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
+            }
         }
     }
 }
 
 // ------------------------------------------------------------------ MXFP4 -> fp32
 __global__ void __launch_bounds__(256)
-dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, uint64_t n_groups,
-               float* __restrict__ out) {
-    uint64_t g = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, uint32_t n_groups,
+               uint32_t gk, FastDiv div_gk, float* __restrict__ out) {
+    uint32_t g = blockIdx.x * 256u + threadIdx.x;
     if (g >= n_groups) return;
     uint4 q = reinterpret_cast<const uint4*>(codes)[g];
-    float s = u2f((uint32_t)scales[g] << 23);
+    const uint32_t row = fast_div(g, div_gk), gi = g - row * gk;
+    float s = u2f((uint32_t)scales[scale_tile_offset(row, gi, (gk + 7u) >> 3)] << 23);
     uint32_t w[4] = {q.x, q.y, q.z, q.w};
-    float4* dst = reinterpret_cast<float4*>(out + g * 32u);
+    float4* dst = reinterpret_cast<float4*>(out + (size_t)g * 32u);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], s, 0);
@@ -274,6 +296,13 @@ dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sc
 
 // ------------------------------------------------------------------ host-side launchers
 
+static FastDiv make_fast_div(uint32_t d) {
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    uint64_t mul = ((((uint64_t)1 << l) - d) << 32) / d + 1;
+    return FastDiv{(uint32_t)mul, l};
+}
+
 template <int MODE>
 static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
                              uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
@@ -284,10 +313,12 @@ static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx
         dim3 grid((tiles + 3) / 4), block(256);
         if (mask)
             hipLaunchKernelGGL((quant_row_flat_kernel<MODE, true>), grid, block, 0, st, (const uint4*)x,
-                               (uint32_t)n_groups, (uint4*)codes, scales, mask, p);
+                               (uint32_t)n_groups, (uint32_t)(k / 32), make_fast_div((uint32_t)(k / 32)),
+                               (uint4*)codes, scales, mask, p);
         else
             hipLaunchKernelGGL((quant_row_flat_kernel<MODE, false>), grid, block, 0, st, (const uint4*)x,
-                               (uint32_t)n_groups, (uint4*)codes, scales, mask, p);
+                               (uint32_t)n_groups, (uint32_t)(k / 32), make_fast_div((uint32_t)(k / 32)),
+                               (uint4*)codes, scales, mask, p);
     } else {
         uint32_t gk = (uint32_t)(k / 32);
         dim3 grid((gk + 255) / 256, (uint32_t)(rows < 65535 ? rows : 65535)), block(256);
@@ -345,7 +376,8 @@ hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t r
     uint64_t n_groups = (uint64_t)rows * (uint64_t)(k / 32);
     if (n_groups == 0) return hipSuccess;
     dim3 grid((uint32_t)((n_groups + 255) / 256)), block(256);
-    hipLaunchKernelGGL(dequant_kernel, grid, block, 0, st, codes, scales, n_groups, out);
+    hipLaunchKernelGGL(dequant_kernel, grid, block, 0, st, codes, scales, (uint32_t)n_groups, (uint32_t)(k / 32),
+                       make_fast_div((uint32_t)(k / 32)), out);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@ import numpy as np
 import torch
 
 from paper_2505_14669_amd import binding as q
+from indep import scales_from_tiled, scales_to_tiled
 
 DEV = "cuda:0"
 
@@ -35,10 +36,10 @@ def quant_fwd(x_u16, transpose=False, want_mask=True, ldx=None):
     ld = x_u16.shape[1] if ldx is None else ldx
     rows, k = (x_u16.shape[1], x_u16.shape[0]) if transpose else x_u16.shape
     codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
-    scales = dev_empty((rows, k // 32), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
     mask = dev_empty((rows, k // 32), np.uint32, 0x5A5A5A5A) if want_mask else None
     q.check(q.quartet_quant_fwd(x, rows, k, ld, transpose, codes, scales, mask))
-    return (to_host(codes, np.uint8), to_host(scales, np.uint8),
+    return (to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k),
             to_host(mask, np.uint32) if want_mask else None)
 
 
@@ -46,25 +47,25 @@ def quant_bwd_sr(x_u16, sign_word, seed, stream_id, rounding=0, transpose=False)
     x = to_dev(x_u16)
     rows, k = (x_u16.shape[1], x_u16.shape[0]) if transpose else x_u16.shape
     codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
-    scales = dev_empty((rows, k // 32), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
     q.check(q.quartet_quant_bwd_sr(x, rows, k, x_u16.shape[1], transpose, sign_word, seed, stream_id,
                                    rounding, codes, scales))
-    return to_host(codes, np.uint8), to_host(scales, np.uint8)
+    return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
 
 
 def requant_transpose_sr(src_codes, src_scales, sign_word, seed, stream_id, rounding=0):
     k, rows = src_codes.shape[0], src_codes.shape[1] * 2
-    sc, ss = to_dev(src_codes), to_dev(src_scales)
+    sc, ss = to_dev(src_codes), to_dev(scales_to_tiled(src_scales))
     codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
-    scales = dev_empty((rows, k // 32), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
     q.check(q.quartet_requant_transpose_sr(sc, ss, rows, k, sign_word, seed, stream_id, rounding, codes, scales))
-    return to_host(codes, np.uint8), to_host(scales, np.uint8)
+    return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
 
 
 def dequant(codes, scales):
     rows, k = codes.shape[0], codes.shape[1] * 2
     out = dev_empty((rows, k), np.float32, float("nan"))
-    q.check(q.quartet_mxfp4_dequant(to_dev(codes), to_dev(scales), rows, k, out))
+    q.check(q.quartet_mxfp4_dequant(to_dev(codes), to_dev(scales_to_tiled(scales)), rows, k, out))
     return to_host(out, np.float32)
 
 
@@ -76,7 +77,8 @@ def gemm(a_codes, a_scales, b_codes, b_scales, alpha=1.0, bf16=False, ldd=None):
         d = dev_empty((m, ldd), np.uint16, 0x7FC0)
     else:
         d = dev_empty((m, ldd), np.float32, float("nan"))
-    q.check(q.quartet_mxfp4_gemm(to_dev(a_codes), to_dev(a_scales), to_dev(b_codes), to_dev(b_scales), m, n, k,
+    q.check(q.quartet_mxfp4_gemm(to_dev(a_codes), to_dev(scales_to_tiled(a_scales)), to_dev(b_codes),
+                                 to_dev(scales_to_tiled(b_scales)), m, n, k,
                                  alpha, d, q.QUARTET_DTYPE_BF16 if bf16 else q.QUARTET_DTYPE_F32, ldd))
     return to_host(d, np.uint16 if bf16 else np.float32)
 
@@ -105,9 +107,11 @@ class Linear:
         t, i, o = self.t, self.i, self.o
         self.x, self.w = to_dev(x_u16), to_dev(w_u16)
         self.y = dev_empty((t, o), np.float32, float("nan"))
-        self.xq_codes, self.xq_scales = dev_empty((t, i // 2), np.uint8, 0), dev_empty((t, i // 32), np.uint8, 0)
+        self.xq_codes = dev_empty((t, i // 2), np.uint8, 0)
+        self.xq_scales = dev_empty((max(q.quartet_scale_bytes(t, i), 4),), np.uint8, 0xFF)
         self.x_mask = dev_empty((t, i // 32), np.uint32, 0)
-        self.wq_codes, self.wq_scales = dev_empty((o, i // 2), np.uint8, 0), dev_empty((o, i // 32), np.uint8, 0)
+        self.wq_codes = dev_empty((o, i // 2), np.uint8, 0)
+        self.wq_scales = dev_empty((max(q.quartet_scale_bytes(o, i), 4),), np.uint8, 0xFF)
         self.w_mask = dev_empty((o, i // 32), np.uint32, 0)
         self.dx = dev_empty((t, i), np.float32, float("nan"))
         self.dw = dev_empty((o, i), np.float32, float("nan"))
@@ -125,6 +129,8 @@ class Linear:
                                      self.dx, self.dw, q.QUARTET_DTYPE_F32, self.ws, self.ws_bytes))
 
     def ctx_host(self):
-        return dict(xq_codes=to_host(self.xq_codes, np.uint8), xq_scales=to_host(self.xq_scales, np.uint8),
+        return dict(xq_codes=to_host(self.xq_codes, np.uint8),
+                    xq_scales=scales_from_tiled(to_host(self.xq_scales, np.uint8), self.t, self.i),
                     x_mask=to_host(self.x_mask, np.uint32), wq_codes=to_host(self.wq_codes, np.uint8),
-                    wq_scales=to_host(self.wq_scales, np.uint8), w_mask=to_host(self.w_mask, np.uint32))
+                    wq_scales=scales_from_tiled(to_host(self.wq_scales, np.uint8), self.o, self.i),
+                    w_mask=to_host(self.w_mask, np.uint32))

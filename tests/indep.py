@@ -62,3 +62,30 @@ def read_table1():
             name, paper, lo, hi = line.split()
             out[name] = (float(paper), float(lo), float(hi))
     return out
+
+
+# ---- tiled scale layout of the HIP library <-> row-major [rows, k/32] (pure index permutation)
+
+def scale_tile_index(rows, k):
+    """int64 array [rows, k/32] of byte offsets into the tiled scale buffer."""
+    r = np.arange(rows, dtype=np.int64)[:, None]
+    g = np.arange(k // 32, dtype=np.int64)[None, :]
+    kq = (k + 255) // 256
+    return ((r // 32) * kq + g // 8) * 256 + ((g % 2) * 32 + r % 32) * 4 + (g % 8) // 2
+
+
+def scale_tiled_bytes(rows, k):
+    return ((rows + 31) // 32) * ((k + 255) // 256) * 256
+
+
+def scales_to_tiled(scales_row_major, fill=0xFF):
+    s = np.asarray(scales_row_major, dtype=np.uint8)
+    rows, k = s.shape[0], s.shape[1] * 32
+    out = np.full(max(scale_tiled_bytes(rows, k), 4), fill, dtype=np.uint8)
+    if s.size:
+        out[scale_tile_index(rows, k)] = s
+    return out
+
+
+def scales_from_tiled(tiled, rows, k):
+    return np.asarray(tiled, dtype=np.uint8)[scale_tile_index(rows, k)] if rows * k else np.zeros((rows, k // 32), np.uint8)

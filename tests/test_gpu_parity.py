@@ -8,6 +8,7 @@ import pytest
 
 import oracle
 from paper_2505_14669_amd import synth
+from indep import scale_tiled_bytes as q_scale_bytes, scales_from_tiled
 
 pytestmark = pytest.mark.gpu
 
@@ -56,13 +57,13 @@ def test_quant_fwd_row_strided(G):
     import torch
     xd = G.to_dev(full)
     codes = G.dev_empty((50, 80), np.uint8, 0)
-    scales = G.dev_empty((50, 5), np.uint8, 0)
+    scales = G.dev_empty((q_scale_bytes(50, 160),), np.uint8, 0)
     mask = G.dev_empty((50, 5), np.uint32, 0)
     from paper_2505_14669_amd import binding as q
     q.check(q.quartet_quant_fwd(xd, 50, 160, 256, 0, codes, scales, mask))
     want = oracle.quant_fwd(np.ascontiguousarray(x))
     same(G.to_host(codes, np.uint8), want[0], "strided codes")
-    same(G.to_host(scales, np.uint8), want[1], "strided scales")
+    same(scales_from_tiled(G.to_host(scales, np.uint8), 50, 160), want[1], "strided scales")
     same(G.to_host(mask, np.uint32), want[2], "strided mask")
 
 
@@ -138,9 +139,19 @@ def test_gemm_exhaustive_code_pairs_bit_exact(G):
     assert np.array_equal(got.astype(np.float64), oracle.mxfp4_gemm(ac, one_a, bc, one_b))
 
 
+@pytest.fixture(params=["auto", "0", "1", "2"])
+def gemm_variant(request, monkeypatch):
+    # every tile shape of the GEMM kernel is checked, not only the one the size heuristic picks
+    if request.param == "auto":
+        monkeypatch.delenv("QUARTET_GEMM_VARIANT", raising=False)
+    else:
+        monkeypatch.setenv("QUARTET_GEMM_VARIANT", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("mnk", [(1, 1, 32), (32, 32, 64), (128, 128, 128), (130, 70, 96), (257, 129, 160),
-                                 (64, 300, 1024), (384, 256, 2048)])
-def test_gemm_random(G, mnk):
+                                 (64, 300, 1024), (384, 256, 2048), (520, 513, 800)])
+def test_gemm_random(G, mnk, gemm_variant):
     m, n, k = mnk
     rng = np.random.default_rng(m * 1000 + n)
     ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
