@@ -136,7 +136,7 @@ int quartet_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_sc
  *   D[m x n] = alpha * sum_k dec(A)[m,k] * dec(B)[n,k]
  * A = (a_codes [m x k/2], a_scales tiled for [m x k]), B = (b_codes [n x k/2], b_scales tiled for
  * [n x k]), both K-contiguous.  Products are exact, accumulation is fp32 on the matrix cores.  d is fp32 or bf16
- * (d_dtype), row-major with leading dimension ldd >= n.  k % 32 == 0, k <= 2^23; m, n arbitrary.
+ * (d_dtype), row-major with leading dimension n <= ldd <= 2^21.  k % 32 == 0, k <= 2^23; m, n arbitrary.
  */
 int quartet_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
                        const uint8_t *b_codes, const uint8_t *b_scales,

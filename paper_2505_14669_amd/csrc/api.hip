@@ -217,6 +217,7 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     if (!a_codes || !a_scales || !b_codes || !b_scales || !d) return QUARTET_EINVAL;
     if (!aligned16(a_codes) || !aligned16(b_codes) || !aligned16(d)) return QUARTET_EINVAL;
     if (m < 0 || n < 0 || k < 0 || (k % 32) != 0 || ldd < n) return QUARTET_EINVAL;
+    if (ldd > ((int64_t)1 << 21)) return QUARTET_ENOTSUP;
     if (d_dtype != QUARTET_DTYPE_F32 && d_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
     if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k > ((int64_t)1 << 23)) return QUARTET_ENOTSUP;
     if (((m + 127) / 128) * ((n + 127) / 128) >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;

@@ -35,7 +35,7 @@ __device__ __forceinline__ v16f mfma_fp4(const uint4& a, const uint4& b, v16f c,
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, c, 4, 4, S, (int)sa, S, (int)sb);
 }
 
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 // Raw buffer resource over [base, base + bytes): loads past the end return zero, which is how ragged
 // tile edges are handled without per-load predicates.
@@ -45,19 +45,28 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here reaches
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_BF16>
-__global__ void __launch_bounds__(WAVES_M * WAVES_N * 64)
+// Block = 4 waves (2 x 2), wave tile (TM*32) x (TN*32), block tile BM x BN = (2*TM*32) x (2*TN*32).
+// Per stage (256 K-elements) a block moves BM + BN rows of 128 code bytes straight from global
+// memory into LDS (buffer_load ... lds, 16 bytes per lane, lane l landing at base + 16 l), into the
+// buffer the matrix cores are not reading; the 16-byte chunk a lane fetches is chosen so that the
+// linear LDS image is the XOR-swizzled tile (chunk c of row r sits at r*8 + (c ^ (r/2)%8)), which
+// makes the 16-byte fragment reads bank-conflict free.  One wave runs per SIMD, so the instruction
+// stream is software-pipelined by hand: fragments of K-step s+1 are read, and a quarter of the next
+// stage's loads is issued, between the matrix-core instructions of K-step s.
+template <int TM, int TN, bool OUT_BF16>
+__global__ void __launch_bounds__(256)
 gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                   const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
-                  uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, int64_t ldd,
+                  uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
                   uint32_t tiles_m, uint32_t tiles_n) {
-    constexpr uint32_t NT = WAVES_M * WAVES_N * 64;
-    constexpr uint32_t BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr uint32_t LA = BM * 8 / NT, LB = BN * 8 / NT;   // 16-byte chunks each thread moves per stage
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0 && (NT / 8) % 8 == 0, "tile/threads mismatch");
-    __shared__ uint4 lds[2][(BM + BN) * 8];
+    constexpr uint32_t BM = 2 * TM * 32, BN = 2 * TN * 32;
+    constexpr uint32_t LA = BM / 32, LB = BN / 32;      // 1 KB (64 lanes x 16 B) loads per wave per stage
+    constexpr uint32_t STAGE = (BM + BN) * 8;           // 16-byte chunks per LDS buffer
+    constexpr uint32_t ESIZE = OUT_BF16 ? 2 : 4;
+    __shared__ uint4 lds[2 * STAGE];
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lives in an SGPR
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
 
     // XCD-aware tile order: consecutive block ids land on different XCDs (8, round-robin), so give
@@ -74,7 +83,7 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
     const uint32_t band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
     const uint32_t in_band = tile - band * GM * tiles_n;
     const uint32_t m0 = (band * GM + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-    const uint32_t wm0 = (wave / WAVES_N) * (TM * 32), wn0 = (wave % WAVES_N) * (TN * 32);
+    const uint32_t wm0 = (wave >> 1) * (TM * 32), wn0 = (wave & 1u) * (TN * 32);
 
     const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;   // code bytes, groups, K-quads per row
     const uint32_t rows_a = (m - m0) < BM ? (m - m0) : BM, rows_b = (n - n0) < BN ? (n - n0) : BN;
@@ -93,131 +102,419 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // this thread's chunk: row tid/8 (+ j*NT/8), 16-byte column tid%8 of the 128-byte stage row
-    const uint32_t crow = tid >> 3, ccol = tid & 7u;
-    const uint32_t goff = crow * kb + ccol * 16u;               // byte offset inside the tile's rows
-    const uint32_t gstep = (NT / 8u) * kb;                       // + j * gstep for the j-th chunk
-    const uint32_t lpos = crow * 8u + (ccol ^ (crow & 7u));     // LDS chunk position (+ j * NT)
-    const uint32_t soff_a = ((wm0 >> 5) * kq * 64u + lane) * 4u;  // + i * kq*256 per 32-row block, + st*256
+    // global -> LDS: load j of this wave fills LDS chunks [j*256 + wave*64, +64) of the operand's
+    // region, i.e. rows j*32 + wave*8 + lane/8; the lane fetches logical chunk (lane%8) ^ ((row/2)%8).
+    const uint32_t drow = wave * 8u + (lane >> 3);
+    const uint32_t dcol = (lane & 7u) ^ ((drow >> 1) & 7u);
+    const uint32_t goff = drow * kb + dcol * 16u;       // + j * 32 * kb, + stage * 128
+    const uint32_t gstep = 32u * kb;
+    const uint32_t soff_a = ((wm0 >> 5) * kq * 64u + lane) * 4u;   // + i * kq*256 per 32-row block, + st*256
     const uint32_t soff_b = ((wn0 >> 5) * kq * 64u + lane) * 4u;
     const uint32_t sstep = kq * 256u;
+    // fragment reads: chunk (2S + lhalf) ^ ((row/2) % 8) of row w?0 + i*32 + lrow
+    const uint32_t swz = lhalf ^ ((lrow >> 1) & 7u);
+    const uint32_t fa_base = (wm0 + lrow) * 8u, fb_base = BM * 8u + (wn0 + lrow) * 8u;
 
     const uint32_t stages = kq;
-    v4u ra[LA], rb[LB];
     uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
+    uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
-#define QUARTET_LOAD_STAGE(ST, XA, XB)                                                                  \
+// Quarter P (0..3) of the loads of stage ST into LDS buffer BUF and scale registers XA, XB.  A stage
+// past the end of K is out of range of the resources and arrives as zeros, so no branch is needed.
+#define QUARTET_ISSUE_PART(P, ST, BUF, XA, XB)                                                          \
     {                                                                                                   \
         const uint32_t st_ = (ST);                                                                      \
-        const uint32_t base_ = (st_ * 128u + ccol * 16u < kb) ? goff + st_ * 128u : kOutOfRange;        \
-        _Pragma("unroll") for (uint32_t j = 0; j < LA; ++j)                                             \
-            ra[j] = __builtin_amdgcn_raw_buffer_load_b128(res_a, base_ + j * gstep, 0, 0);              \
-        _Pragma("unroll") for (uint32_t j = 0; j < LB; ++j)                                             \
-            rb[j] = __builtin_amdgcn_raw_buffer_load_b128(res_b, base_ + j * gstep, 0, 0);              \
+        const uint32_t base_ = (st_ * 128u + dcol * 16u < kb) ? goff + st_ * 128u : kOutOfRange;        \
+        _Pragma("unroll") for (uint32_t j = (P) * LA / 4; j < ((P) + 1) * LA / 4; ++j)                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_a, (lds_ptr_t)&lds[(BUF) * STAGE + j * 256u + wave * 64u], 16, \
+                                                     base_ + j * gstep, 0, 0, 0);                       \
+        _Pragma("unroll") for (uint32_t j = (P) * LB / 4; j < ((P) + 1) * LB / 4; ++j)                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_b, (lds_ptr_t)&lds[(BUF) * STAGE + BM * 8u + j * 256u + wave * 64u], 16, \
+                                                     base_ + j * gstep, 0, 0, 0);                       \
         _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                             \
-            XA[i] = __builtin_amdgcn_raw_buffer_load_b32(res_sa, soff_a + i * sstep + st_ * 256u, 0, 0); \
+            if (i * 4 / TM == (P) && (i * 4) % TM == 0)                                                 \
+                XA[i] = __builtin_amdgcn_raw_buffer_load_b32(res_sa, soff_a + i * sstep + st_ * 256u, 0, 0); \
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
-            XB[j] = __builtin_amdgcn_raw_buffer_load_b32(res_sb, soff_b + j * sstep + st_ * 256u, 0, 0); \
-        if (st_ == stages - 1u && (gk & 7u) != 0u) {                                                    \
-            /* ragged K: groups past k/32 hold zero codes; neutralize whatever their scale bytes hold */ \
-            uint32_t keep = 0u;                                                                         \
-            _Pragma("unroll") for (uint32_t p = 0; p < 4; ++p)                                          \
-                if (st_ * 8u + 2u * p + lhalf < gk) keep |= 0xFFu << (8u * p);                          \
-            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (XA[i] & keep) | (0x7F7F7F7Fu & ~keep); \
-            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (XB[j] & keep) | (0x7F7F7F7Fu & ~keep); \
-        }                                                                                               \
+            if (j * 4 / TN == (P) && (j * 4) % TN == 0)                                                 \
+                XB[j] = __builtin_amdgcn_raw_buffer_load_b32(res_sb, soff_b + j * sstep + st_ * 256u, 0, 0); \
     }
-#define QUARTET_STORE_STAGE(BUF)                                                                        \
+// ragged K: groups past k/32 hold zero codes; neutralize whatever their scale bytes hold
+#define QUARTET_FIX_SCALES(ST, XA, XB)                                                                  \
+    if ((ST) + 1u >= stages && (gk & 7u) != 0u) {                                                       \
+        uint32_t keep = 0u;                                                                             \
+        _Pragma("unroll") for (uint32_t p = 0; p < 4; ++p)                                              \
+            if ((ST) * 8u + 2u * p + lhalf < gk) keep |= 0xFFu << (8u * p);                             \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (XA[i] & keep) | (0x7F7F7F7Fu & ~keep); \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (XB[j] & keep) | (0x7F7F7F7Fu & ~keep); \
+    }
+#define QUARTET_READ_FRAGS(BUF, S, FA, FB)                                                              \
     {                                                                                                   \
-        _Pragma("unroll") for (uint32_t j = 0; j < LA; ++j)                                             \
-            lds[BUF][lpos + j * NT] = make_uint4(ra[j].x, ra[j].y, ra[j].z, ra[j].w);                   \
-        _Pragma("unroll") for (uint32_t j = 0; j < LB; ++j)                                             \
-            lds[BUF][BM * 8u + lpos + j * NT] = make_uint4(rb[j].x, rb[j].y, rb[j].z, rb[j].w);         \
+        const uint4* sbuf_ = &lds[(BUF) * STAGE];                                                       \
+        const uint32_t c_ = (2u * (S)) ^ swz;                                                           \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) FA[i] = sbuf_[fa_base + i * 256u + c_];     \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) FB[j] = sbuf_[fb_base + j * 256u + c_];     \
     }
-#define QUARTET_KSTEP(S)                                                                                \
-    {                                                                                                   \
-        uint4 fa[TM], fb[TN];                                                                           \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) {                                           \
-            uint32_t row = wm0 + i * 32u + lrow;                                                        \
-            fa[i] = sA[row * 8u + ((2u * S + lhalf) ^ (row & 7u))];                                     \
-        }                                                                                               \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) {                                           \
-            uint32_t row = wn0 + j * 32u + lrow;                                                        \
-            fb[j] = sB[row * 8u + ((2u * S + lhalf) ^ (row & 7u))];                                     \
-        }                                                                                               \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                             \
-            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                         \
-                acc[i][j] = mfma_fp4<S>(fa[i], fb[j], acc[i][j], sa[i], sb[j]);                         \
-        if (NT > 256) __builtin_amdgcn_sched_barrier(0); /* two waves per SIMD: keep fragments of one K-step live at a time */ \
+#define QUARTET_MFMAS(S, FA, FB)                                                                        \
+    _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                                 \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
+            acc[i][j] = mfma_fp4<S>(FA[i], FB[j], acc[i][j], sa[i], sb[j]);
+// Zero-instruction pin: the accumulators must hold the results of every matrix-core instruction
+// issued so far, which keeps the compiler from sinking that work below the wait and the barrier.
+#define QUARTET_PIN_ACC()                                                                               \
+    _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                                 \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+// Issue order inside a K-step: one LDS fragment read (if READS), one global load (the first NV
+// groups), then the group's share of the matrix-core instructions.
+#define QUARTET_PIPE(READS, NV)                                                                         \
+    _Pragma("unroll") for (uint32_t g_ = 0; g_ < TM + TN; ++g_) {                                       \
+        if (READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
+        if (g_ < (NV)) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               \
+        __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);                          \
     }
+    constexpr uint32_t NV = LA / 4 + LB / 4 + 2;   // loads per quarter (TM = TN = 2: scale loads only in quarters 0, 2)
 
     if (stages > 0) {
-        QUARTET_LOAD_STAGE(0u, sa, sb)
-        QUARTET_STORE_STAGE(0)
+        QUARTET_ISSUE_PART(0, 0u, 0u, sa, sb)
+        QUARTET_ISSUE_PART(1, 0u, 0u, sa, sb)
+        QUARTET_ISSUE_PART(2, 0u, 0u, sa, sb)
+        QUARTET_ISSUE_PART(3, 0u, 0u, sa, sb)
+        QUARTET_FIX_SCALES(0u, sa, sb)
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-direct loads have landed
+        __syncthreads();
+        QUARTET_READ_FRAGS(0u, 0u, fa0, fb0)
     }
-    __syncthreads();
 
     for (uint32_t st = 0; st < stages; ++st) {
         const uint32_t buf = st & 1u;
-        const bool more = st + 1u < stages;
-        if (more) QUARTET_LOAD_STAGE(st + 1u, sa_n, sb_n)
-        const uint4* sA = &lds[buf][0];
-        const uint4* sB = &lds[buf][BM * 8];
-        QUARTET_KSTEP(0)
-        QUARTET_KSTEP(1)
-        QUARTET_KSTEP(2)
-        QUARTET_KSTEP(3)
-        if (more) {
-            QUARTET_STORE_STAGE(buf ^ 1u)
-#pragma unroll
-            for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];
-#pragma unroll
-            for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        QUARTET_ISSUE_PART(0, st + 1u, buf ^ 1u, sa_n, sb_n)
+        QUARTET_READ_FRAGS(buf, 1u, fa1, fb1)
+        QUARTET_MFMAS(0, fa0, fb0)
+        QUARTET_PIPE(true, NV)
+        QUARTET_PIN_ACC()
+        __builtin_amdgcn_sched_barrier(0);
+        QUARTET_ISSUE_PART(1, st + 1u, buf ^ 1u, sa_n, sb_n)
+        QUARTET_READ_FRAGS(buf, 2u, fa0, fb0)
+        QUARTET_MFMAS(1, fa1, fb1)
+        QUARTET_PIPE(true, NV)
+        QUARTET_PIN_ACC()
+        __builtin_amdgcn_sched_barrier(0);
+        QUARTET_ISSUE_PART(2, st + 1u, buf ^ 1u, sa_n, sb_n)
+        QUARTET_READ_FRAGS(buf, 3u, fa1, fb1)
+        QUARTET_MFMAS(2, fa0, fb0)
+        QUARTET_PIPE(true, NV)
+        QUARTET_PIN_ACC()
+        __builtin_amdgcn_sched_barrier(0);
+        QUARTET_ISSUE_PART(3, st + 1u, buf ^ 1u, sa_n, sb_n)
+        QUARTET_MFMAS(3, fa1, fb1)
+        QUARTET_PIPE(false, NV)
+        QUARTET_PIN_ACC()
+        __builtin_amdgcn_sched_barrier(0);    // the matrix-core work stays ahead of the wait
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // next stage's codes are in LDS, its scales in registers
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        QUARTET_READ_FRAGS(buf ^ 1u, 0u, fa0, fb0)
+        QUARTET_FIX_SCALES(st + 1u, sa_n, sb_n)
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
     }
-#undef QUARTET_LOAD_STAGE
-#undef QUARTET_STORE_STAGE
-#undef QUARTET_KSTEP
+#undef QUARTET_ISSUE_PART
+#undef QUARTET_FIX_SCALES
+#undef QUARTET_READ_FRAGS
+#undef QUARTET_MFMAS
+#undef QUARTET_PIPE
+#undef QUARTET_PIN_ACC
 
+    // D tile through a buffer resource: rows past m fall outside it and are dropped by the hardware;
+    // columns past n are sent out of range per lane.  The wave-uniform part of each address rides in
+    // the scalar offset, so a store costs no vector ALU work beyond the alpha multiply.
+    const uint32_t tile_bytes = ((rows_a - 1u) * ldd + rows_b) * ESIZE;
+    const __amdgpu_buffer_rsrc_t res_d = make_rsrc(static_cast<uint8_t*>(d) + ((size_t)m0 * ldd + n0) * ESIZE, tile_bytes);
+    const uint32_t lane_off = (lhalf * 4u * ldd + lrow) * ESIZE;
 #pragma unroll
-    for (uint32_t i = 0; i < TM; ++i)
+    for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t voff = (wn0 + j * 32u + lrow < rows_b) ? lane_off : kOutOfRange;
 #pragma unroll
-        for (uint32_t j = 0; j < TN; ++j) {
-            uint32_t col = n0 + wn0 + j * 32u + lrow;
+        for (uint32_t i = 0; i < TM; ++i)
 #pragma unroll
             for (uint32_t r = 0; r < 16; ++r) {
-                uint32_t row = m0 + wm0 + i * 32u + (r >> 2) * 8u + lhalf * 4u + (r & 3u);
-                if (row < m && col < n) {
-                    float val = alpha * acc[i][j][r];
-                    if (OUT_BF16)
-                        static_cast<uint16_t*>(d)[(size_t)row * ldd + col] = f32_to_bf16_rne(val);
-                    else
-                        static_cast<float*>(d)[(size_t)row * ldd + col] = val;
-                }
+                const uint32_t soff = ((wm0 + i * 32u + (r >> 2) * 8u + (r & 3u)) * ldd + wn0 + j * 32u) * ESIZE;
+                const float val = alpha * acc[i][j][r];
+                if (OUT_BF16)
+                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(val), res_d, voff, soff, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b32(f2u(val), res_d, voff, soff, 0);
             }
-        }
+    }
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN>
-static hipError_t launch_variant(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                                 const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha,
-                                 void* d, int d_bf16, int64_t ldd, hipStream_t st) {
-    constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
-    dim3 grid(tiles_m * tiles_n), block(WAVES_M * WAVES_N * 64);
-    const uint8_t *as = a_scales, *bs = b_scales;
+// ---------------------------------------------------------------------------------------------
+// Ring variant for large problems.  Same 256 x 256 block tile and 128 x 128 wave tile, but K is staged
+// 128 elements (64 code bytes per row) at a time through a ring of kRing LDS stages that is filled
+// kRing-1 stages ahead, so roughly 100 KB per CU are in flight and no wait ever falls on loads that
+// were just issued.  A stage is [A codes 16 KB][B codes 16 KB][16 scale tiles 4 KB], all written by
+// LDS-direct loads (9 per wave per stage).
+//
+// The LDS-direct loads are issued from inline assembly and the barrier is a bare s_barrier, with the
+// vector-memory counter managed by hand: the compiler cannot tell which LDS reads alias an
+// LDS-direct load in flight, so it would otherwise drain every outstanding load before each
+// fragment read (and before each barrier), which serializes the copy and the matrix-core work.
+constexpr uint32_t kRing = 4;
+
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4i_t make_rsrc_words(const void* base, uint32_t bytes) {
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    v4i_t r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
+    return r;
+}
+
+// 16 bytes per lane from the buffer resource at byte offset voff (past the end: zeros) to LDS byte
+// address lds_base + 16 * lane.  lds_base must be wave-uniform.  Completion is counted by vmcnt.
+__device__ __forceinline__ void lds_direct_load16(v4i_t rsrc, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+}
+
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(256)
+gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+                       const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
+                       uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
+                       uint32_t tiles_m, uint32_t tiles_n) {
+    constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
+    constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
+    constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
+    constexpr uint32_t D = kRing - 1;                    // prefetch distance in stages
+    constexpr uint32_t LOADS = 9;                        // vector-memory operations per wave per stage
+    constexpr uint32_t ESIZE = OUT_BF16 ? 2 : 4;
+    // s_waitcnt: wait until at most (D-1)*LOADS vector-memory operations are outstanding
+    constexpr uint32_t KEEP = (D - 1) * LOADS;
+    constexpr uint32_t WAIT_STAGE = 0x0F70u | (KEEP & 15u) | ((KEEP >> 4) << 14);
+    __shared__ uint4 lds[kRing * STAGE];
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+
+    uint32_t tile;
+    {
+        const uint32_t nb = gridDim.x, xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+        const uint32_t per = nb >> 3, rem = nb & 7u;
+        tile = xcd * per + (xcd < rem ? xcd : rem) + q;
+    }
+    constexpr uint32_t GM = 8;
+    const uint32_t band = tile / (GM * tiles_n);
+    const uint32_t band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
+    const uint32_t in_band = tile - band * GM * tiles_n;
+    const uint32_t m0 = (band * GM + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
+    const uint32_t wm0 = (wave >> 1) * 128u, wn0 = (wave & 1u) * 128u;
+
+    const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;
+    const uint32_t rows_a = (m - m0) < BM ? (m - m0) : BM, rows_b = (n - n0) < BN ? (n - n0) : BN;
+    const v4i_t res_a = make_rsrc_words(a_codes + (size_t)m0 * kb, rows_a * kb);
+    const v4i_t res_b = make_rsrc_words(b_codes + (size_t)n0 * kb, rows_b * kb);
+    // waves 0,1 fetch the A scale tiles, waves 2,3 the B scale tiles (4 tiles of 256 B per load)
+    const bool scales_of_a = wave < 2u;
+    const uint32_t srow0 = scales_of_a ? m0 : n0, srows = scales_of_a ? rows_a : rows_b;
+    const v4i_t res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0 >> 5) * kq * 256u,
+                                        ((srows + 31u) >> 5) * kq * 256u);
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // codes: load j of a wave fills chunks [j*256 + wave*64, +64) = rows j*64 + wave*16 + lane/4 of the
+    // stage (4 chunks per row); chunk c of row r is stored at r*4 + (c ^ (r/2)%4).
+    const uint32_t drow = wave * 16u + (lane >> 2);
+    const uint32_t dcol = (lane & 3u) ^ ((drow >> 1) & 3u);
+    const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
+    const uint32_t gstep = 64u * kb;
+    const uint32_t soff = (((wave & 1u) * 4u + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
+    // fragment reads of K-step s (0,1): chunk (2s + lhalf) ^ (row/2)%4 of row w?0 + i*32 + lrow
+    const uint32_t swz = (lrow >> 1) & 3u;
+    const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
+    const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
+    const uint32_t sb_base = CODES * 4u + 8u * 64u + (wn0 >> 5) * 64u + lane;
+
+    const uint32_t stages = (k + 127u) >> 7;
+    uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
+    uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+
+// load J (0..3: A rows, 4..7: B rows, 8: scale tiles) of stage ST; stages past the end give zeros
+#define RING_ISSUE(ST, J)                                                                               \
+    {                                                                                                   \
+        const uint32_t st_ = (ST);                                                                      \
+        const uint32_t slot_ = lds0 + ((st_ % kRing) * STAGE + wave * 64u) * 16u;                       \
+        if ((J) < 8u) {                                                                                 \
+            const uint32_t base_ = (st_ * 64u + dcol * 16u < kb) ? goff + st_ * 64u : kOutOfRange;      \
+            lds_direct_load16((J) < 4u ? res_a : res_b, base_ + ((J) & 3u) * gstep, slot_ + (J) * 4096u); \
+        } else {                                                                                        \
+            lds_direct_load16(res_s, (st_ < stages) ? soff + (st_ >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+        }                                                                                               \
+    }
+#define RING_FRAG_A(ST, S, FA, I) FA[I] = lds[((ST) % kRing) * STAGE + fa_base + (I) * 128u + ((2u * (S) + lhalf) ^ swz)];
+#define RING_FRAG_B(ST, S, FB, J) FB[J] = lds[((ST) % kRing) * STAGE + fb_base + (J) * 128u + ((2u * (S) + lhalf) ^ swz)];
+// scale dwords of the stage's K-quad, moved so that this stage's two K-steps are bytes 0 and 1
+#define RING_READ_SCALES(ST, XA, XB)                                                                    \
+    {                                                                                                   \
+        const uint32_t st_ = (ST);                                                                      \
+        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(st_ % kRing) * STAGE]);         \
+        const uint32_t sh_ = (st_ & 1u) * 16u;                                                          \
+        uint32_t keep_ = 0u;    /* ragged K: neutralize the scale bytes of groups past k/32 */          \
+        if (st_ * 4u + lhalf < gk) keep_ |= 0xFFu;                                                      \
+        if (st_ * 4u + 2u + lhalf < gk) keep_ |= 0xFF00u;                                               \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                             \
+            XA[i] = ((sbuf_[sa_base + i * 64u] >> sh_) & keep_) | (0x7F7Fu & ~keep_);                   \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
+            XB[j] = ((sbuf_[sb_base + j * 64u] >> sh_) & keep_) | (0x7F7Fu & ~keep_);                   \
+    }
+#define RING_MFMA_ROW(S, FA, FB, I)                                                                     \
+    _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                                 \
+        acc[I][j] = mfma_fp4<S>(FA[I], FB[j], acc[I][j], sa[I], sb[j]);
+// zero-instruction pin: row I of the accumulators holds every result issued so far
+#define RING_PIN_ROW(I)                                                                                 \
+    _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[I][j]));
+#define RING_FENCE() __builtin_amdgcn_sched_barrier(0);
+
+    // prologue: always issue D stages, wait for stage 0
+#pragma unroll
+    for (uint32_t s0 = 0; s0 < D; ++s0) {
+#pragma unroll
+        for (uint32_t j = 0; j < LOADS; ++j) RING_ISSUE(s0, j)
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(0u, 0u, fa0, i) RING_FRAG_B(0u, 0u, fb0, i) }
+    RING_READ_SCALES(0u, sa, sb)
+
+    for (uint32_t st = 0; st < stages; ++st) {
+        // K-step 0 on fragment set 0; fragment set 1 is read and 4 loads of stage st+D are issued meanwhile
+#define RING_K0_ROW(I)                                                                                  \
+        RING_FENCE()                                                                                    \
+        RING_ISSUE(st + D, I)                                                                           \
+        RING_FENCE()                                                                                    \
+        if ((I) < 2) { RING_FRAG_B(st, 1u, fb1, 2 * (I)) RING_FRAG_B(st, 1u, fb1, 2 * (I) + 1) }        \
+        else { RING_FRAG_A(st, 1u, fa1, 2 * (I) - 4) RING_FRAG_A(st, 1u, fa1, 2 * (I) - 3) }            \
+        RING_MFMA_ROW(0, fa0, fb0, I)                                                                   \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                              \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                              \
+        RING_PIN_ROW(I)
+        RING_K0_ROW(0)
+        RING_K0_ROW(1)
+        RING_K0_ROW(2)
+        RING_K0_ROW(3)
+#undef RING_K0_ROW
+        // first half of K-step 1 with the remaining 5 loads
+        RING_FENCE()
+        RING_ISSUE(st + D, 4u)
+        RING_ISSUE(st + D, 5u)
+        RING_FENCE()
+        RING_MFMA_ROW(1, fa1, fb1, 0)
+        RING_PIN_ROW(0)
+        RING_FENCE()
+        RING_ISSUE(st + D, 6u)
+        RING_ISSUE(st + D, 7u)
+        RING_ISSUE(st + D, 8u)
+        RING_FENCE()
+        RING_MFMA_ROW(1, fa1, fb1, 1)
+        RING_PIN_ROW(1)
+        RING_FENCE()
+        // stage st+1 has landed in LDS (stages st+2 .. st+D stay in flight)
+        __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
+        __builtin_amdgcn_s_barrier();
+        RING_FENCE()
+        // second half of K-step 1 over the LDS latency of the next stage's first fragments
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(st + 1u, 0u, fa0, i) RING_FRAG_B(st + 1u, 0u, fb0, i) }
+        RING_READ_SCALES(st + 1u, sa_n, sb_n)
+        RING_MFMA_ROW(1, fa1, fb1, 2)
+        RING_MFMA_ROW(1, fa1, fb1, 3)
+#pragma unroll
+        for (uint32_t g_ = 0; g_ < 8; ++g_) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        RING_PIN_ROW(2)
+        RING_PIN_ROW(3)
+        RING_FENCE()
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the zero-filled stages issued past the end
+#undef RING_ISSUE
+#undef RING_FRAG_A
+#undef RING_FRAG_B
+#undef RING_READ_SCALES
+#undef RING_MFMA_ROW
+#undef RING_PIN_ROW
+#undef RING_FENCE
+
+    const uint32_t tile_bytes = ((rows_a - 1u) * ldd + rows_b) * ESIZE;
+    const __amdgpu_buffer_rsrc_t res_d = make_rsrc(static_cast<uint8_t*>(d) + ((size_t)m0 * ldd + n0) * ESIZE, tile_bytes);
+    const uint32_t lane_off = (lhalf * 4u * ldd + lrow) * ESIZE;
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t voff = (wn0 + j * 32u + lrow < rows_b) ? lane_off : kOutOfRange;
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+            for (uint32_t r = 0; r < 16; ++r) {
+                const uint32_t soff_d = ((wm0 + i * 32u + (r >> 2) * 8u + (r & 3u)) * ldd + wn0 + j * 32u) * ESIZE;
+                const float val = alpha * acc[i][j][r];
+                if (OUT_BF16)
+                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(val), res_d, voff, soff_d, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b32(f2u(val), res_d, voff, soff_d, 0);
+            }
+    }
+}
+
+static hipError_t launch_ring(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                              const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha,
+                              void* d, int d_bf16, int64_t ldd, hipStream_t st) {
+    uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
+    dim3 grid(tiles_m * tiles_n), block(256);
     if (d_bf16)
-        hipLaunchKernelGGL((gemm_mxfp4_kernel<WAVES_M, WAVES_N, TM, TN, true>), grid, block, 0, st, a_codes, as,
-                           b_codes, bs, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, ldd, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<true>), grid, block, 0, st, a_codes, a_scales, b_codes,
+                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
     else
-        hipLaunchKernelGGL((gemm_mxfp4_kernel<WAVES_M, WAVES_N, TM, TN, false>), grid, block, 0, st, a_codes, as,
-                           b_codes, bs, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, ldd, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<false>), grid, block, 0, st, a_codes, a_scales, b_codes,
+                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
-// Tile shapes: 0 = 256x256 (8 waves, 128x64 each), 1 = 256x256 (4 waves, 128x128 each),
-// 2 = 128x128 (4 waves, 64x64 each).  QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
+template <int TM, int TN>
+static hipError_t launch_variant(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                                 const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha,
+                                 void* d, int d_bf16, int64_t ldd, hipStream_t st) {
+    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+    uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
+    dim3 grid(tiles_m * tiles_n), block(256);
+    if (d_bf16)
+        hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, true>), grid, block, 0, st, a_codes, a_scales, b_codes,
+                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, false>), grid, block, 0, st, a_codes, a_scales, b_codes,
+                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// Variants: 0 = 256x256 block, ring of 4 LDS stages (large problems); 1 = 128x128 block, two LDS
+// buffers (problems too small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.  QUARTET_GEMM_VARIANT overrides the
+// size heuristic (tuning aid).
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                        int d_bf16, int64_t ldd, hipStream_t st) {
@@ -226,13 +523,13 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     int variant = (env && *env) ? atoi(env) : -1;
     if (variant < 0) {
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-        variant = big_tiles >= 192 ? 0 : 2;
+        variant = big_tiles >= 192 ? 0 : 1;
     }
-    switch (variant) {
-    case 0: return launch_variant<2, 4, 4, 2>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
-    case 1: return launch_variant<2, 2, 4, 4>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
-    default: return launch_variant<2, 2, 2, 2>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
-    }
+    if (variant == 0)
+        return launch_ring(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
+    if (variant == 2)
+        return launch_variant<4, 4>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
+    return launch_variant<2, 2>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
 }
 
 }  // namespace quartet
