@@ -107,7 +107,8 @@ int quartet_quant_fwd(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, 
  * two); v_i = fl((h_i 2^-e) * 3/4), so |v_i| < 6 and nothing clips; code_i = E2M1 of v_i by
  *   rounding = QUARTET_ROUND_NEAREST   : round-to-nearest-even (Algorithm 1 as printed), or
  *   rounding = QUARTET_ROUND_STOCHASTIC: with lo <= |v| < hi the neighbouring grid points and
- *     f = (|v|-lo)/(hi-lo), round up iff (r + 1/2) / 2^16 < f, r = the element's 16-bit draw.
+ *     f = (|v|-lo)/(hi-lo), round up iff floor(f 2^22) + 64 r >= 2^22, r = the element's 16-bit
+ *     draw (probability floor(f 2^16) / 2^16 of rounding up).
  * Draws: Philox4x32-10 with key (seed & 0xFFFFFFFF, seed >> 32); the element at output position
  * L = row*k + kk uses call q = L / 8 with counter (q_lo, q_hi, stream_id, 0) and takes bits
  * [16 j, 16 j + 16) of the 128-bit output, j = L mod 8.  Row and transposed mode therefore give

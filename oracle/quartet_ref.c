@@ -104,8 +104,11 @@ uint8_t quartet_ref_e2m1_rtn(float v) {
 /* stochastic rounding onto the E2M1 grid for |v| < 6 (Section 3, "Rounding":
  * up or down with probability given by the distance to the two neighbours).
  * lo <= |v| < hi are adjacent grid points, f = (|v|-lo)/(hi-lo) in [0,1);
- * r is a uniform SR_BITS-bit integer, u = (r + 1/2) / 2^SR_BITS; the result is hi
- * iff u < f.  Grid points never move (f = 0); P(up) differs from f by < 2^-SR_BITS. */
+ * r is a uniform SR_BITS-bit integer; the result is hi iff
+ *     floor(f * 2^22) + r * 2^(22-SR_BITS) >= 2^22,
+ * i.e. P(up) = floor(f 2^SR_BITS) / 2^SR_BITS: within 2^-SR_BITS of f, never above it.
+ * Grid points never move (f = 0).  (f is compared at a resolution of 2^-22, the number of
+ * fp32 mantissa bits below the one E2M1 keeps.) */
 uint8_t quartet_ref_e2m1_sr(float v, uint32_t r) {
     double a = fabs((double)v);
     int lo = 0;
@@ -114,8 +117,9 @@ uint8_t quartet_ref_e2m1_sr(float v, uint32_t r) {
     int code = lo;
     if (lo < 7) {
         double f = (a - E2M1_MAG[lo]) / (E2M1_MAG[lo + 1] - E2M1_MAG[lo]);
-        double u = ((double)(r & ((1u << SR_BITS) - 1)) + 0.5) / (double)(1u << SR_BITS);
-        if (u < f) code = lo + 1;
+        uint64_t F = (uint64_t)floor(f * 4194304.0);                 /* floor(f 2^22), exact */
+        uint64_t R = (uint64_t)(r & ((1u << SR_BITS) - 1)) << (22 - SR_BITS);
+        if (F + R >= 4194304u) code = lo + 1;
     }
     return (uint8_t)(code | ((f32_to_bits(v) >> 31) << 3));
 }

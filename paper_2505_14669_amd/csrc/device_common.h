@@ -71,26 +71,42 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// Stochastic rounding of v (|v| < 6) onto the E2M1 grid with a 16-bit draw r (Section 3,
-// "Rounding"): with lo <= |v| < hi adjacent grid points and f = (|v|-lo)/(hi-lo), the result is
-// hi iff (r + 1/2) / 2^16 < f.  Returns the 4-bit code (bit 3 = sign bit of v).
-//  |v| >= 1: the grid keeps one mantissa bit, f is the 22 discarded bits F / 2^22, and
-//            f > (r + 1/2)/2^16  <=>  F >= 64 r + 33  <=>  F + 2^22 - 64 r - 33 carries into bit 22.
-//  |v| <  1: the grid is {0, 1/2, 1}; with u = (r + 1/2)/2^16 the code is the number of the
-//            thresholds u, 1 + u that 2|v| exceeds = ceil(fl(2|v| - u)); the subtraction's sign is
-//            exact, and when 2|v| >= 1 both operands are multiples of 2^-23 below 2, so it is exact.
-__device__ __forceinline__ uint32_t sr_e2m1(float v, uint32_t r) {
-    uint32_t bits = f2u(v);
-    uint32_t abits = bits & 0x7FFFFFFFu;
-    // large path
-    uint32_t t = abits + (0x400000u - 33u) - (r << 6);
-    uint32_t code_large = (t >> 22) - 252u;
-    // small path
-    float u = u2f(0x3F800040u | (r << 7)) - 1.0f;          // (r + 1/2) / 2^16, exact
-    float d = __builtin_fmaf(u2f(abits), 2.0f, -u);        // fl(2|v| - u): one rounding
-    uint32_t code_small = (uint32_t)(int)__builtin_ceilf(d);
-    uint32_t code = (abits >= 0x3F800000u) ? code_large : code_small;
-    return code | ((bits >> 28) & 8u);
+// Stochastic rounding of eight values (|v| < 6) onto the E2M1 grid with eight 16-bit draws held in
+// four words (element 2p uses bits 15:0 of w[p], element 2p+1 bits 31:16), packed into one dword,
+// element j in bits [4j, 4j+4) (Section 3, "Rounding").  Rule: with lo <= |v| < hi adjacent grid
+// points and f = (|v|-lo)/(hi-lo), the result is hi iff floor(f 2^22) + 64 r >= 2^22 for the draw r.
+// v_cvt_scalef32_sr_pk_fp4_f32 was measured on gfx950 to compute exactly
+//     floor(f 2^22) + R[31:10] >= 2^22
+// for the first value of its pair with R = its 32-bit random operand, and the same with R << 1 for
+// the second value (all binades down to 2^-16, thresholds probed to +-1); the two values of a pair
+// therefore share random bits, so each pair is converted twice, once with the draw of the even
+// element in R[31:16] and once with the draw of the odd element in R[30:15], and the valid nibbles
+// are merged.
+// One conversion of a pair into byte SEL of dst, keeping dst's other bytes.  Written as inline
+// assembly because the destination must be tied to the previous partial result.
+#define QUARTET_SR_CVT(SEL, OPSEL)                                                                 \
+    template <> __device__ __forceinline__ void sr_cvt_pair<SEL>(uint32_t& dst, v2f pair, uint32_t rnd) { \
+        asm("v_cvt_scalef32_sr_pk_fp4_f32 %0, %1, %2, 1.0 op_sel:" OPSEL : "+v"(dst) : "v"(pair), "v"(rnd)); \
+    }
+template <int SEL> __device__ __forceinline__ void sr_cvt_pair(uint32_t& dst, v2f pair, uint32_t rnd);
+QUARTET_SR_CVT(0, "[0,0,0,0]")
+QUARTET_SR_CVT(1, "[0,0,1,0]")
+QUARTET_SR_CVT(2, "[0,0,0,1]")
+QUARTET_SR_CVT(3, "[0,0,1,1]")
+#undef QUARTET_SR_CVT
+
+__device__ __forceinline__ uint32_t sr_pack8(const float* v, const uint32_t (&w)[4]) {
+    uint32_t even = 0u, odd = 0u;
+    v2f p0 = {v[0], v[1]}, p1 = {v[2], v[3]}, p2 = {v[4], v[5]}, p3 = {v[6], v[7]};
+    sr_cvt_pair<0>(even, p0, w[0] << 16);
+    sr_cvt_pair<1>(even, p1, w[1] << 16);
+    sr_cvt_pair<2>(even, p2, w[2] << 16);
+    sr_cvt_pair<3>(even, p3, w[3] << 16);
+    sr_cvt_pair<0>(odd, p0, (w[0] >> 1) & 0x7FFF8000u);
+    sr_cvt_pair<1>(odd, p1, (w[1] >> 1) & 0x7FFF8000u);
+    sr_cvt_pair<2>(odd, p2, (w[2] >> 1) & 0x7FFF8000u);
+    sr_cvt_pair<3>(odd, p3, (w[3] >> 1) & 0x7FFF8000u);
+    return (even & 0x0F0F0F0Fu) | (odd & 0xF0F0F0F0u);
 }
 
 }  // namespace quartet

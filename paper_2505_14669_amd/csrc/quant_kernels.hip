@@ -78,13 +78,7 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p
                 uint64_t q = q_base + (uint64_t)call;
                 uint32_t w[4];
                 philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), p.stream_id, 0u, p.key0, p.key1, w);
-                uint32_t word = 0u;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    uint32_t r = (w[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                    word |= sr_e2m1(v[8 * call + j], r) << (4 * j);
-                }
-                c[call] = word;
+                c[call] = sr_pack8(&v[8 * call], w);
             }
         }
         scale_byte = b;

@@ -139,17 +139,22 @@ def test_sr_probability_enumerated(v):
     out = np.array([GRID[oracle.e2m1_sr(v, int(x))] for x in r])
     assert set(np.unique(out)) <= {lo, hi}
     ups = int((out == hi).sum())
-    assert abs(ups - f * 65536) <= 1.0           # P(up) = f to within 2^-16
-    assert abs(out.mean() - float(v)) <= (hi - lo) * 2.0 ** -16
+    assert ups == int(np.floor(f * 65536))       # P(up) = floor(f 2^16) / 2^16: within 2^-16 of f
+    assert -(hi - lo) * 2.0 ** -16 <= out.mean() - float(v) <= 0
     neg = np.array([GRID[oracle.e2m1_sr(-v, int(x))] for x in r[::97]])
     assert np.array_equal(neg, -out[::97])       # sign symmetric
 
 
 def test_sr_monotone_in_draw():
-    # u < f: small draws round up, large draws round down
+    # f + r/2^16 >= 1: large draws round up, small draws round down; f(2.4) = 0.4, 0.6 * 65536 = 39321.6
     v = f32(2.4)
-    codes = [oracle.e2m1_sr(v, r) for r in (0, 1000, 26213, 26215, 65535)]
-    assert [GRID[c] for c in codes] == [3.0, 3.0, 3.0, 2.0, 2.0]
+    codes = [oracle.e2m1_sr(v, r) for r in (0, 1000, 39321, 39322, 65535)]
+    assert [GRID[c] for c in codes] == [2.0, 2.0, 2.0, 3.0, 3.0]
+    # f = 2^-22 (one fp32 ulp above 1.0) is below the 16-bit resolution and never goes up;
+    # f = 1 - 2^-16 goes up for every draw but 0
+    assert GRID[oracle.e2m1_sr(np.nextafter(f32(1.0), f32(2.0)), 65535)] == 1.0
+    almost = f32(1.5 - 0.5 * 2.0 ** -16)
+    assert GRID[oracle.e2m1_sr(almost, 0)] == 1.0 and GRID[oracle.e2m1_sr(almost, 1)] == 1.5
 
 
 # ----------------------------------------------------------------- Hadamard
