@@ -51,6 +51,11 @@ def _declare(L):
     L.quartet_ref_sign_word.argtypes = [_u64]
     L.quartet_ref_hadamard32.argtypes = [_p, _u32]
     L.quartet_ref_quant_fwd.argtypes = [_p, _i64, _i64, _i64, ctypes.c_int, _p, _p, _p]
+    L.quartet_ref_quant_fwd_rows.argtypes = [_p, _i64, _i64, _i64, ctypes.c_int, _i64, _i64, _p, _p, _p]
+    L.quartet_ref_quant_bwd_sr_rows.argtypes = [_p, _i64, _i64, _i64, ctypes.c_int, _u32, _u64, _u32,
+                                                ctypes.c_int, _i64, _i64, _p, _p]
+    L.quartet_ref_requant_transpose_sr_rows.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u32,
+                                                        ctypes.c_int, _i64, _i64, _p, _p]
     L.quartet_ref_quant_bwd_sr.argtypes = [_p, _i64, _i64, _i64, ctypes.c_int, _u32, _u64, _u32,
                                            ctypes.c_int, _p, _p]
     L.quartet_ref_requant_transpose_sr.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u32,
@@ -135,41 +140,58 @@ def _logical_shape(x, transpose):
     return (x.shape[1], x.shape[0]) if transpose else (x.shape[0], x.shape[1])
 
 
-def quant_fwd(x_bf16, transpose=False, want_mask=True):
-    """Forward (QuEST) quantizer.  Returns codes [rows,k/2] u8, scales [rows,k/32] u8, mask u32."""
-    x = _c(x_bf16, np.uint16)
-    rows, k = _logical_shape(x, transpose)
-    codes = np.zeros((rows, k // 2), dtype=np.uint8)
-    scales = np.zeros((rows, k // G), dtype=np.uint8)
-    mask = np.zeros((rows, k // G), dtype=np.uint32) if want_mask else None
-    _ok(lib().quartet_ref_quant_fwd(_ptr(x), rows, k, x.shape[1], int(bool(transpose)),
-                                    _ptr(codes), _ptr(scales), _ptr(mask)), "quant_fwd")
-    return codes, scales, mask
+def _slab(rows_range, rows):
+    r0, r1 = (0, rows) if rows_range is None else rows_range
+    return int(r0), int(r1)
 
 
-def quant_bwd_sr(x_bf16, sign_word, seed, stream_id, rounding=0, transpose=False):
-    """Backward quantizer (randomized Hadamard, AbsMax, 3/4, SR or RTN)."""
+def quant_fwd(x_bf16, transpose=False, want_mask=True, rows_range=None):
+    """Forward (QuEST) quantizer.  Returns codes [rows,k/2] u8, scales [rows,k/32] u8, mask u32.
+    rows_range=(begin,end) computes only those logical rows and returns just that slab."""
     x = _c(x_bf16, np.uint16)
     rows, k = _logical_shape(x, transpose)
-    codes = np.zeros((rows, k // 2), dtype=np.uint8)
-    scales = np.zeros((rows, k // G), dtype=np.uint8)
-    _ok(lib().quartet_ref_quant_bwd_sr(_ptr(x), rows, k, x.shape[1], int(bool(transpose)),
-                                       int(sign_word), int(seed), int(stream_id), int(rounding),
-                                       _ptr(codes), _ptr(scales)), "quant_bwd_sr")
+    r0, r1 = _slab(rows_range, rows)
+    n = r1 - r0
+    # slab outputs are written at full-matrix positions: hand the C code pointers shifted back by r0 rows
+    cs = np.zeros((n, k // 2), dtype=np.uint8)
+    ss = np.zeros((n, k // G), dtype=np.uint8)
+    ms = np.zeros((n, k // G), dtype=np.uint32) if want_mask else None
+    off = lambda a, per_row: None if a is None else ctypes.c_void_p(a.ctypes.data - r0 * per_row * a.itemsize)
+    _ok(lib().quartet_ref_quant_fwd_rows(_ptr(x), rows, k, x.shape[1], int(bool(transpose)), r0, r1,
+                                         off(cs, k // 2), off(ss, k // G), off(ms, k // G)), "quant_fwd")
+    return cs, ss, ms
+
+
+def quant_bwd_sr(x_bf16, sign_word, seed, stream_id, rounding=0, transpose=False, rows_range=None):
+    """Backward quantizer (randomized Hadamard, AbsMax, 3/4, SR or RTN).  rows_range as in quant_fwd."""
+    x = _c(x_bf16, np.uint16)
+    rows, k = _logical_shape(x, transpose)
+    r0, r1 = _slab(rows_range, rows)
+    n = r1 - r0
+    codes = np.zeros((n, k // 2), dtype=np.uint8)
+    scales = np.zeros((n, k // G), dtype=np.uint8)
+    off = lambda a, per_row: ctypes.c_void_p(a.ctypes.data - r0 * per_row * a.itemsize)
+    _ok(lib().quartet_ref_quant_bwd_sr_rows(_ptr(x), rows, k, x.shape[1], int(bool(transpose)),
+                                            int(sign_word), int(seed), int(stream_id), int(rounding), r0, r1,
+                                            off(codes, k // 2), off(scales, k // G)), "quant_bwd_sr")
     return codes, scales
 
 
-def requant_transpose_sr(src_codes, src_scales, sign_word, seed, stream_id, rounding=0):
+def requant_transpose_sr(src_codes, src_scales, sign_word, seed, stream_id, rounding=0, rows_range=None):
     """src is MXFP4 [k, rows] (codes [k, rows/2]); returns the backward quantization of its
-    decoded transpose: codes [rows, k/2], scales [rows, k/32]."""
+    decoded transpose: codes [rows, k/2], scales [rows, k/32].  rows_range as in quant_fwd."""
     sc = _c(src_codes, np.uint8)
     ss = _c(src_scales, np.uint8)
     k, rows = sc.shape[0], sc.shape[1] * 2
-    codes = np.zeros((rows, k // 2), dtype=np.uint8)
-    scales = np.zeros((rows, k // G), dtype=np.uint8)
-    _ok(lib().quartet_ref_requant_transpose_sr(_ptr(sc), _ptr(ss), rows, k, int(sign_word),
-                                               int(seed), int(stream_id), int(rounding),
-                                               _ptr(codes), _ptr(scales)), "requant_transpose_sr")
+    r0, r1 = _slab(rows_range, rows)
+    n = r1 - r0
+    codes = np.zeros((n, k // 2), dtype=np.uint8)
+    scales = np.zeros((n, k // G), dtype=np.uint8)
+    off = lambda a, per_row: ctypes.c_void_p(a.ctypes.data - r0 * per_row * a.itemsize)
+    _ok(lib().quartet_ref_requant_transpose_sr_rows(_ptr(sc), _ptr(ss), rows, k, int(sign_word),
+                                                    int(seed), int(stream_id), int(rounding), r0, r1,
+                                                    off(codes, k // 2), off(scales, k // G)),
+        "requant_transpose_sr")
     return codes, scales
 
 

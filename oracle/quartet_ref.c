@@ -268,13 +268,26 @@ static int check_quant_args(int64_t rows, int64_t k) {
 
 /* codes [rows x k/2], scales [rows x k/32], mask [rows x k/32] (bit i of word j <-> element 32j+i;
  * may be NULL).  transpose = 0: A = x[rows x ldx];  transpose = 1: A = x^T, x stored [k x ldx]. */
+int quartet_ref_quant_fwd_rows(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                               int64_t row_begin, int64_t row_end,
+                               uint8_t *codes, uint8_t *scales, uint32_t *mask);
+
 int quartet_ref_quant_fwd(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
                           uint8_t *codes, uint8_t *scales, uint32_t *mask) {
+    return quartet_ref_quant_fwd_rows(x, rows, k, ldx, transpose, 0, rows, codes, scales, mask);
+}
+
+/* Only logical rows [row_begin, row_end) are computed; outputs keep their full-matrix indexing, so
+ * large cases can be checked on slabs. */
+int quartet_ref_quant_fwd_rows(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                               int64_t row_begin, int64_t row_end,
+                               uint8_t *codes, uint8_t *scales, uint32_t *mask) {
     if (check_quant_args(rows, k)) return -1;
+    if (row_begin < 0 || row_end > rows || row_begin > row_end) return -1;
     Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
     int64_t gk = k / G;
 #pragma omp parallel for schedule(static)
-    for (int64_t r = 0; r < rows; ++r) {
+    for (int64_t r = row_begin; r < row_end; ++r) {
         for (int64_t g = 0; g < gk; ++g) {
             float h[G];
             uint8_t code[G], sb;
@@ -319,11 +332,12 @@ static void quant_bwd_group(float h[G], uint32_t sign_word, int rounding, uint64
 }
 
 static int quant_bwd_src(const Src *s, uint32_t sign_word, uint64_t seed, uint32_t stream_id,
-                         int rounding, uint8_t *codes, uint8_t *scales) {
+                         int rounding, int64_t row_begin, int64_t row_end, uint8_t *codes, uint8_t *scales) {
     int64_t rows = s->rows, k = s->k, gk = k / G;
     if (rounding != 0 && rounding != 1) return -1;
+    if (row_begin < 0 || row_end > rows || row_begin > row_end) return -1;
 #pragma omp parallel for schedule(static)
-    for (int64_t r = 0; r < rows; ++r) {
+    for (int64_t r = row_begin; r < row_end; ++r) {
         for (int64_t g = 0; g < gk; ++g) {
             float h[G];
             uint8_t code[G], sb;
@@ -342,7 +356,16 @@ int quartet_ref_quant_bwd_sr(const uint16_t *x, int64_t rows, int64_t k, int64_t
                              uint8_t *codes, uint8_t *scales) {
     if (check_quant_args(rows, k)) return -1;
     Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
-    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, codes, scales);
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, 0, rows, codes, scales);
+}
+
+/* slab variant: logical rows [row_begin, row_end) only, full-matrix indexing and draw positions */
+int quartet_ref_quant_bwd_sr_rows(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                                  uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
+                                  int64_t row_begin, int64_t row_end, uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k)) return -1;
+    Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, row_begin, row_end, codes, scales);
 }
 
 /* Source is an MXFP4 tensor stored [k x rows] (its groups run along `rows`); the output is the
@@ -352,7 +375,16 @@ int quartet_ref_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *sr
                                      uint32_t stream_id, int rounding, uint8_t *codes, uint8_t *scales) {
     if (check_quant_args(rows, k) || (rows % G) != 0) return -1;
     Src s = {SRC_MX_T, 0, 0, src_codes, src_scales, rows, k};
-    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, codes, scales);
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, 0, rows, codes, scales);
+}
+
+int quartet_ref_requant_transpose_sr_rows(const uint8_t *src_codes, const uint8_t *src_scales,
+                                          int64_t rows, int64_t k, uint32_t sign_word, uint64_t seed,
+                                          uint32_t stream_id, int rounding, int64_t row_begin, int64_t row_end,
+                                          uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k) || (rows % G) != 0) return -1;
+    Src s = {SRC_MX_T, 0, 0, src_codes, src_scales, rows, k};
+    return quant_bwd_src(&s, sign_word, seed, stream_id, rounding, row_begin, row_end, codes, scales);
 }
 
 /* ----------------------------------------------------------------- decode */

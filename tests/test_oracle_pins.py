@@ -373,6 +373,24 @@ def test_requant_transpose_equals_quantizing_the_decoded_transpose():
         assert a[0].shape == (96, 32) and a[1].shape == (96, 2)
 
 
+def test_slab_variants_equal_the_full_computation():
+    # the row-range entry points used for full-size checks index codes, scales and draws as the full call
+    x = synth.small_matrix(5, 96, 160, "heavy")
+    full = oracle.quant_bwd_sr(x, 0xABCDEF01, 9, 2, 0)
+    slab = oracle.quant_bwd_sr(x, 0xABCDEF01, 9, 2, 0, rows_range=(17, 40))
+    assert np.array_equal(slab[0], full[0][17:40]) and np.array_equal(slab[1], full[1][17:40])
+    fullt = oracle.quant_bwd_sr(x, 0xABCDEF01, 9, 2, 0, transpose=True)
+    slabt = oracle.quant_bwd_sr(x, 0xABCDEF01, 9, 2, 0, transpose=True, rows_range=(100, 160))
+    assert np.array_equal(slabt[0], fullt[0][100:160]) and np.array_equal(slabt[1], fullt[1][100:160])
+    ff = oracle.quant_fwd(x)
+    fs = oracle.quant_fwd(x, rows_range=(3, 9))
+    assert all(np.array_equal(a, b[3:9]) for a, b in zip(fs, ff))
+    sc, ss, _ = oracle.quant_fwd(x)
+    rf = oracle.requant_transpose_sr(sc, ss, 1, 2, 3, 0)
+    rs = oracle.requant_transpose_sr(sc, ss, 1, 2, 3, 0, rows_range=(32, 64))
+    assert np.array_equal(rs[0], rf[0][32:64]) and np.array_equal(rs[1], rf[1][32:64])
+
+
 # --------------------------------------------------------------------- GEMM
 
 def test_dequant_matches_table_lookup():
