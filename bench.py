@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-kind time breakdown to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run a plain 1 GiB elementwise copy kernel (torch.mul by 1), the known-size "
+                         "reference that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
 
@@ -116,6 +119,19 @@ def quant_sweep(q, torch, synth):
     return out
 
 
+def recorded_traffic(config):
+    """HBM bytes per GEMM launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+    plain copy kernel of known size); read from the committed summary, None if it is not there."""
+    path = os.path.join(ROOT, "profiles", f"gemm_config{config}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -182,7 +198,7 @@ def main():
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
         "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_kernel (all three GEMMs of every layer)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_FP4_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_FP4_TFLOPS, 4), "traffic": recorded_traffic(args.config),
                      "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms)},
         "kernel_time_share": {k: round(sum(v) / (dt * 1e3), 4) for k, v in sorted(per_kind.items())},
     }
@@ -190,6 +206,13 @@ def main():
         for k, v in sorted(per_kind.items()):
             print(f"  {k:10s} launches {len(v):4d} total {sum(v):9.3f} ms  ({sum(v) / (dt * 1e3) * 100:5.1f} % of wall)",
                   file=sys.stderr)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     if args.quant_sweep:
         del layers, ws
         torch.cuda.empty_cache()

@@ -40,7 +40,7 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
     if (transpose && (rows % 8) != 0) return QUARTET_EINVAL;
     if (rows > 0 && (k / 32) > kMaxGroups / (rows > 0 ? rows : 1)) return QUARTET_ENOTSUP;
     if (rows * (k / 32) >= kMaxGroups) return QUARTET_ENOTSUP;
-    if (transpose && k / 256 > 65535) return QUARTET_ENOTSUP;
+    if ((k + 255) / 256 > 65535) return QUARTET_ENOTSUP;
     return QUARTET_OK;
 }
 

@@ -94,65 +94,69 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
     v[6] = u2f(q.w << 16); v[7] = u2f(q.w & 0xFFFF0000u);
 }
 
-// ------------------------------------------------------------------ row mode, contiguous input
-// x is a flat array of n_groups groups (rows*k/32, ldx == k).  Block = 4 waves, a wave per 64 groups.
+// ------------------------------------------------------------------ row mode
+// Block = 8 rows x 32 groups (four 256-element K-quads, 2 KB of bf16 per row).  Wave w owns rows
+// 2w, 2w+1; lane l the group l%32 of row l/32.  Loads are lane-contiguous 16-byte chunks, swizzled
+// through LDS so each lane ends up with its own group's 64 bytes.  Codes leave as 512 contiguous
+// bytes per row, mask words as 128; the 256 scale bytes of the block are exchanged through LDS and
+// leave as whole 32-byte runs of the scale tiles (8 rows x one dword), never as single bytes.
 template <int MODE, bool MASK>
 __global__ void __launch_bounds__(256)
-quant_row_flat_kernel(const uint4* __restrict__ x, uint32_t n_groups, uint32_t gk, FastDiv div_gk,
-                      uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
-                      SrParams p) {
+quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
+                 uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
+                 SrParams p, uint32_t k_blocks, FastDiv div_k_blocks) {
     __shared__ uint4 stage[4][256];
+    __shared__ uint32_t s_scale[64];
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-    const uint32_t base_group = (blockIdx.x * 4u + wave) * 64u;
+    // consecutive blocks walk along K inside the same 8 rows, so the blocks in flight cover one
+    // contiguous stretch of the input
+    const uint32_t row_set = fast_div(blockIdx.x, div_k_blocks);
+    const uint32_t row0 = row_set * 8u, kq0 = (blockIdx.x - row_set * k_blocks) * 4u, kqs = (gk + 7u) >> 3;
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
-        uint32_t c = 64u * j + lane;                       // 16-byte chunk inside the wave's 4 KB
-        uint32_t g = base_group + (c >> 2);
-        uint4 q = (g < n_groups) ? x[(size_t)base_group * 4u + c] : zero;
-        uint32_t pos = (c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u));
-        stage[wave][pos] = q;
+        uint32_t c = 64u * j + lane;                       // 16-byte chunk inside the wave's 2 rows x 2 KB
+        uint32_t r = row0 + wave * 2u + (c >> 7), g = kq0 * 8u + ((c & 127u) >> 2);
+        uint4 q = zero;
+        if (r < rows && g < gk)
+            q = *reinterpret_cast<const uint4*>(x + (size_t)r * ldx + (size_t)kq0 * 256u + (c & 127u) * 8u);
+        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = q;
     }
     __syncthreads();
     float v[32];
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
-        uint32_t pos = 4u * lane + (j ^ ((lane >> 1) & 3u));
-        uint4 q = stage[wave][pos];
+        uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 1) & 3u))];
         unpack_bf16x8(q, &v[8 * j]);
     }
-    const uint32_t g = base_group + lane;
+    const uint32_t row_local = wave * 2u + (lane >> 5), gi = lane & 31u;
+    const uint32_t row = row0 + row_local, g = kq0 * 8u + gi;
     uint4 out;
     uint32_t sb, mw;
-    quantize_group<MODE>(v, p, (uint64_t)g * 4u, out, sb, mw);
-    if (g < n_groups) {
-        const uint32_t row = fast_div(g, div_gk), gi = g - row * gk;
-        codes[g] = out;
-        scales[scale_tile_offset(row, gi, (gk + 7u) >> 3)] = (uint8_t)sb;
-        if (MASK) mask[g] = mw;
+    quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 4u, out, sb, mw);
+    // scale byte of (row, group gi) -> position of the tiled layout inside the block's 256 bytes:
+    // [K-quad gi/8][h = gi%2][row_local][p = (gi%8)/2]
+    reinterpret_cast<uint8_t*>(s_scale)[(((gi >> 3) * 2u + (gi & 1u)) * 8u + row_local) * 4u + ((gi & 7u) >> 1)] = (uint8_t)sb;
+    if (row < rows && g < gk) {
+        const size_t gidx = (size_t)row * gk + g;
+        codes[gidx] = out;
+        if (MASK) mask[gidx] = mw;
     }
-}
-
-// ------------------------------------------------------------------ row mode, strided rows
-template <int MODE, bool MASK>
-__global__ void __launch_bounds__(256)
-quant_row_strided_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
-                         uint4* __restrict__ codes, uint8_t* __restrict__ scales,
-                         uint32_t* __restrict__ mask, SrParams p) {
-    const uint32_t g = blockIdx.x * 256u + threadIdx.x;   // group inside the row
-    if (g >= gk) return;
-    for (uint32_t row = blockIdx.y; row < rows; row += gridDim.y) {
-        const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)row * ldx + (size_t)g * 32u);
-        float v[32];
+    __syncthreads();
+    if (threadIdx.x < 64u) {
+        const uint32_t t = threadIdx.x, kql = t >> 4, h = (t >> 3) & 1u, rl = t & 7u;
+        const uint32_t r = row0 + rl, kq = kq0 + kql;
+        if (r < rows && kq * 8u + h < gk) {
+            uint8_t* dst = scales + scale_tile_offset(r, kq * 8u + h, kqs);   // dword of (row, h) in tile kq
+            const uint32_t w = s_scale[t];
+            if (kq * 8u + 8u <= gk) {
+                *reinterpret_cast<uint32_t*>(dst) = w;
+            } else {                                         // ragged last K-quad: only the bytes that exist
 #pragma unroll
-        for (int j = 0; j < 4; ++j) unpack_bf16x8(src[j], &v[8 * j]);
-        const uint64_t gi = (uint64_t)row * gk + g;
-        uint4 out;
-        uint32_t sb, mw;
-        quantize_group<MODE>(v, p, gi * 4u, out, sb, mw);
-        codes[gi] = out;
-        scales[scale_tile_offset(row, g, (gk + 7u) >> 3)] = (uint8_t)sb;
-        if (MASK) mask[gi] = mw;
+                for (uint32_t q = 0; q < 4; ++q)
+                    if (kq * 8u + 2u * q + h < gk) dst[q] = (uint8_t)(w >> (8u * q));
+            }
+        }
     }
 }
 
@@ -300,29 +304,16 @@ static FastDiv make_fast_div(uint32_t d) {
 template <int MODE>
 static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
                              uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
-    const uint64_t n_groups = (uint64_t)rows * (uint64_t)(k / 32);
-    if (n_groups == 0) return hipSuccess;
-    if (ldx == k) {
-        uint32_t tiles = (uint32_t)((n_groups + 63) / 64);
-        dim3 grid((tiles + 3) / 4), block(256);
-        if (mask)
-            hipLaunchKernelGGL((quant_row_flat_kernel<MODE, true>), grid, block, 0, st, (const uint4*)x,
-                               (uint32_t)n_groups, (uint32_t)(k / 32), make_fast_div((uint32_t)(k / 32)),
-                               (uint4*)codes, scales, mask, p);
-        else
-            hipLaunchKernelGGL((quant_row_flat_kernel<MODE, false>), grid, block, 0, st, (const uint4*)x,
-                               (uint32_t)n_groups, (uint32_t)(k / 32), make_fast_div((uint32_t)(k / 32)),
-                               (uint4*)codes, scales, mask, p);
-    } else {
-        uint32_t gk = (uint32_t)(k / 32);
-        dim3 grid((gk + 255) / 256, (uint32_t)(rows < 65535 ? rows : 65535)), block(256);
-        if (mask)
-            hipLaunchKernelGGL((quant_row_strided_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)x,
-                               (uint32_t)rows, gk, ldx, (uint4*)codes, scales, mask, p);
-        else
-            hipLaunchKernelGGL((quant_row_strided_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)x,
-                               (uint32_t)rows, gk, ldx, (uint4*)codes, scales, mask, p);
-    }
+    if (rows == 0 || k == 0) return hipSuccess;
+    const uint32_t gk = (uint32_t)(k / 32);
+    const uint32_t k_blocks = (gk + 31) / 32;
+    dim3 grid((uint32_t)((rows + 7) / 8) * k_blocks), block(256);
+    if (mask)
+        hipLaunchKernelGGL((quant_row_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
+                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
+    else
+        hipLaunchKernelGGL((quant_row_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
+                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
     return hipGetLastError();
 }
 
