@@ -25,7 +25,7 @@ grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t
     for (uint32_t j = 0; j < 8; ++j) {
         uint32_t c = 64u * j + lane;                       // 16-byte chunk in the wave's 8 KB
         uint32_t grp = base_group + (c >> 3);
-        uint4 q = (grp < n_groups) ? g[(size_t)base_group * 8u + c] : zero;
+        uint4 q = (grp < n_groups) ? load_stream16(&g[(size_t)base_group * 8u + c]) : zero;
         stage[wave][(c & ~7u) | ((c & 7u) ^ ((c >> 3) & 7u))] = q;
     }
     __syncthreads();

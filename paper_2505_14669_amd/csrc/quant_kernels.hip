@@ -119,7 +119,7 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
         uint32_t r = row0 + wave * 2u + (c >> 7), g = kq0 * 8u + ((c & 127u) >> 2);
         uint4 q = zero;
         if (r < rows && g < gk)
-            q = *reinterpret_cast<const uint4*>(x + (size_t)r * ldx + (size_t)kq0 * 256u + (c & 127u) * 8u);
+            q = load_stream16(x + (size_t)r * ldx + (size_t)kq0 * 256u + (c & 127u) * 8u);
         stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = q;
     }
     __syncthreads();
@@ -139,8 +139,8 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
     reinterpret_cast<uint8_t*>(s_scale)[(((gi >> 3) * 2u + (gi & 1u)) * 8u + row_local) * 4u + ((gi & 7u) >> 1)] = (uint8_t)sb;
     if (row < rows && g < gk) {
         const size_t gidx = (size_t)row * gk + g;
-        codes[gidx] = out;
-        if (MASK) mask[gidx] = mw;
+        store_stream16(&codes[gidx], out);
+        if (MASK) store_stream4(&mask[gidx], mw);
     }
     __syncthreads();
     if (threadIdx.x < 64u) {
@@ -191,7 +191,7 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 uint32_t w = 0u;
-                if (ok) w = *reinterpret_cast<const uint32_t*>(x + (size_t)(grp * 32u + i) * ldx + col);
+                if (ok) w = load_stream4(x + (size_t)(grp * 32u + i) * ldx + col);
                 v0[i] = u2f(w << 16);
                 v1[i] = u2f(w & 0xFFFF0000u);
             }
@@ -236,7 +236,7 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
         uint32_t r = col0 + lc, grp = grp0 + part;
         if (r < rows && grp < gk) {
             uint4 q = s_codes[lc * 8u + (part ^ ((lc >> 1) & 7u))];
-            *reinterpret_cast<uint4*>(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u) = q;
+            store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, q);
         }
     }
     if (MASK) {
