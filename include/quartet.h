@@ -145,6 +145,20 @@ int quartet_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
                        void *d, int d_dtype, int64_t ldd, void *stream);
 
 /*
+ * GEMM_LP with the gradient epilogue applied in the same kernel (Algorithm 1 Backward:
+ * dx = 16/9 H_g^-1(dx_q . M_x), dW likewise):
+ *   D[m x n] = scale * H_32_along_n( (sum_k dec(A)[m,k] dec(B)[n,k]) . mask )
+ * Operands and limits as quartet_mxfp4_gemm, plus n % 32 == 0; mask is [m x n/32] words (bit i of
+ * word [r, g] = column 32 g + i) or NULL (all ones).  The result equals quartet_mxfp4_gemm with
+ * alpha = 1 into fp32 followed by quartet_grad_epilogue, bit for bit, without the fp32
+ * intermediate ever reaching memory.
+ */
+int quartet_mxfp4_gemm_grad(const uint8_t *a_codes, const uint8_t *a_scales,
+                            const uint8_t *b_codes, const uint8_t *b_scales,
+                            int64_t m, int64_t n, int64_t k, const uint32_t *mask, float scale,
+                            void *d, int d_dtype, int64_t ldd, void *stream);
+
+/*
  * Gradient epilogue (Algorithm 1 Backward: 16/9 H_g^-1(G . M)):
  *   out[m x n] = scale * H_32_along_n( g . mask ),  g fp32 [m x n], mask [m x n/32] or NULL (all ones).
  * g . mask keeps g where the bit is set and is +0 elsewhere; H_32 is its own inverse; fp32 steps

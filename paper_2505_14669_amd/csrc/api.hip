@@ -85,14 +85,13 @@ size_t scale_bytes(int64_t rows, int64_t k) {
 }
 
 struct BwdWorkspace {
-    size_t g_codes, g_scales, b_codes, b_scales, acc, total;
+    size_t g_codes, g_scales, b_codes, b_scales, total;
 };
 
 BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
     BwdWorkspace w;
     size_t to = (size_t)tokens * (size_t)out;
     size_t bmax = (size_t)in * (size_t)(out > tokens ? out : tokens);
-    size_t amax = (size_t)in * (size_t)(tokens > out ? tokens : out);
     size_t gs = scale_bytes(tokens, out), gts = scale_bytes(out, tokens);
     size_t bs = scale_bytes(in, out), bts = scale_bytes(in, tokens);
     size_t off = 0;
@@ -100,7 +99,6 @@ BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
     w.g_scales = off; off += align256(gs > gts ? gs : gts);
     w.b_codes = off; off += align256(bmax / 2);
     w.b_scales = off; off += align256(bs > bts ? bs : bts);
-    w.acc = off; off += align256(amax * 4);
     w.total = off;
     return w;
 }
@@ -210,10 +208,9 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
-int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
-                       const uint8_t* b_codes, const uint8_t* b_scales,
-                       int64_t m, int64_t n, int64_t k, float alpha,
-                       void* d, int d_dtype, int64_t ldd, void* stream) {
+static int check_gemm_args(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                           const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, const void* d, int d_dtype,
+                           int64_t ldd) {
     if (!a_codes || !a_scales || !b_codes || !b_scales || !d) return QUARTET_EINVAL;
     if (!aligned16(a_codes) || !aligned16(b_codes) || !aligned16(d)) return QUARTET_EINVAL;
     if (m < 0 || n < 0 || k < 0 || (k % 32) != 0 || ldd < n) return QUARTET_EINVAL;
@@ -222,9 +219,32 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     if (m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31) || k > ((int64_t)1 << 23)) return QUARTET_ENOTSUP;
     if (((m + 127) / 128) * ((n + 127) / 128) >= ((int64_t)1 << 31)) return QUARTET_ENOTSUP;
     if ((reinterpret_cast<uintptr_t>(a_scales) | reinterpret_cast<uintptr_t>(b_scales)) & 3u) return QUARTET_EINVAL;
+    return QUARTET_OK;
+}
+
+int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                       const uint8_t* b_codes, const uint8_t* b_scales,
+                       int64_t m, int64_t n, int64_t k, float alpha,
+                       void* d, int d_dtype, int64_t ldd, void* stream) {
+    int rc = check_gemm_args(a_codes, a_scales, b_codes, b_scales, m, n, k, d, d_dtype, ldd);
+    if (rc) return rc;
     ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
     hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
-                                        d_dtype == QUARTET_DTYPE_BF16, ldd, (hipStream_t)stream);
+                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 0, nullptr, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_mxfp4_gemm_grad(const uint8_t* a_codes, const uint8_t* a_scales,
+                            const uint8_t* b_codes, const uint8_t* b_scales,
+                            int64_t m, int64_t n, int64_t k, const uint32_t* mask, float scale,
+                            void* d, int d_dtype, int64_t ldd, void* stream) {
+    int rc = check_gemm_args(a_codes, a_scales, b_codes, b_scales, m, n, k, d, d_dtype, ldd);
+    if (rc) return rc;
+    if ((n % 32) != 0) return QUARTET_EINVAL;
+    if (mask && (reinterpret_cast<uintptr_t>(mask) & 3u)) return QUARTET_EINVAL;
+    ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
+    hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, scale, d,
+                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 1, mask, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
@@ -292,7 +312,6 @@ int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t 
     uint8_t* base = static_cast<uint8_t*>(workspace);
     uint8_t *g_codes = base + w.g_codes, *g_scales = base + w.g_scales;
     uint8_t *b_codes = base + w.b_codes, *b_scales = base + w.b_scales;
-    float* acc = reinterpret_cast<float*>(base + w.acc);
     const uint32_t sw = quartet_sign_word(seed);
     const float c169 = 16.0f / 9.0f;
     int rc;
@@ -301,18 +320,14 @@ int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t 
     if (rc) return rc;
     rc = quartet_requant_transpose_sr(wq_codes, wq_scales, in, out, sw, seed, 1u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
-    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
-    if (rc) return rc;
-    rc = quartet_grad_epilogue(acc, x_mask, tokens, in, c169, dx, grad_dtype, stream);
+    rc = quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, tokens, in, out, x_mask, c169, dx, grad_dtype, in, stream);
     if (rc) return rc;
     // dW = 16/9 H( (Q(dy^T) Q(X_q^T)^T) . M_w ), inner dimension = tokens
     rc = quartet_quant_bwd_sr(dy_bf16, out, tokens, out, 1, sw, seed, 2u, rounding, g_codes, g_scales, stream);
     if (rc) return rc;
     rc = quartet_requant_transpose_sr(xq_codes, xq_scales, in, tokens, sw, seed, 3u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
-    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
-    if (rc) return rc;
-    return quartet_grad_epilogue(acc, w_mask, out, in, c169, dw, grad_dtype, stream);
+    return quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, out, in, tokens, w_mask, c169, dw, grad_dtype, in, stream);
 }
 
 }  // extern "C"

@@ -45,6 +45,118 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here reaches
 
+// Epilogue of both kernels.  The wave's accumulator tile goes through LDS one 32-column slice at a
+// time and comes back with 8 consecutive lanes holding the 32 columns of one row (4 each): a
+// store instruction then writes 8 whole 128-byte lines.  The slice is exactly one Hadamard
+// group, so with FUSED the gradient epilogue of Algorithm 1 Backward,
+// D = alpha * H_32_along_n(acc . M), is applied on the way: mask select, butterflies of stride 1
+// and 2 inside the lane and of stride 4, 8, 16 between the 8 lanes (the lower partner forms a + b,
+// the upper a - b = b' + (-a'), bit-identical to the in-register transform), the normalization,
+// then the scale.  Lane i of the 8 holds 4-column chunk i ^ (i & 4 ? 3 : 0), which makes the three
+// partners lane ^ 1, lane ^ 2 and 7 - lane: all reachable by DPP, none through LDS.
+// wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
+constexpr uint32_t kEpiStride = 36;   // floats per LDS row (144 bytes: 16-byte aligned, rows spread over banks)
+
+template <int DPP_CTRL>
+__device__ __forceinline__ float butterfly_across(float own, uint32_t upper_sign) {
+    float other = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own), DPP_CTRL, 0xF, 0xF, true));
+    return other + __uint_as_float(__float_as_uint(own) ^ upper_sign);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141;
+
+// FULL: the whole wave tile lies inside D and rows are 16-byte aligned, so nothing is predicated.
+template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
+__device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
+                                                const uint32_t* mask, float alpha, uint32_t row_base,
+                                                uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+    constexpr uint32_t ITERS = TM * 4;   // 8 rows per pass
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
+    const uint32_t up4 = (c & 1u) << 31, up8 = (c & 2u) << 30, up16 = (c & 4u) << 29;   // sign flip of the upper partner
+    const bool wide = FULL || (ldd & 3u) == 0u;   // every 4-column chunk starts 16-byte (fp32) / 8-byte (bf16) aligned
+    const uint32_t mask_ld = n >> 5;
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t gcol = col_base + j * 32u;
+        uint32_t mw[ITERS];
+        if (FUSED) {
+#pragma unroll
+            for (uint32_t it = 0; it < ITERS; ++it) {
+                const uint32_t grow = row_base + it * 8u + sub;
+                if (FULL) mw[it] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
+                else mw[it] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
+            }
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+            for (uint32_t r = 0; r < 16; ++r)
+                wbuf[(i * 32u + (r >> 2) * 8u + lhalf * 4u + (r & 3u)) * kEpiStride + lrow] = acc[i][j][r];
+        float4 slice[ITERS];   // all reads in flight before the first use: one wave per SIMD hides no LDS latency
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it)
+            slice[it] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * kEpiStride + 4u * c]);
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it) {
+            const uint32_t rr = it * 8u + sub, grow = row_base + rr;
+            float v0 = slice[it].x, v1 = slice[it].y, v2 = slice[it].z, v3 = slice[it].w;
+            if (FUSED) {
+                // bit clear -> +0: and with the bit spread over the word
+                const int32_t bits = (int32_t)(mw[it] >> (4u * c));
+                v0 = __uint_as_float(__float_as_uint(v0) & (uint32_t)((bits << 31) >> 31));
+                v1 = __uint_as_float(__float_as_uint(v1) & (uint32_t)((bits << 30) >> 31));
+                v2 = __uint_as_float(__float_as_uint(v2) & (uint32_t)((bits << 29) >> 31));
+                v3 = __uint_as_float(__float_as_uint(v3) & (uint32_t)((bits << 28) >> 31));
+                const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
+                v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
+                v0 = butterfly_across<kDppXor1>(v0, up4); v1 = butterfly_across<kDppXor1>(v1, up4);   // stride 4
+                v2 = butterfly_across<kDppXor1>(v2, up4); v3 = butterfly_across<kDppXor1>(v3, up4);
+                v0 = butterfly_across<kDppXor2>(v0, up8); v1 = butterfly_across<kDppXor2>(v1, up8);   // stride 8
+                v2 = butterfly_across<kDppXor2>(v2, up8); v3 = butterfly_across<kDppXor2>(v3, up8);
+                v0 = butterfly_across<kDppHalfMirror>(v0, up16); v1 = butterfly_across<kDppHalfMirror>(v1, up16);   // stride 16
+                v2 = butterfly_across<kDppHalfMirror>(v2, up16); v3 = butterfly_across<kDppHalfMirror>(v3, up16);
+                v0 = v0 * kInvSqrt32; v1 = v1 * kInvSqrt32; v2 = v2 * kInvSqrt32; v3 = v3 * kInvSqrt32;
+            }
+            v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
+            if (!FULL && grow >= m) continue;
+            const uint32_t col = gcol + 4u * c;
+            const size_t at = (size_t)grow * ldd + col;
+            if (OUT_BF16) {
+                uint16_t* dst = static_cast<uint16_t*>(d) + at;
+                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                } else {
+                    if (col < n) dst[0] = (uint16_t)h0;
+                    if (col + 1u < n) dst[1] = (uint16_t)h1;
+                    if (col + 2u < n) dst[2] = (uint16_t)h2;
+                    if (col + 3u < n) dst[3] = (uint16_t)h3;
+                }
+            } else {
+                float* dst = static_cast<float*>(d) + at;
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                } else {
+                    if (col < n) dst[0] = v0;
+                    if (col + 1u < n) dst[1] = v1;
+                    if (col + 2u < n) dst[2] = v2;
+                    if (col + 3u < n) dst[3] = v3;
+                }
+            }
+        }
+    }
+}
+
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
+__device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
+                                           const uint32_t* mask, float alpha, uint32_t row_base,
+                                           uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+    const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n &&
+                      (!FUSED || mask != nullptr);   // wave-uniform
+    if (full) store_tile_body<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
+    else store_tile_body<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
+}
+
 // Block = 4 waves (2 x 2), wave tile (TM*32) x (TN*32), block tile BM x BN = (2*TM*32) x (2*TN*32).
 // Per stage (256 K-elements) a block moves BM + BN rows of 128 code bytes straight from global
 // memory into LDS (buffer_load ... lds, 16 bytes per lane, lane l landing at base + 16 l), into the
@@ -53,16 +165,15 @@ constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here 
 // makes the 16-byte fragment reads bank-conflict free.  One wave runs per SIMD, so the instruction
 // stream is software-pipelined by hand: fragments of K-step s+1 are read, and a quarter of the next
 // stage's loads is issued, between the matrix-core instructions of K-step s.
-template <int TM, int TN, bool OUT_BF16>
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
 gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                   const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                   uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                  uint32_t tiles_m, uint32_t tiles_n) {
+                  const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n) {
     constexpr uint32_t BM = 2 * TM * 32, BN = 2 * TN * 32;
     constexpr uint32_t LA = BM / 32, LB = BN / 32;      // 1 KB (64 lanes x 16 B) loads per wave per stage
     constexpr uint32_t STAGE = (BM + BN) * 8;           // 16-byte chunks per LDS buffer
-    constexpr uint32_t ESIZE = OUT_BF16 ? 2 : 4;
     __shared__ uint4 lds[2 * STAGE];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -227,27 +338,10 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
 #undef QUARTET_PIPE
 #undef QUARTET_PIN_ACC
 
-    // D tile through a buffer resource: rows past m fall outside it and are dropped by the hardware;
-    // columns past n are sent out of range per lane.  The wave-uniform part of each address rides in
-    // the scalar offset, so a store costs no vector ALU work beyond the alpha multiply.
-    const uint32_t tile_bytes = ((rows_a - 1u) * ldd + rows_b) * ESIZE;
-    const __amdgpu_buffer_rsrc_t res_d = make_rsrc(static_cast<uint8_t*>(d) + ((size_t)m0 * ldd + n0) * ESIZE, tile_bytes);
-    const uint32_t lane_off = (lhalf * 4u * ldd + lrow) * ESIZE;
-#pragma unroll
-    for (uint32_t j = 0; j < TN; ++j) {
-        const uint32_t voff = (wn0 + j * 32u + lrow < rows_b) ? lane_off : kOutOfRange;
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i)
-#pragma unroll
-            for (uint32_t r = 0; r < 16; ++r) {
-                const uint32_t soff = ((wm0 + i * 32u + (r >> 2) * 8u + (r & 3u)) * ldd + wn0 + j * 32u) * ESIZE;
-                const float val = alpha * acc[i][j][r];
-                if (OUT_BF16)
-                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(val), res_d, voff, soff, 0);
-                else
-                    __builtin_amdgcn_raw_buffer_store_b32(f2u(val), res_d, voff, soff, 0);
-            }
-    }
+    // every wave is done reading the stage buffers: reuse them as the epilogue's scratch
+    __syncthreads();
+    store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
+                                        alpha, m0 + wm0, n0 + wn0, m, n, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -282,18 +376,17 @@ __device__ __forceinline__ void lds_direct_load16(v4i_t rsrc, uint32_t voff, uin
                  :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }
 
-template <bool OUT_BF16>
+template <bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
 gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                        const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                        uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                       uint32_t tiles_m, uint32_t tiles_n) {
+                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
     constexpr uint32_t D = kRing - 1;                    // prefetch distance in stages
     constexpr uint32_t LOADS = 9;                        // vector-memory operations per wave per stage
-    constexpr uint32_t ESIZE = OUT_BF16 ? 2 : 4;
     // s_waitcnt: wait until at most (D-1)*LOADS vector-memory operations are outstanding
     constexpr uint32_t KEEP = (D - 1) * LOADS;
     constexpr uint32_t WAIT_STAGE = 0x0F70u | (KEEP & 15u) | ((KEEP >> 4) << 14);
@@ -335,15 +428,16 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     // codes: load j of a wave fills chunks [j*256 + wave*64, +64) = rows j*64 + wave*16 + lane/4 of the
-    // stage (4 chunks per row); chunk c of row r is stored at r*4 + (c ^ (r/2)%4).
+    // stage (4 chunks per row); chunk c of row r is stored at r*4 + (c ^ (r/4)%4), the XOR pattern that
+    // measured conflict-free for 16-byte reads of 64-byte rows (144 B/clk/CU against 114 for (r/2)%4).
     const uint32_t drow = wave * 16u + (lane >> 2);
-    const uint32_t dcol = (lane & 3u) ^ ((drow >> 1) & 3u);
+    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
     const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
     const uint32_t gstep = 64u * kb;
     const uint32_t soff = (((wave & 1u) * 4u + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
-    // fragment reads of K-step s (0,1): chunk (2s + lhalf) ^ (row/2)%4 of row w?0 + i*32 + lrow
-    const uint32_t swz = (lrow >> 1) & 3u;
+    // fragment reads of K-step s (0,1): chunk (2s + lhalf) ^ (row/4)%4 of row w?0 + i*32 + lrow
+    const uint32_t swz = (lrow >> 2) & 3u;
     const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
     const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
     const uint32_t sb_base = CODES * 4u + 8u * 64u + (wn0 >> 5) * 64u + lane;
@@ -466,62 +560,41 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
 #undef RING_PIN_ROW
 #undef RING_FENCE
 
-    const uint32_t tile_bytes = ((rows_a - 1u) * ldd + rows_b) * ESIZE;
-    const __amdgpu_buffer_rsrc_t res_d = make_rsrc(static_cast<uint8_t*>(d) + ((size_t)m0 * ldd + n0) * ESIZE, tile_bytes);
-    const uint32_t lane_off = (lhalf * 4u * ldd + lrow) * ESIZE;
-#pragma unroll
-    for (uint32_t j = 0; j < TN; ++j) {
-        const uint32_t voff = (wn0 + j * 32u + lrow < rows_b) ? lane_off : kOutOfRange;
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i)
-#pragma unroll
-            for (uint32_t r = 0; r < 16; ++r) {
-                const uint32_t soff_d = ((wm0 + i * 32u + (r >> 2) * 8u + (r & 3u)) * ldd + wn0 + j * 32u) * ESIZE;
-                const float val = alpha * acc[i][j][r];
-                if (OUT_BF16)
-                    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16_rne(val), res_d, voff, soff_d, 0);
-                else
-                    __builtin_amdgcn_raw_buffer_store_b32(f2u(val), res_d, voff, soff_d, 0);
-            }
-    }
+    // every wave is done reading the ring (and the zero-filled stages have landed): reuse it as the
+    // epilogue's scratch
+    __builtin_amdgcn_s_barrier();
+    store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
+                                        alpha, m0 + wm0, n0 + wn0, m, n, lane);
 }
 
-static hipError_t launch_ring(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                              const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha,
-                              void* d, int d_bf16, int64_t ldd, hipStream_t st) {
+template <bool OUT_BF16, bool FUSED>
+static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                          const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
+                          int64_t ldd, const uint32_t* mask, hipStream_t st) {
     uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
-    dim3 grid(tiles_m * tiles_n), block(256);
-    if (d_bf16)
-        hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<true>), grid, block, 0, st, a_codes, a_scales, b_codes,
-                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
-    else
-        hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<false>), grid, block, 0, st, a_codes, a_scales, b_codes,
-                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
-    return hipGetLastError();
+    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
+                       a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
+                       tiles_m, tiles_n);
 }
 
-template <int TM, int TN>
-static hipError_t launch_variant(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                                 const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha,
-                                 void* d, int d_bf16, int64_t ldd, hipStream_t st) {
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
+static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                             const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
+                             int64_t ldd, const uint32_t* mask, hipStream_t st) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
-    dim3 grid(tiles_m * tiles_n), block(256);
-    if (d_bf16)
-        hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, true>), grid, block, 0, st, a_codes, a_scales, b_codes,
-                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
-    else
-        hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, false>), grid, block, 0, st, a_codes, a_scales, b_codes,
-                           b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, tiles_m, tiles_n);
-    return hipGetLastError();
+    hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
+                       a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
+                       tiles_m, tiles_n);
 }
 
 // Variants: 0 = 256x256 block, ring of 4 LDS stages (large problems); 1 = 128x128 block, two LDS
-// buffers (problems too small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.  QUARTET_GEMM_VARIANT overrides the
-// size heuristic (tuning aid).
+// buffers (problems too small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.
+// QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
+// fused != 0: D = alpha * H_32_along_n((A B^T) . mask) (mask may be null = all ones), n % 32 == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                       int d_bf16, int64_t ldd, hipStream_t st) {
+                       int d_bf16, int64_t ldd, int fused, const uint32_t* mask, hipStream_t st) {
     if (m == 0 || n == 0) return hipSuccess;
     const char* env = getenv("QUARTET_GEMM_VARIANT");
     int variant = (env && *env) ? atoi(env) : -1;
@@ -529,11 +602,18 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
         variant = big_tiles >= 192 ? 0 : 1;
     }
-    if (variant == 0)
-        return launch_ring(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
-    if (variant == 2)
-        return launch_variant<4, 4>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
-    return launch_variant<2, 2>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_bf16, ldd, st);
+#define QUARTET_DISPATCH(FN, ...)                                                                     \
+    do {                                                                                              \
+        if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); \
+                      else FN<__VA_ARGS__ true, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }   \
+        else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st);      \
+               else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }         \
+    } while (0)
+    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, );
+    else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
+    else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
+#undef QUARTET_DISPATCH
+    return hipGetLastError();
 }
 
 }  // namespace quartet

@@ -83,6 +83,21 @@ def gemm(a_codes, a_scales, b_codes, b_scales, alpha=1.0, bf16=False, ldd=None):
     return to_host(d, np.uint16 if bf16 else np.float32)
 
 
+def gemm_grad(a_codes, a_scales, b_codes, b_scales, mask, scale, bf16=False, ldd=None):
+    m, k = a_codes.shape[0], a_codes.shape[1] * 2
+    n = b_codes.shape[0]
+    ldd = n if ldd is None else ldd
+    if bf16:
+        d = dev_empty((m, ldd), np.uint16, 0x7FC0)
+    else:
+        d = dev_empty((m, ldd), np.float32, float("nan"))
+    q.check(q.quartet_mxfp4_gemm_grad(to_dev(a_codes), to_dev(scales_to_tiled(a_scales)), to_dev(b_codes),
+                                      to_dev(scales_to_tiled(b_scales)), m, n, k,
+                                      None if mask is None else to_dev(mask), scale, d,
+                                      q.QUARTET_DTYPE_BF16 if bf16 else q.QUARTET_DTYPE_F32, ldd))
+    return to_host(d, np.uint16 if bf16 else np.float32)
+
+
 def grad_epilogue(g, mask, scale, bf16=False, in_place=False):
     m, n = g.shape
     gd = to_dev(g)

@@ -62,6 +62,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 4, 40, 1.0, P, 0, 4, 0) == E
     assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 8, 64, 1.0, P, 0, 4, 0) == E    # ldd < n
     assert q.quartet_mxfp4_gemm(P, P, P, P, 4, 8, 64, 1.0, P, 7, 8, 0) == E    # dtype
+    assert q.quartet_mxfp4_gemm_grad(P, P, P, P, 4, 40, 64, None, 1.0, P, 0, 40, 0) == E    # n % 32
+    assert q.quartet_mxfp4_gemm_grad(P, P, P, P, 4, 64, 48, None, 1.0, P, 0, 64, 0) == E    # k % 32
+    assert q.quartet_mxfp4_gemm_grad(P, P, P, P, 4, 64, 64, None, 1.0, P, 0, 32, 0) == E    # ldd < n
     assert q.quartet_grad_epilogue(P, None, 4, 40, 1.0, P, 0, 0) == E
     assert q.quartet_grad_epilogue(P, None, 4, 64, 1.0, P, 1, 0) == E          # bf16 in place
     assert q.quartet_mxfp4_dequant(P, None, 4, 64, P, 0) == E

@@ -167,6 +167,31 @@ def test_gemm_random(G, mnk, gemm_variant):
     assert np.array_equal(got_bf, synth.bf16_to_f32(synth.f32_to_bf16(got)))
 
 
+@pytest.mark.parametrize("mnk", [(1, 32, 32), (130, 96, 96), (257, 160, 160), (64, 320, 1024), (520, 544, 800)])
+def test_gemm_grad_fused(G, mnk, gemm_variant):
+    # GEMM_LP with the backward epilogue of Algorithm 1 in the same kernel against the oracle's two steps
+    m, n, k = mnk
+    rng = np.random.default_rng(m * 1000 + n + 7)
+    ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    asc = rng.integers(117, 137, size=(m, k // 32), dtype=np.uint8)
+    bsc = rng.integers(117, 137, size=(n, k // 32), dtype=np.uint8)
+    mask = rng.integers(0, 2 ** 32, size=(m, n // 32), dtype=np.uint32)
+    acc = oracle.mxfp4_gemm(ac, asc, bc, bsc).astype(np.float32)
+    want = oracle.grad_epilogue(acc, mask)
+    got = G.gemm_grad(ac, asc, bc, bsc, mask, oracle.FL_16_9)
+    assert rel_fro(got, want) < FRO_TOL
+    # the header promises the same bits as the library's own two separate steps
+    two_step = G.grad_epilogue(G.gemm(ac, asc, bc, bsc), mask, oracle.FL_16_9)
+    assert np.array_equal(got.view(np.uint32), two_step.view(np.uint32))
+    got_ld = G.gemm_grad(ac, asc, bc, bsc, mask, oracle.FL_16_9, ldd=n + 3)
+    assert np.array_equal(got_ld[:, :n].view(np.uint32), got.view(np.uint32)) and np.all(np.isnan(got_ld[:, n:]))
+    got_bf = G.gemm_grad(ac, asc, bc, bsc, mask, oracle.FL_16_9, bf16=True)
+    assert np.array_equal(got_bf, synth.f32_to_bf16(got))
+    got_nomask = G.gemm_grad(ac, asc, bc, bsc, None, 1.0)
+    assert rel_fro(got_nomask, oracle.grad_epilogue(acc, None, 1.0)) < FRO_TOL
+
+
 @pytest.mark.parametrize("shape", [(1, 32), (6, 96), (77, 160), (256, 512)])
 def test_grad_epilogue(G, shape):
     rng = np.random.default_rng(shape[0])
