@@ -89,10 +89,17 @@ def cpu_baseline(config):
 
 
 def quant_sweep(q, torch, synth):
+    """Quantizer-only sweep (configuration 5): 10 warm-up + 50 timed launches per case over 4 rotating
+    buffer sets (each pass streams from HBM, not from the 256 MB cache), every launch timed by the
+    library's own HIP event pair; GB/s = algorithmic bytes / median launch time."""
+    import statistics
+    warm, reps, sets = 10, 50, 4
     out = []
+    kinds = (ctypes.c_int * reps)()
+    ms = (ctypes.c_float * reps)()
     for idx, (r, c) in enumerate(synth.QUANT_SWEEP):
         x = synth.device_quant_sweep_matrix(idx)
-        xs = [x] + [x.clone() for _ in range(2)]   # rotate buffers: every pass streams from HBM, not cache
+        xs = [x] + [x.clone() for _ in range(sets - 1)]
         codes = [torch.empty((r, c // 2), dtype=torch.uint8, device=x.device) for _ in xs]
         scales = [torch.empty((max(q.quartet_scale_bytes(r, c), q.quartet_scale_bytes(c, r)),), dtype=torch.uint8, device=x.device) for _ in xs]
         mask = [torch.empty((r, c // 32), dtype=torch.int32, device=x.device) for _ in xs]
@@ -102,34 +109,50 @@ def quant_sweep(q, torch, synth):
                  ("bwd_sr_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 0, codes[j], scales[j])),
                  ("bwd_rtn_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 1, codes[j], scales[j]))]
         for name, bpe, fn in cases:
-            for j in range(3):
-                q.check(fn(j))
+            for j in range(warm):
+                q.check(fn(j % sets))
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 12
-            e0.record()
+            q.check(q.quartet_profile_enable(reps))
             for it in range(reps):
-                q.check(fn(it % 3))
-            e1.record()
+                q.check(fn(it % sets))
             torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            gbs = bpe * r * c / ms / 1e6
-            out.append(dict(shape=[r, c], mode=name, ms=round(ms, 4), GBps=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
+            n = q.quartet_profile_read(kinds, ms, reps)
+            q.quartet_profile_enable(0)
+            if n != reps:
+                raise RuntimeError(f"quantizer sweep: {n} of {reps} launches were timed")
+            med, best = statistics.median(ms[:n]), min(ms[:n])
+            gbs = bpe * r * c / med / 1e6
+            out.append(dict(shape=[r, c], mode=name, ms_median=round(med, 4), ms_min=round(best, 4), GBps=round(gbs, 1),
+                            GBps_best=round(bpe * r * c / best / 1e6, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
         del xs, codes, scales, mask
     return out
 
 
-def recorded_traffic(config):
-    """HBM bytes per GEMM launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-    plain copy kernel of known size); read from the committed summary, None if it is not there."""
-    path = os.path.join(ROOT, "profiles", f"gemm_config{config}_hbm_traffic.txt")
+def recorded(config, name, key):
+    """A figure measured offline with rocprofv3 counters (HBM bytes per GEMM launch scaled by a plain
+    copy kernel of known size; shader clock while the GEMMs run), read from the committed summary
+    profiles/<name>; None if it is not there."""
+    path = os.path.join(ROOT, "profiles", name.format(config=config))
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith(key + ":"):
                 return float(line.split(":")[1])
     except OSError:
         pass
     return None
+
+
+def lower_bound_ms(layers):
+    """Time no implementation of the path can beat on this chip's published peaks:
+    6*T*I*O / peak MFMA + (bytes of the memory-bound steps) / 8 TB/s."""
+    total = 0.0
+    for l in layers:
+        t, i, o = l.t, l.i, l.o
+        mem = 2.65625 * (t * i + o * i)          # forward quantizers of X and W (codes, scales, mask)
+        mem += 2.53125 * 2 * t * o               # backward quantizers of dy, row and transposed
+        mem += 1.0625 * (o * i + t * i)          # re-quantization of W_q and X_q along the other dimension
+        total += 6.0 * t * i * o / (PEAK_FP4_TFLOPS * 1e12) + mem / (PEAK_HBM_GBS * 1e9)
+    return total * 1e3
 
 
 def main():
@@ -145,12 +168,13 @@ def main():
     from paper_2505_14669_amd import synth
 
     torch.cuda.set_device(0)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
     cfg = synth.CONFIGS[args.config]
     layers = [Layer(q, torch, synth.device_layer(args.config, li)) for li in range(len(cfg["layers"]))]
     ws_bytes = max(l.ws_bytes for l in layers)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     flops_step = sum(l.flops for l in layers)
-    launches_per_step = 11 * len(layers)
+    launches_per_step = 9 * len(layers)    # 2 + 1 forward, (2 + 1) x 2 backward
 
     def one_step(step):
         for l in layers:
@@ -196,12 +220,20 @@ def main():
         "config": {"workload": f"config {args.config}: {cfg['name']}, {len(layers)} linear layers fwd+bwd, "
                                f"backward rounding {'stochastic' if args.rounding == 0 else 'nearest'}",
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_kernel (all three GEMMs of every layer)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_ring_kernel (all three GEMMs of every layer)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_FP4_TFLOPS, 4), "traffic": recorded_traffic(args.config),
-                     "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms)},
+                     "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
+                     "traffic": recorded(args.config, "gemm_config{config}_hbm_traffic.txt", "traffic_bytes_per_launch"),
+                     "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms),
+                     "compute_units": cus},
+        "lower_bound_ms_per_step": round(lower_bound_ms(layers), 4),
         "kernel_time_share": {k: round(sum(v) / (dt * 1e3), 4) for k, v in sorted(per_kind.items())},
     }
+    clock = recorded(args.config, "gemm_config{config}_mfma_counters.txt", "observed_clock_ghz")
+    if clock:   # the same fraction against what the chip can do at the clock it actually holds under this kernel
+        peak_obs = cus * clock * 1e9 * 16384 / 1e12
+        result["roofline"].update(observed_clock_ghz=clock, peak_at_observed_clock=round(peak_obs, 1),
+                                  frac_at_observed_clock=round(achieved / peak_obs, 4))
     if args.breakdown:
         for k, v in sorted(per_kind.items()):
             print(f"  {k:10s} launches {len(v):4d} total {sum(v):9.3f} ms  ({sum(v) / (dt * 1e3) * 100:5.1f} % of wall)",
