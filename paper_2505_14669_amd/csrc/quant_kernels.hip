@@ -270,6 +270,112 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
     }
 }
 
+// ------------------------------------------------------------------ MXFP4 source, other dimension
+// Re-quantization of a saved MXFP4 tensor S [k x rows] along its other dimension (Algorithm 1
+// Backward: the operands W_q^T and X_q^T).  Block tile = 256 source rows (one K-quad of the output)
+// x 256 source columns (256 output rows).  The tile is walked one output group (32 source rows) at a
+// time: every thread fetches 16 bytes of codes (32 columns of one source row: 8 lanes cover a whole
+// 128-byte line), decodes them exactly and writes the 32 values into an LDS stage laid out
+// [column][source row]; then thread c reads the 32 values of column c back, quantizes the group and
+// parks its 16 bytes of codes in LDS.  After the eighth group the block holds 128 contiguous bytes
+// of codes for each of its 256 output rows and 8 whole scale tiles, which leave as full lines.
+constexpr uint32_t kStageStride = 36;   // floats per column of the stage: 16-byte aligned, b128 reads conflict-free
+
+template <int MODE>
+__global__ void __launch_bounds__(256)
+requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
+                          uint32_t rows, uint32_t k, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                          SrParams p) {
+    __shared__ float s_stage[256 * kStageStride];
+    __shared__ uint4 s_codes[256 * 8];
+    __shared__ uint8_t s_scales[256 * 8];
+    const uint32_t t = threadIdx.x;
+    const uint32_t gk = k >> 5, okq = (k + 255u) >> 8;          // output groups per row, output K-quads
+    const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;  // source row pitch in bytes, source K-quads
+    const uint32_t c0 = blockIdx.x * 256u, kq = blockIdx.y, grp0 = kq * 8u;
+    // load role: source row rl of the group, 32-column chunk ch
+    const uint32_t rl = t >> 3, ch = t & 7u;
+    const bool chunk_ok = c0 + 32u * ch < rows;
+    const uint8_t* code_ptr = src_codes + (size_t)(grp0 * 32u + rl) * half + ((c0 + 32u * ch) >> 1);
+    // the 32 rows x 8 column groups of one step are exactly one scale tile of the source
+    const uint8_t* scale_ptr = src_scales + ((size_t)grp0 * skq + (c0 >> 8)) * 256u + (((ch & 1u) << 5) + rl) * 4u + (ch >> 1);
+    const size_t code_step = (size_t)32u * half, scale_step = (size_t)skq * 256u;
+    const uint32_t wr = (rl + 8u * ch) & 31u;                   // rotated row slot: spreads the 8 chunks over banks
+    // quantize role: output row c0 + t
+    const uint32_t out_row = c0 + t, rot = (8u * (t >> 5)) & 31u;
+
+    uint4 cw = make_uint4(0u, 0u, 0u, 0u);
+    uint32_t sb_src = 127u;
+    if (chunk_ok && grp0 * 32u + rl < k) {
+        cw = *reinterpret_cast<const uint4*>(code_ptr);
+        sb_src = *scale_ptr;
+    }
+#pragma unroll 1
+    for (uint32_t g = 0; g < 8; ++g) {
+        // decode this step's codes; fetch the next step's
+        const float sc = u2f(sb_src << 23);
+        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};
+        float f[32];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 0);
+            v2f b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 1);
+            v2f c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 2);
+            v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 3);
+            f[8 * i] = a[0]; f[8 * i + 1] = a[1]; f[8 * i + 2] = b[0]; f[8 * i + 3] = b[1];
+            f[8 * i + 4] = c[0]; f[8 * i + 5] = c[1]; f[8 * i + 6] = d[0]; f[8 * i + 7] = d[1];
+        }
+        cw = make_uint4(0u, 0u, 0u, 0u);
+        sb_src = 127u;
+        if (g + 1u < 8u && chunk_ok && (grp0 + g + 1u) * 32u + rl < k) {
+            cw = *reinterpret_cast<const uint4*>(code_ptr + (g + 1u) * code_step);
+            sb_src = scale_ptr[(g + 1u) * scale_step];
+        }
+        if (g > 0) __syncthreads();                              // everyone has read the previous stage
+#pragma unroll
+        for (uint32_t j = 0; j < 32; ++j) s_stage[(32u * ch + j) * kStageStride + wr] = f[j];
+        __syncthreads();
+        float v[32];
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            const float4 x = *reinterpret_cast<const float4*>(&s_stage[t * kStageStride + ((4u * q + rot) & 31u)]);
+            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+        }
+        uint4 out;
+        uint32_t sb, mw;
+        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + g) * 32u) >> 3, out, sb, mw);
+        s_codes[t * 8u + (g ^ (t & 7u))] = out;
+        s_scales[t * 8u + g] = (uint8_t)sb;
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t j = 0; j < 8; ++j) {
+        const uint32_t id = t + 256u * j, lc = id >> 3, part = id & 7u;
+        const uint32_t r = c0 + lc, grp = grp0 + part;
+        if (r < rows && grp < gk) store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, s_codes[lc * 8u + (part ^ (lc & 7u))]);
+    }
+    // scales: each 32-row block of the tile is one 256-byte scale tile of the output; thread id writes
+    // dword id%64 of tile id/64 (bytes = groups h, 2+h, 4+h, 6+h of its row)
+#pragma unroll
+    for (uint32_t j = 0; j < 2; ++j) {
+        const uint32_t id = t + 256u * j, lc = (id >> 6) * 32u + (id & 31u), h = (id >> 5) & 1u;
+        const uint32_t r = c0 + lc;
+        if (r < rows) {
+            uint32_t w = 0u;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) w |= (uint32_t)s_scales[lc * 8u + 2u * q + h] << (8u * q);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(r, grp0 + h, okq));
+            if (grp0 + 6u + h < gk) {
+                *dst = w;
+            } else {
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q)
+                    if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ MXFP4 -> fp32
 __global__ void __launch_bounds__(256)
 dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, uint32_t n_groups,
@@ -351,9 +457,15 @@ hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_
 hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const uint8_t* src_scales,
                                     int64_t rows, int64_t k, const SrParams& p, uint8_t* codes,
                                     uint8_t* scales, hipStream_t st) {
+    if (rows == 0 || k == 0) return hipSuccess;
+    dim3 grid((uint32_t)((rows + 255) / 256), (uint32_t)((k + 255) / 256)), block(256);
     if (mode == kBwdRtn)
-        return launch_transposed<kBwdRtn, 1>(src_codes, src_scales, rows, k, 0, codes, scales, nullptr, p, st);
-    return launch_transposed<kBwdSr, 1>(src_codes, src_scales, rows, k, 0, codes, scales, nullptr, p, st);
+        hipLaunchKernelGGL((requant_transposed_kernel<kBwdRtn>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows,
+                           (uint32_t)k, codes, scales, p);
+    else
+        hipLaunchKernelGGL((requant_transposed_kernel<kBwdSr>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows,
+                           (uint32_t)k, codes, scales, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t k, float* out,
