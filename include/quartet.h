@@ -71,8 +71,11 @@ size_t quartet_scale_bytes(int64_t rows, int64_t k);
  * of its next kernel launches, up to n, with a pair of hipEvents recorded on the caller's stream;
  * n = 0 disables it and frees the events.  quartet_profile_read() waits for the recorded launches,
  * writes kind (QUARTET_KIND_*) and duration in milliseconds of each, in launch order, returns how
- * many it wrote (or a negative error) and restarts the record.  The record is process-global:
- * use it from one thread, with profiling calls and launches on the same device.
+ * many it wrote (or a negative error) and restarts the record.  quartet_profile_kinds(mask) limits
+ * the record to the kinds whose bit (1 << QUARTET_KIND_*) is set (default: all); an event pair costs
+ * a few microseconds of stream time, so a timed region records only the kernel it is about.  The
+ * record is process-global: use it from one thread, with profiling calls and launches on the same
+ * device.
  */
 #define QUARTET_KIND_QUANT_FWD 0
 #define QUARTET_KIND_QUANT_BWD 1
@@ -81,6 +84,7 @@ size_t quartet_scale_bytes(int64_t rows, int64_t k);
 #define QUARTET_KIND_EPILOGUE 4
 #define QUARTET_KIND_DEQUANT 5
 int quartet_profile_enable(int max_records);
+int quartet_profile_kinds(unsigned kind_mask);
 int quartet_profile_read(int *kinds, float *ms, int capacity);
 
 /*

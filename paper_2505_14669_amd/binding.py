@@ -23,7 +23,7 @@ QUARTET_ROUND_NEAREST = 1
 
 EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
-    "quartet_profile_enable", "quartet_profile_read", "quartet_scale_bytes",
+    "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr",
     "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
@@ -40,6 +40,7 @@ _i64, _u32, _u64, _p, _int, _f = (ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint
 _lib.quartet_last_hip_error.restype = _int
 _lib.quartet_sr_bits.restype = _int
 _lib.quartet_profile_enable.argtypes = [_int]
+_lib.quartet_profile_kinds.argtypes = [ctypes.c_uint]
 _lib.quartet_profile_read.argtypes = [_p, _p, _int]
 _lib.quartet_scale_bytes.restype = ctypes.c_size_t
 _lib.quartet_scale_bytes.argtypes = [_i64, _i64]
@@ -104,10 +105,15 @@ def quartet_sr_bits():
 
 
 KIND_NAMES = ["quant_fwd", "quant_bwd", "requant", "gemm", "epilogue", "dequant"]
+QUARTET_KIND_GEMM = 3
 
 
 def quartet_profile_enable(max_records):
     return _lib.quartet_profile_enable(max_records)
+
+
+def quartet_profile_kinds(kind_mask):
+    return _lib.quartet_profile_kinds(kind_mask)
 
 
 def quartet_profile_read(kinds, ms, capacity):

@@ -48,6 +48,7 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
 struct ProfileState {
     bool enabled = false;
     int capacity = 0, count = 0;
+    unsigned kinds = ~0u;   // bit i set: launches of kind i are recorded
     hipEvent_t* start = nullptr;
     hipEvent_t* stop = nullptr;
     int* kind = nullptr;
@@ -58,7 +59,7 @@ struct ProfileScope {
     int slot = -1;
     hipStream_t st;
     ProfileScope(int kind, hipStream_t s) : st(s) {
-        if (g_prof.enabled && g_prof.count < g_prof.capacity) {
+        if (g_prof.enabled && ((g_prof.kinds >> kind) & 1u) && g_prof.count < g_prof.capacity) {
             slot = g_prof.count++;
             g_prof.kind[slot] = kind;
             (void)hipEventRecord(g_prof.start[slot], st);
@@ -75,7 +76,9 @@ void profile_free() {
         (void)hipEventDestroy(g_prof.stop[i]);
     }
     delete[] g_prof.start; delete[] g_prof.stop; delete[] g_prof.kind;
+    const unsigned kinds = g_prof.kinds;
     g_prof = ProfileState();
+    g_prof.kinds = kinds;
 }
 
 size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
@@ -136,6 +139,11 @@ int quartet_profile_enable(int max_records) {
         g_prof.capacity = i + 1;
     }
     g_prof.enabled = true;
+    return QUARTET_OK;
+}
+
+int quartet_profile_kinds(unsigned kind_mask) {
+    g_prof.kinds = kind_mask;
     return QUARTET_OK;
 }
 
