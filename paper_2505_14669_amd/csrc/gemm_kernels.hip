@@ -600,7 +600,9 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     int variant = (env && *env) ? atoi(env) : -1;
     if (variant < 0) {
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-        variant = big_tiles >= 192 ? 0 : 1;
+        // measured crossover on an MI355X: 128 big tiles (4096 x 2048 x 2048) are 8 % faster as 128 x 128 tiles,
+        // 176 (5632 x 2048 x 8192) are 1.75 x faster as 256 x 256 tiles even though they leave 80 CUs idle
+        variant = big_tiles >= 160 ? 0 : 1;
     }
 #define QUARTET_DISPATCH(FN, ...)                                                                     \
     do {                                                                                              \
