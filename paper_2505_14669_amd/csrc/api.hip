@@ -41,6 +41,7 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
     if (rows > 0 && (k / 32) > kMaxGroups / (rows > 0 ? rows : 1)) return QUARTET_ENOTSUP;
     if (rows * (k / 32) >= kMaxGroups) return QUARTET_ENOTSUP;
     if ((k + 255) / 256 > 65535) return QUARTET_ENOTSUP;
+    if (ldx >= ((int64_t)1 << 27)) return QUARTET_ENOTSUP;   // 8 rows of the source must fit a 32-bit byte range
     return QUARTET_OK;
 }
 

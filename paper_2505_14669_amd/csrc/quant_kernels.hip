@@ -112,15 +112,18 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
     // contiguous stretch of the input
     const uint32_t row_set = fast_div(blockIdx.x, div_k_blocks);
     const uint32_t row0 = row_set * 8u, kq0 = (blockIdx.x - row_set * k_blocks) * 4u, kqs = (gk + 7u) >> 3;
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    // The block's rows through a buffer resource that ends with the last element of its last row:
+    // rows past the matrix read as zeros without a predicate.  Groups past k inside a row read
+    // whatever lies there (the row's padding or the next row); their results are never stored.
+    const uint32_t rows_here = (rows - row0) < 8u ? (rows - row0) : 8u;
+    const __amdgpu_buffer_rsrc_t res_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(x + (size_t)row0 * ldx), 0, (int)(((rows_here - 1u) * (uint32_t)ldx + gk * 32u) * 2u), 0x00020000);
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
         uint32_t c = 64u * j + lane;                       // 16-byte chunk inside the wave's 2 rows x 2 KB
-        uint32_t r = row0 + wave * 2u + (c >> 7), g = kq0 * 8u + ((c & 127u) >> 2);
-        uint4 q = zero;
-        if (r < rows && g < gk)
-            q = load_stream16(x + (size_t)r * ldx + (size_t)kq0 * 256u + (c & 127u) * 8u);
-        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = q;
+        const uint32_t voff = ((wave * 2u + (c >> 7)) * (uint32_t)ldx + kq0 * 256u + (c & 127u) * 8u) * 2u;
+        v4u_t q = __builtin_amdgcn_raw_buffer_load_b128(res_x, (int)voff, 0, 2 /* non-temporal */);
+        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = make_uint4(q.x, q.y, q.z, q.w);
     }
     __syncthreads();
     float v[32];
