@@ -41,7 +41,8 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
     if (rows > 0 && (k / 32) > kMaxGroups / (rows > 0 ? rows : 1)) return QUARTET_ENOTSUP;
     if (rows * (k / 32) >= kMaxGroups) return QUARTET_ENOTSUP;
     if ((k + 255) / 256 > 65535) return QUARTET_ENOTSUP;
-    if (ldx >= ((int64_t)1 << 27)) return QUARTET_ENOTSUP;   // 8 rows of the source must fit a 32-bit byte range
+    // a block's corner of the source (8 rows; 256 rows when transposed) must fit a 32-bit byte range
+    if (ldx >= ((int64_t)1 << (transpose ? 22 : 27))) return QUARTET_ENOTSUP;
     return QUARTET_OK;
 }
 

@@ -176,12 +176,19 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
     __shared__ uint4 s_codes[128 * 8];
     __shared__ uint8_t s_scales[128 * 8];
     __shared__ uint32_t s_mask[128 * 8];
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
     const uint32_t gk = k >> 5;
     const uint32_t col0 = blockIdx.x * 128u;
     const uint32_t grp0 = blockIdx.y * 8u;
     const uint32_t col = col0 + 2u * lane;                // even; rows is even, so col+1 < rows too
     const bool col_ok = col < rows;
+    // bf16 source: the block's corner through a buffer resource that ends with the last column of the
+    // last source row (unused, with an empty range, for an MXFP4 source)
+    const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
+    const uint32_t src_cols = (rows - col0) < 128u ? (rows - col0) : 128u;
+    const __amdgpu_buffer_rsrc_t res_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(static_cast<const uint16_t*>(src) + (SRC == 0 ? (size_t)grp0 * 32u * ldx + col0 : 0)), 0,
+        SRC == 0 ? (int)(((src_rows - 1u) * (uint32_t)ldx + src_cols) * 2u) : 0, 0x00020000);
 
 #pragma unroll 1
     for (uint32_t rb = 0; rb < 2; ++rb) {
@@ -190,11 +197,13 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
         const bool ok = col_ok && grp < gk;
         float v0[32], v1[32];
         if (SRC == 0) {
-            const uint16_t* x = static_cast<const uint16_t*>(src);
+            // the block's corner of the source through a buffer resource that ends with the last column of
+            // the last source row: rows past k read as zeros without a predicate; columns past `rows`
+            // inside a source row read whatever lies there, their results are never stored
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
-                uint32_t w = 0u;
-                if (ok) w = load_stream4(x + (size_t)(grp * 32u + i) * ldx + col);
+                // the row part of the address is wave-uniform and rides in the scalar offset
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(res_x, (int)(4u * lane), (int)((gl * 32u + i) * (uint32_t)ldx * 2u), 2 /* non-temporal */);
                 v0[i] = u2f(w << 16);
                 v1[i] = u2f(w & 0xFFFF0000u);
             }
