@@ -208,6 +208,7 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
     if (!aligned16(src_codes) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     if (rows < 0 || (rows % 32) != 0) return QUARTET_EINVAL;
+    if (rows >= ((int64_t)1 << 24)) return QUARTET_ENOTSUP;   // 256 source rows of rows/2 bytes must fit a 32-bit byte range
     int rc = check_quant_shape(rows, k, (rows + 7) / 8 * 8, 1);
     if (rc) return rc;
     SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};

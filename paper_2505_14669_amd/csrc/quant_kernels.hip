@@ -284,106 +284,134 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
 
 // ------------------------------------------------------------------ MXFP4 source, other dimension
 // Re-quantization of a saved MXFP4 tensor S [k x rows] along its other dimension (Algorithm 1
-// Backward: the operands W_q^T and X_q^T).  Block tile = 256 source rows (one K-quad of the output)
-// x 256 source columns (256 output rows).  The tile is walked one output group (32 source rows) at a
-// time: every thread fetches 16 bytes of codes (32 columns of one source row: 8 lanes cover a whole
-// 128-byte line), decodes them exactly and writes the 32 values into an LDS stage laid out
-// [column][source row]; then thread c reads the 32 values of column c back, quantizes the group and
-// parks its 16 bytes of codes in LDS.  After the eighth group the block holds 128 contiguous bytes
-// of codes for each of its 256 output rows and 8 whole scale tiles, which leave as full lines.
+// Backward: the operands W_q^T and X_q^T).  A block covers 256 source rows (one K-quad of the
+// output) x 256 source columns (256 output rows); each of its waves owns 64 of the columns and works
+// alone, without block barriers.  Per output group (32 source rows) a lane fetches 16 bytes of codes
+// (32 columns of one source row; the four waves of the block together read whole 128-byte lines),
+// decodes them exactly and writes the 32 values into the wave's LDS stage laid out
+// [column][source row]; then lane c reads the 32 values of column c back, quantizes the group and
+// keeps its 16 bytes of codes; the scale bytes collect in two registers that are, after the eighth
+// group, exactly the two scale-tile dwords of the lane's output row.  Each lane then writes the 128
+// contiguous bytes of codes of its row and its two scale dwords.
 constexpr uint32_t kStageStride = 36;   // floats per column of the stage: 16-byte aligned, b128 reads conflict-free
 
 template <int MODE>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 4)   // 4 waves per SIMD: at most 128 registers
 requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
                           uint32_t rows, uint32_t k, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
                           SrParams p) {
-    __shared__ float s_stage[256 * kStageStride];
-    __shared__ uint4 s_codes[256 * 8];
-    __shared__ uint8_t s_scales[256 * 8];
-    const uint32_t t = threadIdx.x;
+    __shared__ float s_stage[4][64 * kStageStride];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    float* stage = s_stage[wave];
     const uint32_t gk = k >> 5, okq = (k + 255u) >> 8;          // output groups per row, output K-quads
     const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;  // source row pitch in bytes, source K-quads
-    const uint32_t c0 = blockIdx.x * 256u, kq = blockIdx.y, grp0 = kq * 8u;
-    // load role: source row rl of the group, 32-column chunk ch
-    const uint32_t rl = t >> 3, ch = t & 7u;
-    const bool chunk_ok = c0 + 32u * ch < rows;
-    const uint8_t* code_ptr = src_codes + (size_t)(grp0 * 32u + rl) * half + ((c0 + 32u * ch) >> 1);
-    // the 32 rows x 8 column groups of one step are exactly one scale tile of the source
-    const uint8_t* scale_ptr = src_scales + ((size_t)grp0 * skq + (c0 >> 8)) * 256u + (((ch & 1u) << 5) + rl) * 4u + (ch >> 1);
-    const size_t code_step = (size_t)32u * half, scale_step = (size_t)skq * 256u;
-    const uint32_t wr = (rl + 8u * ch) & 31u;                   // rotated row slot: spreads the 8 chunks over banks
-    // quantize role: output row c0 + t
-    const uint32_t out_row = c0 + t, rot = (8u * (t >> 5)) & 31u;
+    const uint32_t c0 = blockIdx.x * 256u + wave * 64u, kq = blockIdx.y, grp0 = kq * 8u;
+    // load role: source row rl of the group, 32-column chunk ch of the wave's 64 columns
+    const uint32_t rl = lane >> 1, ch = lane & 1u, cg = wave * 2u + ch;   // cg: column group inside the source's K-quad
+    // The block's corner of the source codes and the scale tiles below it through buffer resources that
+    // end with the data: source rows past k read as zeros without predicates or branches.  Columns
+    // past `rows` read whatever lies there; the output rows they feed are never stored.
+    const uint32_t cb0 = blockIdx.x * 256u;
+    const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
+    const uint32_t src_cols = (rows - cb0) < 256u ? (rows - cb0) : 256u;
+    const __amdgpu_buffer_rsrc_t res_c = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(src_codes + (size_t)grp0 * 32u * half + (cb0 >> 1)), 0,
+        (int)((src_rows - 1u) * half + (src_cols >> 1)), 0x00020000);
+    // the 32 rows x 8 column groups of one step of the block are exactly one scale tile of the source
+    const size_t tile0 = ((size_t)grp0 * skq + (cb0 >> 8)) * 256u;
+    const __amdgpu_buffer_rsrc_t res_s = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(src_scales + tile0), 0, (int)((size_t)gk * skq * 256u - tile0), 0x00020000);
+    const uint32_t code_off = rl * half + ((wave * 64u + 32u * ch) >> 1);
+    const uint32_t scale_off = (((cg & 1u) << 5) + rl) * 4u + (cg >> 1);
+    const uint32_t code_step = 32u * half, scale_step = skq * 256u;   // wave-uniform: they ride in the scalar offset
+    const uint32_t wr = (rl + 8u * ch) & 31u;                   // rotated row slot: the two chunks land on different banks
+    // quantize role: output row c0 + lane
+    const uint32_t out_row = c0 + lane, rot = (8u * (lane >> 5)) & 31u;
 
-    uint4 cw = make_uint4(0u, 0u, 0u, 0u);
-    uint32_t sb_src = 127u;
-    if (chunk_ok && grp0 * 32u + rl < k) {
-        cw = *reinterpret_cast<const uint4*>(code_ptr);
-        sb_src = *scale_ptr;
+    v4u_t cw = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, 0, 0);
+    uint32_t sb_src = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, 0, 0);
+    uint32_t sw0 = 0u, sw1 = 0u;   // the row's scale bytes as the two dwords of the output's scale tile (groups h, 2+h, 4+h, 6+h)
+    uint8_t* crow = codes + (size_t)out_row * (k >> 1) + (size_t)grp0 * 16u;   // the row's 128 bytes of codes in this K-quad
+// One step g: fetch the next step's codes and scale byte (past the eighth step the values are not
+// used), decode this step's, pass them through the wave's stage, quantize column `lane`.
+#define REQUANT_STEP(G, OUT)                                                                            \
+    {                                                                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        v4u_t cw_next = cw;                                                                             \
+        uint32_t sb_next = sb_src;                                                                      \
+        if ((G) + 1u < 8u) {                                                                            \
+            cw_next = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, (int)(((G) + 1u) * code_step), 0); \
+            sb_next = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, (int)(((G) + 1u) * scale_step), 0); \
+        }                                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+        asm volatile("" : "+v"(sb_src)); /* the scale is formed here, not next to its load: no early wait */ \
+        const float sc = u2f(sb_src << 23);                                                             \
+        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};                                                 \
+        float f[32];                                                                                    \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+            v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 0);                              \
+            v2f b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 1);                              \
+            v2f c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 2);                              \
+            v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 3);                              \
+            f[8 * i] = a[0]; f[8 * i + 1] = a[1]; f[8 * i + 2] = b[0]; f[8 * i + 3] = b[1];             \
+            f[8 * i + 4] = c[0]; f[8 * i + 5] = c[1]; f[8 * i + 6] = d[0]; f[8 * i + 7] = d[1];         \
+        }                                                                                               \
+        cw = cw_next;                                                                                   \
+        sb_src = sb_next;                                                                               \
+        /* The stage belongs to this wave alone and a wave's LDS operations complete in order, so the   \
+           exchange needs no barrier and no fence (a fence would also wait for the loads just issued):  \
+           only the compiler must keep the writes and the reads in program order. */                    \
+        __builtin_amdgcn_wave_barrier();                                                                \
+        _Pragma("unroll") for (uint32_t j = 0; j < 32; ++j) stage[(32u * ch + j) * kStageStride + wr] = f[j]; \
+        __builtin_amdgcn_wave_barrier();                                                                \
+        float v[32];                                                                                    \
+        _Pragma("unroll") for (uint32_t q = 0; q < 8; ++q) {                                            \
+            const float4 x = *reinterpret_cast<const float4*>(&stage[lane * kStageStride + ((4u * q + rot) & 31u)]); \
+            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;                 \
+        }                                                                                               \
+        uint32_t sb, mw;                                                                                \
+        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + (G)) * 32u) >> 3, OUT, sb, mw);     \
+        if ((G) & 1u) sw1 |= sb << (8u * ((G) >> 1));                                                   \
+        else sw0 |= sb << (8u * ((G) >> 1));                                                            \
     }
+    if (MODE == kBwdSr) {
+        // Unrolled, with the instruction scheduler fenced at the step boundaries: each step's codes get
+        // registers of their own, so the wait before decoding them lets the next step's loads stay in
+        // flight; the row's 128 bytes of codes leave together at the end (a store inside the loop makes
+        // every step wait for it before its registers can be reused).
+        uint4 out[8];
+#pragma unroll
+        for (uint32_t g = 0; g < 8; ++g) REQUANT_STEP(g, out[g])
+        __builtin_amdgcn_sched_barrier(0);
+        if (out_row >= rows) return;
+#pragma unroll
+        for (uint32_t g = 0; g < 8; ++g)
+            if (grp0 + g < gk) *reinterpret_cast<uint4*>(crow + 16u * g) = out[g];
+    } else {
+        // round-to-nearest: the unrolled form costs this variant more registers than a CU can give four
+        // waves; it keeps the loop, and each step stores its own 16 bytes
 #pragma unroll 1
-    for (uint32_t g = 0; g < 8; ++g) {
-        // decode this step's codes; fetch the next step's
-        const float sc = u2f(sb_src << 23);
-        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};
-        float f[32];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 0);
-            v2f b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 1);
-            v2f c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 2);
-            v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 3);
-            f[8 * i] = a[0]; f[8 * i + 1] = a[1]; f[8 * i + 2] = b[0]; f[8 * i + 3] = b[1];
-            f[8 * i + 4] = c[0]; f[8 * i + 5] = c[1]; f[8 * i + 6] = d[0]; f[8 * i + 7] = d[1];
+        for (uint32_t g = 0; g < 8; ++g) {
+            uint4 out;
+            REQUANT_STEP(g, out)
+            if (out_row < rows && grp0 + g < gk) *reinterpret_cast<uint4*>(crow + 16u * g) = out;
         }
-        cw = make_uint4(0u, 0u, 0u, 0u);
-        sb_src = 127u;
-        if (g + 1u < 8u && chunk_ok && (grp0 + g + 1u) * 32u + rl < k) {
-            cw = *reinterpret_cast<const uint4*>(code_ptr + (g + 1u) * code_step);
-            sb_src = scale_ptr[(g + 1u) * scale_step];
-        }
-        if (g > 0) __syncthreads();                              // everyone has read the previous stage
-#pragma unroll
-        for (uint32_t j = 0; j < 32; ++j) s_stage[(32u * ch + j) * kStageStride + wr] = f[j];
-        __syncthreads();
-        float v[32];
-#pragma unroll
-        for (uint32_t q = 0; q < 8; ++q) {
-            const float4 x = *reinterpret_cast<const float4*>(&s_stage[t * kStageStride + ((4u * q + rot) & 31u)]);
-            v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
-        }
-        uint4 out;
-        uint32_t sb, mw;
-        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + g) * 32u) >> 3, out, sb, mw);
-        s_codes[t * 8u + (g ^ (t & 7u))] = out;
-        s_scales[t * 8u + g] = (uint8_t)sb;
+        if (out_row >= rows) return;
     }
-    __syncthreads();
+#undef REQUANT_STEP
+    // scales: dwords (row, h = 0) and (row, h = 1) of the output's scale tile; a wave's 64 rows fill two
+    // 128-byte runs per h
 #pragma unroll
-    for (uint32_t j = 0; j < 8; ++j) {
-        const uint32_t id = t + 256u * j, lc = id >> 3, part = id & 7u;
-        const uint32_t r = c0 + lc, grp = grp0 + part;
-        if (r < rows && grp < gk) store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, s_codes[lc * 8u + (part ^ (lc & 7u))]);
-    }
-    // scales: each 32-row block of the tile is one 256-byte scale tile of the output; thread id writes
-    // dword id%64 of tile id/64 (bytes = groups h, 2+h, 4+h, 6+h of its row)
+    for (uint32_t h = 0; h < 2; ++h) {
+        const uint32_t w = h ? sw1 : sw0;
+        if (grp0 + h >= gk) continue;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(out_row, grp0 + h, okq));
+        if (grp0 + 6u + h < gk) {
+            *dst = w;
+        } else {
 #pragma unroll
-    for (uint32_t j = 0; j < 2; ++j) {
-        const uint32_t id = t + 256u * j, lc = (id >> 6) * 32u + (id & 31u), h = (id >> 5) & 1u;
-        const uint32_t r = c0 + lc;
-        if (r < rows) {
-            uint32_t w = 0u;
-#pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) w |= (uint32_t)s_scales[lc * 8u + 2u * q + h] << (8u * q);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(r, grp0 + h, okq));
-            if (grp0 + 6u + h < gk) {
-                *dst = w;
-            } else {
-#pragma unroll
-                for (uint32_t q = 0; q < 4; ++q)
-                    if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
-            }
+            for (uint32_t q = 0; q < 4; ++q)
+                if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
         }
     }
 }
