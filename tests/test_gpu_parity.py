@@ -67,6 +67,33 @@ def test_quant_fwd_row_strided(G):
     same(G.to_host(mask, np.uint32), want[2], "strided mask")
 
 
+@pytest.mark.parametrize("transpose", [False, True])
+def test_quant_strided_source_with_nan_padding(G, transpose):
+    # the columns between the logical width and the leading dimension hold NaN patterns: the kernels read
+    # past the logical width inside a row (their loads are range-checked per block, not per element) but
+    # nothing of it may reach the output
+    from paper_2505_14669_amd import binding as q
+    src_rows, width, ld = (160, 96, 136) if transpose else (77, 160, 392)
+    full = np.full((src_rows, ld), 0x7FC1, dtype=np.uint16)
+    x = synth.small_matrix(21, src_rows, width, "heavy")
+    full[:, :width] = x
+    rows, k = (width, src_rows) if transpose else (src_rows, width)
+    xd = G.to_dev(full)
+    for mode in ("fwd", "rtn", "sr"):
+        codes = G.dev_empty((rows, k // 2), np.uint8, 0)
+        scales = G.dev_empty((q_scale_bytes(rows, k),), np.uint8, 0)
+        if mode == "fwd":
+            mask = G.dev_empty((rows, k // 32), np.uint32, 0)
+            q.check(q.quartet_quant_fwd(xd, rows, k, ld, int(transpose), codes, scales, mask))
+            want = oracle.quant_fwd(x, transpose=transpose)
+            same(G.to_host(mask, np.uint32), want[2], f"{mode} mask")
+        else:
+            q.check(q.quartet_quant_bwd_sr(xd, rows, k, ld, int(transpose), 0x9E3779B9, 31, 2, int(mode == "rtn"), codes, scales))
+            want = oracle.quant_bwd_sr(x, 0x9E3779B9, 31, 2, int(mode == "rtn"), transpose=transpose)
+        same(scales_from_tiled(G.to_host(scales, np.uint8), rows, k), want[1], f"{mode} scales")
+        same(G.to_host(codes, np.uint8), want[0], f"{mode} codes")
+
+
 @pytest.mark.parametrize("shape", [(32, 8), (64, 128), (96, 40), (256, 136), (288, 264), (1056, 72)])
 def test_quant_fwd_transposed(G, shape):
     # source stored [k, rows]
