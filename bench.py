@@ -74,7 +74,7 @@ def cpu_baseline(config):
     import oracle
     from paper_2505_14669_amd import synth
     name, t, i, o = synth.CONFIGS[config]["layers"][0]
-    budget = 1.2e11                       # MACs-ish the plain fp64 loops get through in ~15 s on a few cores
+    budget = 3.6e11                       # multiply-adds the plain fp64 loops get through in 10-15 s on the box's 16 cores
     ts = int(min(t, max(32, (budget / (3.0 * i * o)) // 32 * 32)))
     rng = np.random.Generator(np.random.PCG64(4242))
     x = synth.f32_to_bf16(rng.standard_t(3.0, size=(ts, i)).astype(np.float32))
