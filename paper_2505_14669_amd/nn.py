@@ -75,16 +75,18 @@ class QuartetLinearFunction(torch.autograd.Function):
 
 
 class QuartetLinear(torch.nn.Module):
-    """nn.Linear replacement: bf16 weight [out, in], optional bf16 bias added outside the quantized
-    product.  Every backward pass uses a fresh stochastic-rounding seed: base seed, layer id and a
+    """nn.Linear replacement: weight [out, in] (bf16, or fp32 master weights cast to bf16 on the way
+    in), optional bf16 bias added outside the quantized product.  Every backward pass uses a fresh stochastic-rounding seed: base seed, layer id and a
     per-layer call counter packed into 64 bits, so runs are reproducible and no two calls share draws."""
     _next_id = 0
 
-    def __init__(self, in_features, out_features, bias=False, seed=0, rounding=0, device="cuda"):
+    def __init__(self, in_features, out_features, bias=False, seed=0, rounding=0, device="cuda",
+                 weight_dtype=torch.bfloat16):
         super().__init__()
         self.in_features, self.out_features = in_features, out_features
         w = torch.randn(out_features, in_features, device=device) * (in_features ** -0.5)
-        self.weight = torch.nn.Parameter(w.to(torch.bfloat16))
+        # weight_dtype=torch.float32 keeps fp32 master weights; the kernels always see a bf16 copy
+        self.weight = torch.nn.Parameter(w.to(weight_dtype))
         self.bias = torch.nn.Parameter(torch.zeros(out_features, dtype=torch.bfloat16, device=device)) if bias else None
         self.rounding = rounding
         self.base_seed = int(seed) & 0xFFFF
@@ -95,5 +97,5 @@ class QuartetLinear(torch.nn.Module):
     def forward(self, x):
         seed = (self.base_seed << 48) | (self.layer_id << 32) | (self.calls & 0xFFFFFFFF)
         self.calls += 1
-        y = QuartetLinearFunction.apply(x, self.weight, seed, self.rounding)
+        y = QuartetLinearFunction.apply(x, self.weight.to(torch.bfloat16), seed, self.rounding)
         return y if self.bias is None else y + self.bias
