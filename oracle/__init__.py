@@ -63,6 +63,13 @@ def _declare(L):
     L.quartet_ref_mxfp4_dequant.argtypes = [_p, _p, _i64, _i64, _p]
     L.quartet_ref_mxfp4_gemm_rows.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, ctypes.c_double,
                                               _i64, _i64, _p]
+    L.quartet_ref_e4m3_decode.restype = ctypes.c_double
+    L.quartet_ref_e4m3_decode.argtypes = [ctypes.c_uint8]
+    L.quartet_ref_e4m3_rtn.restype = ctypes.c_uint8
+    L.quartet_ref_e4m3_rtn.argtypes = [ctypes.c_float]
+    L.quartet_ref_mxfp8_quant.argtypes = [_p, _i64, _i64, _i64, _p, _p]
+    L.quartet_ref_mxfp8_dequant.argtypes = [_p, _p, _i64, _i64, _p]
+    L.quartet_ref_mxfp8_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, ctypes.c_double, _p]
     L.quartet_ref_grad_epilogue.argtypes = [_p, _p, _i64, _i64, ctypes.c_float, _p]
     L.quartet_ref_linear_fwd.argtypes = [_p, _p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p]
     L.quartet_ref_linear_bwd.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64,
@@ -217,6 +224,44 @@ def mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, alpha=1.0, rows=None):
     d = np.zeros((m, n), dtype=np.float64)
     _ok(lib().quartet_ref_mxfp4_gemm_rows(_ptr(ac), _ptr(as_), _ptr(bc), _ptr(bs), m, n, k,
                                           float(alpha), r0, r1, _ptr(d)), "mxfp4_gemm")
+    return d
+
+
+def e4m3_decode(code):
+    return lib().quartet_ref_e4m3_decode(int(code) & 0xFF)
+
+
+def e4m3_rtn(v):
+    return lib().quartet_ref_e4m3_rtn(float(np.float32(v)))
+
+
+def mxfp8_quant(x):
+    """bf16 [rows, k] (uint16 bit patterns) -> (codes [rows, k] E4M3 bytes, scales [rows, k/32] E8M0 bytes)."""
+    xx = _c(x, np.uint16)
+    rows, k = xx.shape
+    codes = np.zeros((rows, k), dtype=np.uint8)
+    scales = np.zeros((rows, k // G), dtype=np.uint8)
+    _ok(lib().quartet_ref_mxfp8_quant(_ptr(xx), rows, k, k, _ptr(codes), _ptr(scales)), "mxfp8_quant")
+    return codes, scales
+
+
+def mxfp8_dequant(codes, scales):
+    c, s = _c(codes, np.uint8), _c(scales, np.uint8)
+    rows, k = c.shape
+    out = np.zeros((rows, k), dtype=np.float64)
+    _ok(lib().quartet_ref_mxfp8_dequant(_ptr(c), _ptr(s), rows, k, _ptr(out)), "mxfp8_dequant")
+    return out
+
+
+def mxfp8_gemm(a_codes, a_scales, b_codes, b_scales, alpha=1.0):
+    ac, as_ = _c(a_codes, np.uint8), _c(a_scales, np.uint8)
+    bc, bs = _c(b_codes, np.uint8), _c(b_scales, np.uint8)
+    m, k = ac.shape
+    n = bc.shape[0]
+    if bc.shape[1] != k:
+        raise ValueError("inner dimensions differ")
+    d = np.zeros((m, n), dtype=np.float64)
+    _ok(lib().quartet_ref_mxfp8_gemm(_ptr(ac), _ptr(as_), _ptr(bc), _ptr(bs), m, n, k, float(alpha), _ptr(d)), "mxfp8_gemm")
     return d
 
 

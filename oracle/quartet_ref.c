@@ -13,6 +13,7 @@
  *                                           : Section 3 "Rounding"; Algorithm 1 Backward
  *   - GEMM_LP  D = (A x SFA)(B x SFB)^T     : Section 4.4 "Stage 2"
  *   - gradient epilogue 16/9 H^-1(G . M)    : Algorithm 1 Backward
+ *   - MXFP8 (E4M3 + E8M0 / 32) comparison format: Section 3; Section 5 "Speedup results"
  * Where the paper is silent the reading taken here is stated next to the code.
  *
  * Arithmetic: every fp32 step is a single IEEE-754 binary32 operation, rounded
@@ -442,6 +443,102 @@ int quartet_ref_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
                            const uint8_t *b_codes, const uint8_t *b_scales,
                            int64_t m, int64_t n, int64_t k, double alpha, double *d) {
     return quartet_ref_mxfp4_gemm_rows(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, 0, m, d);
+}
+
+/* ----------------------------------------------- MXFP8 comparison format
+ * The paper measures its MXFP4 layers against MXFP8 ones (Section 5, "Speedup results").  The
+ * format is the one it names in Section 3 ("MXFP4/6/8"): E4M3 elements (1 sign, 4 exponent bits
+ * of bias 7, 3 mantissa bits; no infinities, S.1111.111 is NaN, largest magnitude 448,
+ * subnormals down to 2^-9) sharing one E8M0 scale per 32 elements.  No rotation, no clipping
+ * mask: plain absolute-maximum scaling, the reading of "MXFP8" taken here:
+ *     scale byte b = max(E - 8, 0) with E the biased fp32 exponent of the group's largest
+ *     magnitude (2^8 <= 448 < 2^9 is the element format's largest binade), element =
+ *     round-to-nearest-even of v 2^(127-b) onto the E4M3 grid, saturating at 448. */
+
+double quartet_ref_e4m3_decode(uint8_t code) {
+    int e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if ((code & 0x7F) == 0x7F) return NAN;
+    v = e == 0 ? ldexp((double)m, -9) : ldexp(1.0 + m / 8.0, e - 7);
+    return (code & 0x80) ? -v : v;
+}
+
+/* nearest E4M3 value, ties to the even mantissa, magnitudes above 448 saturate; NaN -> 0x7F.
+ * Written as "pick the binade, round the mantissa to 3 bits": every step is exact in fp64. */
+uint8_t quartet_ref_e4m3_rtn(float v) {
+    uint8_t sign = (uint8_t)((f32_to_bits(v) >> 31) << 7);
+    double a = fabs((double)v), q;
+    int e, code;
+    if (v != v) return 0x7F;
+    if (a >= 448.0) return (uint8_t)(sign | 0x7E);
+    if (a < ldexp(1.0, -6)) {                     /* subnormal range: multiples of 2^-9 */
+        q = nearbyint(ldexp(a, 9));               /* 0..8, ties to even; 8 is the smallest normal */
+        return (uint8_t)(sign | (int)q);
+    }
+    (void)frexp(a, &e);                           /* a = f 2^e, f in [0.5, 1) -> binade exponent e - 1 */
+    e -= 1;
+    q = nearbyint(ldexp(a, 3 - e));               /* (1 + m/8) 8 = 8 + m, 8..16 */
+    if (q == 16.0) { q = 8.0; e += 1; }
+    code = ((e + 7) << 3) | ((int)q - 8);
+    if (code > 0x7E) code = 0x7E;
+    return (uint8_t)(sign | code);
+}
+
+/* x bf16 [rows x ldx] -> codes [rows x k] (one byte per element), scales [rows x k/32] */
+int quartet_ref_mxfp8_quant(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx,
+                            uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k) || ldx < k) return -1;
+    int64_t gk = k / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t g = 0; g < gk; ++g) {
+            float v[G], amax = 0.0f;
+            for (int i = 0; i < G; ++i) {
+                v[i] = bf16_to_f32(x[r * ldx + g * G + i]);
+                if (fabsf(v[i]) > amax) amax = fabsf(v[i]);
+            }
+            int E = (int)((f32_to_bits(amax) >> 23) & 0xFF);
+            int b = E >= 8 ? E - 8 : 0;
+            float mult = bits_to_f32((uint32_t)(254 - b) << 23);   /* 2^(127-b), exact */
+            scales[r * gk + g] = (uint8_t)b;
+            for (int i = 0; i < G; ++i) codes[r * k + g * G + i] = quartet_ref_e4m3_rtn(v[i] * mult);
+        }
+    return 0;
+}
+
+int quartet_ref_mxfp8_dequant(const uint8_t *codes, const uint8_t *scales, int64_t rows, int64_t k,
+                              double *out) {
+    if (check_quant_args(rows, k)) return -1;
+    int64_t gk = k / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t kk = 0; kk < k; ++kk)
+            out[r * k + kk] = quartet_ref_e4m3_decode(codes[r * k + kk]) * quartet_ref_e8m0_decode(scales[r * gk + kk / G]);
+    return 0;
+}
+
+/* D[m x n] = alpha * sum_k dec(A)[m,k] dec(B)[n,k] for MXFP8 operands, fp64 accumulation in increasing k */
+int quartet_ref_mxfp8_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
+                           const uint8_t *b_codes, const uint8_t *b_scales,
+                           int64_t m, int64_t n, int64_t k, double alpha, double *d) {
+    if (m < 0 || n < 0 || check_quant_args(m, k)) return -1;
+    if (n == 0 || m == 0) return 0;
+    double *da = (double *)malloc(sizeof(double) * (size_t)m * (size_t)(k > 0 ? k : 1));
+    double *db = (double *)malloc(sizeof(double) * (size_t)n * (size_t)(k > 0 ? k : 1));
+    if (!da || !db) { free(da); free(db); return -2; }
+    quartet_ref_mxfp8_dequant(a_codes, a_scales, m, k, da);
+    quartet_ref_mxfp8_dequant(b_codes, b_scales, n, k, db);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double acc = 0.0;
+            const double *pa = da + i * k, *pb = db + j * k;
+            for (int64_t kk = 0; kk < k; ++kk) acc += pa[kk] * pb[kk];
+            d[i * n + j] = alpha * acc;
+        }
+    free(da);
+    free(db);
+    return 0;
 }
 
 /* ------------------------------------------------------- gradient epilogue */
