@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--rounding", type=int, default=0, help="backward rounding: 0 = stochastic, 1 = nearest")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
+    ap.add_argument("--fp8-compare", action="store_true",
+                    help="also time the library's own MXFP8 GEMM and quantizer on the workload's shapes (the paper's comparison format)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-kind time breakdown to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 1 GiB elementwise copy kernel (torch.mul by 1), the known-size "
@@ -126,6 +128,60 @@ def quant_sweep(q, torch, synth):
                             GBps_best=round(bpe * r * c / best / 1e6, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
         del xs, codes, scales, mask
     return out
+
+
+def fp8_compare(q, torch, layers):
+    """The workload's 21 GEMM shapes in MXFP4 and in MXFP8 (same tile skeleton, the matrix cores' FP8 rate is half
+    the FP4 rate), random codes, fp32 results, every launch timed by the library's event pairs; and the forward
+    quantizer of each format on the largest activation."""
+    import statistics
+    dev = "cuda:0"
+    shapes = []
+    for l in layers:
+        shapes += [(l.t, l.o, l.i), (l.t, l.i, l.o), (l.o, l.i, l.t)]
+    reps = 5
+    kinds = (ctypes.c_int * reps)()
+    ms = (ctypes.c_float * reps)()
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        q.check(q.quartet_profile_kinds(0xFFFFFFFF))
+        q.check(q.quartet_profile_enable(reps))
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        n = q.quartet_profile_read(kinds, ms, reps)
+        q.quartet_profile_enable(0)
+        return statistics.median(ms[:n])
+
+    t4 = t8 = flops = 0.0
+    for (m, n, k) in shapes:
+        d = torch.empty((m, n), dtype=torch.float32, device=dev)
+        asc = torch.randint(120, 134, (q.quartet_scale_bytes(m, k),), dtype=torch.uint8, device=dev)
+        bsc = torch.randint(120, 134, (q.quartet_scale_bytes(n, k),), dtype=torch.uint8, device=dev)
+        a4 = torch.randint(0, 256, (m, k // 2), dtype=torch.uint8, device=dev)
+        b4 = torch.randint(0, 256, (n, k // 2), dtype=torch.uint8, device=dev)
+        t4 += timed(lambda: q.check(q.quartet_mxfp4_gemm(a4, asc, b4, bsc, m, n, k, 1.0, d, q.QUARTET_DTYPE_F32, n)))
+        del a4, b4
+        a8 = torch.randint(0, 0x7F, (m, k), dtype=torch.uint8, device=dev)      # no NaN codes
+        b8 = torch.randint(0, 0x7F, (n, k), dtype=torch.uint8, device=dev)
+        t8 += timed(lambda: q.check(q.quartet_mxfp8_gemm(a8, asc, b8, bsc, m, n, k, 1.0, d, q.QUARTET_DTYPE_F32, n)))
+        del a8, b8, d
+        flops += 2.0 * m * n * k
+    big = max(layers, key=lambda l: l.t * l.i)
+    r, c = big.t, big.i
+    codes = torch.empty((r, c), dtype=torch.uint8, device=dev)
+    scales = torch.empty((q.quartet_scale_bytes(r, c),), dtype=torch.uint8, device=dev)
+    mask = torch.empty((r, c // 32), dtype=torch.int32, device=dev)
+    tq4 = timed(lambda: q.check(q.quartet_quant_fwd(big.x, r, c, c, 0, codes, scales, mask)))
+    tq8 = timed(lambda: q.check(q.quartet_mxfp8_quant(big.x, r, c, c, codes, scales)))
+    return {"gemm_shapes": len(shapes),
+            "gemm_mxfp4_tflops": round(flops / t4 / 1e9, 1), "gemm_mxfp8_tflops": round(flops / t8 / 1e9, 1),
+            "gemm_speedup_mxfp4_over_mxfp8": round(t8 / t4, 3),
+            "quantizer_shape": [r, c], "quant_mxfp4_ms": round(tq4, 4), "quant_mxfp8_ms": round(tq8, 4),
+            "paper_context": "the paper reports almost 2x over FP8 for linear layers on an RTX 5090 (Section 1); "
+                             "up to 2x forward and 1.5x backward (Section 5)"}
 
 
 def recorded(config, name, key):
@@ -259,6 +315,8 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    if args.fp8_compare:
+        result["fp8_comparison"] = fp8_compare(q, torch, layers)
     if args.quant_sweep:
         del layers, ws
         torch.cuda.empty_cache()

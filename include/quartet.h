@@ -83,6 +83,8 @@ size_t quartet_scale_bytes(int64_t rows, int64_t k);
 #define QUARTET_KIND_GEMM 3
 #define QUARTET_KIND_EPILOGUE 4
 #define QUARTET_KIND_DEQUANT 5
+#define QUARTET_KIND_FP8_QUANT 6
+#define QUARTET_KIND_FP8_GEMM 7
 int quartet_profile_enable(int max_records);
 int quartet_profile_kinds(unsigned kind_mask);
 int quartet_profile_read(int *kinds, float *ms, int capacity);
@@ -161,6 +163,30 @@ int quartet_mxfp4_gemm_grad(const uint8_t *a_codes, const uint8_t *a_scales,
                             const uint8_t *b_codes, const uint8_t *b_scales,
                             int64_t m, int64_t n, int64_t k, const uint32_t *mask, float scale,
                             void *d, int d_dtype, int64_t ldd, void *stream);
+
+/*
+ * MXFP8 twin of the quantizer and the GEMM, for the comparison the paper draws (Section 5, "Speedup
+ * results": MXFP4 linear layers against MXFP8 ones; Section 3 names the format).  Elements are E4M3
+ * (OCP 8-bit floating point: bias 7, largest magnitude 448, S.1111.111 = NaN, no infinities), one
+ * byte each, with one E8M0 scale per 32 along k in the same tiled layout as MXFP4.
+ *
+ * quartet_mxfp8_quant: x bf16 [rows x ldx] -> codes [rows x k] bytes, scales tiled for [rows x k].
+ *   Per group: scale byte b = max(E - 8, 0), E the biased fp32 exponent of the largest magnitude
+ *   (which lands in the format's top binade); element = round-to-nearest-even of v 2^(127-b),
+ *   saturating at 448.  No rotation, no clipping mask.  k % 32 == 0, ldx % 8 == 0, ldx >= k.
+ * quartet_mxfp8_gemm: D[m x n] = alpha * sum_k dec(A)[m,k] dec(B)[n,k], operands as above
+ *   (a_codes [m x k], b_codes [n x k]), fp32 accumulation on the matrix cores, which align the 64
+ *   products of one instruction to a common exponent: results agree with exact accumulation to
+ *   about 2^-12 of the sum of the products' magnitudes in the worst case (relative Frobenius error
+ *   below 1e-4), not to the last bit.  Arguments and limits
+ *   otherwise as quartet_mxfp4_gemm.
+ */
+int quartet_mxfp8_quant(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx,
+                        uint8_t *codes, uint8_t *scales, void *stream);
+int quartet_mxfp8_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
+                       const uint8_t *b_codes, const uint8_t *b_scales,
+                       int64_t m, int64_t n, int64_t k, float alpha,
+                       void *d, int d_dtype, int64_t ldd, void *stream);
 
 /*
  * Gradient epilogue (Algorithm 1 Backward: 16/9 H_g^-1(G . M)):

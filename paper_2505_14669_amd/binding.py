@@ -25,7 +25,7 @@ EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
     "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr",
-    "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
+    "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
 ]
 
@@ -51,6 +51,8 @@ _lib.quartet_quant_bwd_sr.argtypes = [_p, _i64, _i64, _i64, _int, _u32, _u64, _u
 _lib.quartet_requant_transpose_sr.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u32, _int, _p, _p, _p]
 _lib.quartet_mxfp4_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
 _lib.quartet_mxfp4_gemm_grad.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _p, _f, _p, _int, _i64, _p]
+_lib.quartet_mxfp8_quant.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p]
+_lib.quartet_mxfp8_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
 _lib.quartet_grad_epilogue.argtypes = [_p, _p, _i64, _i64, _f, _p, _int, _p]
 _lib.quartet_mxfp4_dequant.argtypes = [_p, _p, _i64, _i64, _p, _p]
 _lib.quartet_linear_fwd.argtypes = [_p, _p, _i64, _i64, _i64, _p, _int, _p, _p, _p, _p, _p, _p, _p]
@@ -104,7 +106,7 @@ def quartet_sr_bits():
     return _lib.quartet_sr_bits()
 
 
-KIND_NAMES = ["quant_fwd", "quant_bwd", "requant", "gemm", "epilogue", "dequant"]
+KIND_NAMES = ["quant_fwd", "quant_bwd", "requant", "gemm", "epilogue", "dequant", "fp8_quant", "fp8_gemm"]
 QUARTET_KIND_GEMM = 3
 
 
@@ -154,6 +156,15 @@ def quartet_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, 
 def quartet_mxfp4_gemm_grad(a_codes, a_scales, b_codes, b_scales, m, n, k, mask, scale, d, d_dtype, ldd, stream=None):
     return _lib.quartet_mxfp4_gemm_grad(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
                                         _ptr(mask), scale, _ptr(d), d_dtype, ldd, _stream(stream))
+
+
+def quartet_mxfp8_quant(x_bf16, rows, k, ldx, codes, scales, stream=None):
+    return _lib.quartet_mxfp8_quant(_ptr(x_bf16), rows, k, ldx, _ptr(codes), _ptr(scales), _stream(stream))
+
+
+def quartet_mxfp8_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_dtype, ldd, stream=None):
+    return _lib.quartet_mxfp8_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
+                                   alpha, _ptr(d), d_dtype, ldd, _stream(stream))
 
 
 def quartet_grad_epilogue(g, mask, m, n, scale, out, out_dtype, stream=None):

@@ -259,6 +259,29 @@ int quartet_mxfp4_gemm_grad(const uint8_t* a_codes, const uint8_t* a_scales,
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
+int quartet_mxfp8_quant(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx,
+                        uint8_t* codes, uint8_t* scales, void* stream) {
+    if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
+    if (!aligned16(x_bf16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
+    int rc = check_quant_shape(rows, k, ldx, 0);
+    if (rc) return rc;
+    ProfileScope prof(QUARTET_KIND_FP8_QUANT, (hipStream_t)stream);
+    hipError_t e = quartet::launch_mxfp8_quant(x_bf16, rows, k, ldx, codes, scales, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_mxfp8_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
+                       const uint8_t* b_codes, const uint8_t* b_scales,
+                       int64_t m, int64_t n, int64_t k, float alpha,
+                       void* d, int d_dtype, int64_t ldd, void* stream) {
+    int rc = check_gemm_args(a_codes, a_scales, b_codes, b_scales, m, n, k, d, d_dtype, ldd);
+    if (rc) return rc;
+    ProfileScope prof(QUARTET_KIND_FP8_GEMM, (hipStream_t)stream);
+    hipError_t e = quartet::launch_mxfp8_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
+                                              d_dtype == QUARTET_DTYPE_BF16, ldd, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
 int quartet_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, float scale,
                           void* out, int out_dtype, void* stream) {
     if (!g || !out) return QUARTET_EINVAL;

@@ -1,0 +1,158 @@
+// Pieces shared by the matrix-core GEMM kernels: buffer resources, LDS-direct loads and the epilogue
+// that takes a wave's accumulator tile through LDS to full-line stores.
+#pragma once
+#include "device_common.h"
+
+namespace quartet {
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = f2u(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// Raw buffer resource over [base, base + bytes): loads past the end return zero, which is how ragged
+// tile edges are handled without per-load predicates.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here reaches
+
+// Epilogue of both kernels.  The wave's accumulator tile goes through LDS one 32-column slice at a
+// time and comes back with 8 consecutive lanes holding the 32 columns of one row (4 each): a
+// store instruction then writes 8 whole 128-byte lines.  The slice is exactly one Hadamard
+// group, so with FUSED the gradient epilogue of Algorithm 1 Backward,
+// D = alpha * H_32_along_n(acc . M), is applied on the way: mask select, butterflies of stride 1
+// and 2 inside the lane and of stride 4, 8, 16 between the 8 lanes (the lower partner forms a + b,
+// the upper a - b = b' + (-a'), bit-identical to the in-register transform), the normalization,
+// then the scale.  Lane i of the 8 holds 4-column chunk i ^ (i & 4 ? 3 : 0), which makes the three
+// partners lane ^ 1, lane ^ 2 and 7 - lane: all reachable by DPP, none through LDS.
+// wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
+constexpr uint32_t kEpiStride = 36;   // floats per LDS row (144 bytes: 16-byte aligned, rows spread over banks)
+
+template <int DPP_CTRL>
+__device__ __forceinline__ float butterfly_across(float own, uint32_t upper_sign) {
+    float other = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(own), DPP_CTRL, 0xF, 0xF, true));
+    return other + __uint_as_float(__float_as_uint(own) ^ upper_sign);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141;
+
+// FULL: the whole wave tile lies inside D and rows are 16-byte aligned, so nothing is predicated.
+template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
+__device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
+                                                const uint32_t* mask, float alpha, uint32_t row_base,
+                                                uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+    constexpr uint32_t ITERS = TM * 4;   // 8 rows per pass
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
+    const uint32_t up4 = (c & 1u) << 31, up8 = (c & 2u) << 30, up16 = (c & 4u) << 29;   // sign flip of the upper partner
+    const bool wide = FULL || (ldd & 3u) == 0u;   // every 4-column chunk starts 16-byte (fp32) / 8-byte (bf16) aligned
+    const uint32_t mask_ld = n >> 5;
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t gcol = col_base + j * 32u;
+        uint32_t mw[ITERS];
+        if (FUSED) {
+#pragma unroll
+            for (uint32_t it = 0; it < ITERS; ++it) {
+                const uint32_t grow = row_base + it * 8u + sub;
+                if (FULL) mw[it] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
+                else mw[it] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
+            }
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+            for (uint32_t r = 0; r < 16; ++r)
+                wbuf[(i * 32u + (r >> 2) * 8u + lhalf * 4u + (r & 3u)) * kEpiStride + lrow] = acc[i][j][r];
+        float4 slice[ITERS];   // all reads in flight before the first use: one wave per SIMD hides no LDS latency
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it)
+            slice[it] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * kEpiStride + 4u * c]);
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it) {
+            const uint32_t rr = it * 8u + sub, grow = row_base + rr;
+            float v0 = slice[it].x, v1 = slice[it].y, v2 = slice[it].z, v3 = slice[it].w;
+            if (FUSED) {
+                // bit clear -> +0: and with the bit spread over the word
+                const int32_t bits = (int32_t)(mw[it] >> (4u * c));
+                v0 = __uint_as_float(__float_as_uint(v0) & (uint32_t)((bits << 31) >> 31));
+                v1 = __uint_as_float(__float_as_uint(v1) & (uint32_t)((bits << 30) >> 31));
+                v2 = __uint_as_float(__float_as_uint(v2) & (uint32_t)((bits << 29) >> 31));
+                v3 = __uint_as_float(__float_as_uint(v3) & (uint32_t)((bits << 28) >> 31));
+                const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
+                v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
+                v0 = butterfly_across<kDppXor1>(v0, up4); v1 = butterfly_across<kDppXor1>(v1, up4);   // stride 4
+                v2 = butterfly_across<kDppXor1>(v2, up4); v3 = butterfly_across<kDppXor1>(v3, up4);
+                v0 = butterfly_across<kDppXor2>(v0, up8); v1 = butterfly_across<kDppXor2>(v1, up8);   // stride 8
+                v2 = butterfly_across<kDppXor2>(v2, up8); v3 = butterfly_across<kDppXor2>(v3, up8);
+                v0 = butterfly_across<kDppHalfMirror>(v0, up16); v1 = butterfly_across<kDppHalfMirror>(v1, up16);   // stride 16
+                v2 = butterfly_across<kDppHalfMirror>(v2, up16); v3 = butterfly_across<kDppHalfMirror>(v3, up16);
+                v0 = v0 * kInvSqrt32; v1 = v1 * kInvSqrt32; v2 = v2 * kInvSqrt32; v3 = v3 * kInvSqrt32;
+            }
+            v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
+            if (!FULL && grow >= m) continue;
+            const uint32_t col = gcol + 4u * c;
+            const size_t at = (size_t)grow * ldd + col;
+            if (OUT_BF16) {
+                uint16_t* dst = static_cast<uint16_t*>(d) + at;
+                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                } else {
+                    if (col < n) dst[0] = (uint16_t)h0;
+                    if (col + 1u < n) dst[1] = (uint16_t)h1;
+                    if (col + 2u < n) dst[2] = (uint16_t)h2;
+                    if (col + 3u < n) dst[3] = (uint16_t)h3;
+                }
+            } else {
+                float* dst = static_cast<float*>(d) + at;
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                } else {
+                    if (col < n) dst[0] = v0;
+                    if (col + 1u < n) dst[1] = v1;
+                    if (col + 2u < n) dst[2] = v2;
+                    if (col + 3u < n) dst[3] = v3;
+                }
+            }
+        }
+    }
+}
+
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
+__device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
+                                           const uint32_t* mask, float alpha, uint32_t row_base,
+                                           uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+    const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n &&
+                      (!FUSED || mask != nullptr);   // wave-uniform
+    if (full) store_tile_body<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
+    else store_tile_body<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
+}
+
+// Depth of the LDS ring of the large-tile kernels.
+constexpr uint32_t kRing = 4;
+
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4i_t make_rsrc_words(const void* base, uint32_t bytes) {
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    v4i_t r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), (int)bytes, 0x00020000};
+    return r;
+}
+
+// 16 bytes per lane from the buffer resource at byte offset voff (past the end: zeros) to LDS byte
+// address lds_base + 16 * lane.  lds_base must be wave-uniform.  Completion is counted by vmcnt.
+__device__ __forceinline__ void lds_direct_load16(v4i_t rsrc, uint32_t voff, uint32_t lds_base) {
+#ifdef QUARTET_TIMING_WITHOUT_LOADS   // timing experiments only: results are meaningless
+    (void)rsrc; (void)voff; (void)lds_base;
+    return;
+#endif
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
+}
+
+}  // namespace quartet
