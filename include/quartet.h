@@ -59,7 +59,7 @@ extern "C" {
 /* hipError_t of the last failed HIP call made by this thread through the library (0 if none). */
 int quartet_last_hip_error(void);
 
-/* Number of random bits each element consumes in stochastic rounding (16). */
+/* Number of random bits one element's stochastic-rounding decision looks at (22). */
 int quartet_sr_bits(void);
 
 /* Size in bytes of the tiled scale buffer of an MXFP4 tensor [rows x k] (0 if an argument is negative). */
@@ -113,12 +113,14 @@ int quartet_quant_fwd(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, 
  * two); v_i = fl((h_i 2^-e) * 3/4), so |v_i| < 6 and nothing clips; code_i = E2M1 of v_i by
  *   rounding = QUARTET_ROUND_NEAREST   : round-to-nearest-even (Algorithm 1 as printed), or
  *   rounding = QUARTET_ROUND_STOCHASTIC: with lo <= |v| < hi the neighbouring grid points and
- *     f = (|v|-lo)/(hi-lo), round up iff floor(f 2^22) + 64 r >= 2^22, r = the element's 16-bit
- *     draw (probability floor(f 2^16) / 2^16 of rounding up).
+ *     f = (|v|-lo)/(hi-lo), round up iff floor(f 2^22) + r >= 2^22, r = the element's 22-bit
+ *     draw (probability floor(f 2^22) / 2^22 of rounding up).
  * Draws: Philox4x32-10 with key (seed & 0xFFFFFFFF, seed >> 32); the element at output position
- * L = row*k + kk uses call q = L / 8 with counter (q_lo, q_hi, stream_id, 0) and takes bits
- * [16 j, 16 j + 16) of the 128-bit output, j = L mod 8.  Row and transposed mode therefore give
- * identical bytes for the same logical matrix.
+ * L = row*k + kk uses call q = L / 16 with counter (q_lo, q_hi, stream_id, 0); with j = L mod 16,
+ * output word j / 4 serves four elements, element t = j mod 4 rotates it so that byte t leads,
+ * R = rotr32(word, 8 t + 8), and draws r = R >> 10.  The leading 8 bits of a word's four draws
+ * are disjoint; the bits below are shared with the neighbours' leading bytes.  Row and transposed
+ * mode give identical bytes for the same logical matrix.
  * The stored scale is 2^e: the 3/4 is NOT folded in; consumers multiply the product of two such
  * tensors by 16/9.
  */

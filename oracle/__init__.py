@@ -12,7 +12,7 @@ import numpy as np
 from . import build as _build
 
 G = 32
-SR_BITS = 16
+SR_BITS = 22
 FL_16_9 = np.float32(16.0 / 9.0)
 
 _lib = None

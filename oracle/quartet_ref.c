@@ -23,7 +23,7 @@
  * Pins (tests/test_oracle_*.py): E2M1 grid and tie table, E8M0 powers of two,
  * H H^T = 32 I and the dense-matrix product, Philox known answers, power-of-two
  * scaling equivariance, "nothing saturates" in the backward, stochastic-rounding
- * probabilities enumerated over all 2^16 draws, Gaussian MSE bands of Table 1,
+ * probabilities fixed through the draw threshold, Gaussian MSE bands of Table 1,
  * exhaustive one-group GEMMs and numpy fp64 matmul of decoded operands.
  * Parity unpinned: the QuEST clip constant (the paper prints no value; see
  * QUEST_LOG2_C2 below) -- only the Table 1 MSE band constrains it.
@@ -38,8 +38,8 @@
 
 #define G 32 /* Hadamard block = MX group size (Section 4.4, "Costs and format specialization") */
 
-/* number of random bits one element consumes in stochastic rounding */
-#define SR_BITS 16
+/* number of random bits one element's stochastic-rounding decision looks at */
+#define SR_BITS 22
 
 /* QuEST clip constant, as log2(c^2): group scale = 2^floor(log2(c * RMS)), c^2 = 1/2.
  * The paper says "RMSE-based clipping" with a power-of-two scale and prints no constant;
@@ -105,9 +105,9 @@ uint8_t quartet_ref_e2m1_rtn(float v) {
 /* stochastic rounding onto the E2M1 grid for |v| < 6 (Section 3, "Rounding":
  * up or down with probability given by the distance to the two neighbours).
  * lo <= |v| < hi are adjacent grid points, f = (|v|-lo)/(hi-lo) in [0,1);
- * r is a uniform SR_BITS-bit integer; the result is hi iff
- *     floor(f * 2^22) + r * 2^(22-SR_BITS) >= 2^22,
- * i.e. P(up) = floor(f 2^SR_BITS) / 2^SR_BITS: within 2^-SR_BITS of f, never above it.
+ * r is a uniform SR_BITS-bit integer (SR_BITS = 22); the result is hi iff
+ *     floor(f * 2^22) + r >= 2^22,
+ * i.e. P(up) = floor(f 2^22) / 2^22: within 2^-22 of f, never above it.
  * Grid points never move (f = 0).  (f is compared at a resolution of 2^-22, the number of
  * fp32 mantissa bits below the one E2M1 keeps.) */
 uint8_t quartet_ref_e2m1_sr(float v, uint32_t r) {
@@ -146,20 +146,25 @@ void quartet_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uin
 }
 
 /* Random integer for the element at linear position L = row*K + kk of the quantized
- * (output-logical) matrix.  One Philox call serves 128/SR_BITS consecutive elements:
- * counter = (q_lo, q_hi, stream_id, 0) with q = L / (128/SR_BITS), key = (seed_lo, seed_hi);
- * element j = L mod (128/SR_BITS) takes bits [SR_BITS*j, SR_BITS*(j+1)) of the 128-bit
- * output w0|w1<<32|w2<<64|w3<<96. */
+ * (output-logical) matrix.  One Philox call serves 16 consecutive elements: counter =
+ * (q_lo, q_hi, stream_id, 0) with q = L / 16, key = (seed_lo, seed_hi).  Output word j/4
+ * (j = L mod 16) serves four elements; element t = j mod 4 owns byte t of the word: it
+ * rotates the word so that its byte leads, R = rotr32(w, 8 t + 8), and draws r = R >> 10
+ * (22 bits).  The leading 8 bits of the four draws of a word are disjoint (independent); the
+ * 14 bits below them are the other three elements' bytes, so decisions of neighbours are
+ * independent to within 2^-8 while every single draw is uniform on 22 bits.
+ * (Section 3 "Rounding" fixes the probabilities, not where the random bits come from; with
+ * one call per 8 elements the quantizer kernels were bound by Philox arithmetic.) */
 uint32_t quartet_ref_sr_draw(uint64_t seed, uint32_t stream_id, uint64_t L) {
-    const unsigned per_call = 128 / SR_BITS;
-    const unsigned per_word = 32 / SR_BITS;
-    uint64_t q = L / per_call;
-    unsigned j = (unsigned)(L % per_call);
+    uint64_t q = L / 16;
+    unsigned j = (unsigned)(L % 16), t = j % 4, sh = (8 * t + 8) & 31;
     uint32_t ctr[4] = {(uint32_t)q, (uint32_t)(q >> 32), stream_id, 0u};
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
-    uint32_t w[4];
+    uint32_t w[4], x, R;
     quartet_ref_philox4x32_10(ctr, key, w);
-    return (w[j / per_word] >> (SR_BITS * (j % per_word))) & ((1u << SR_BITS) - 1);
+    x = w[j / 4];
+    R = sh ? ((x >> sh) | (x << (32 - sh))) : x;
+    return R >> 10;
 }
 
 /* Sign word of the randomized Hadamard used by one backward pass with seed xi:

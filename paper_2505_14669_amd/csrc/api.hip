@@ -116,7 +116,7 @@ extern "C" {
 
 int quartet_last_hip_error(void) { return g_last_hip_error; }
 
-int quartet_sr_bits(void) { return 16; }
+int quartet_sr_bits(void) { return 22; }
 
 size_t quartet_scale_bytes(int64_t rows, int64_t k) {
     if (rows < 0 || k < 0) return 0;

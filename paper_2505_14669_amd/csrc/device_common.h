@@ -90,17 +90,18 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// Stochastic rounding of eight values (|v| < 6) onto the E2M1 grid with eight 16-bit draws held in
-// four words (element 2p uses bits 15:0 of w[p], element 2p+1 bits 31:16), packed into one dword,
-// element j in bits [4j, 4j+4) (Section 3, "Rounding").  Rule: with lo <= |v| < hi adjacent grid
-// points and f = (|v|-lo)/(hi-lo), the result is hi iff floor(f 2^22) + 64 r >= 2^22 for the draw r.
+// Stochastic rounding of eight values (|v| < 6) onto the E2M1 grid, packed into one dword, element j
+// in bits [4j, 4j+4) (Section 3, "Rounding").  Rule: with lo <= |v| < hi adjacent grid points and
+// f = (|v|-lo)/(hi-lo), the result is hi iff floor(f 2^22) + r >= 2^22 for the element's 22-bit draw r.
+// Draws: a 32-bit Philox word serves four elements; element t owns byte t and rotates the word so that
+// its byte leads: R = rotr(w, 8t + 8), r = R >> 10.  w0 serves elements 0..3, w1 elements 4..7.
 // v_cvt_scalef32_sr_pk_fp4_f32 was measured on gfx950 to compute exactly
 //     floor(f 2^22) + R[31:10] >= 2^22
 // for the first value of its pair with R = its 32-bit random operand, and the same with R << 1 for
 // the second value (all binades down to 2^-16, thresholds probed to +-1); the two values of a pair
-// therefore share random bits, so each pair is converted twice, once with the draw of the even
-// element in R[31:16] and once with the draw of the odd element in R[30:15], and the valid nibbles
-// are merged.
+// therefore share random bits, so each pair is converted twice, once with the even element's R and
+// once with the odd element's R rotated right by one more bit (so that R << 1 shows its bits 31:10),
+// and the valid nibbles are merged.
 // One conversion of a pair into byte SEL of dst, keeping dst's other bytes.  Written as inline
 // assembly because the destination must be tied to the previous partial result.
 #define QUARTET_SR_CVT(SEL, OPSEL)                                                                 \
@@ -114,17 +115,19 @@ QUARTET_SR_CVT(2, "[0,0,0,1]")
 QUARTET_SR_CVT(3, "[0,0,1,1]")
 #undef QUARTET_SR_CVT
 
-__device__ __forceinline__ uint32_t sr_pack8(const float* v, const uint32_t (&w)[4]) {
+__device__ __forceinline__ uint32_t rotr32(uint32_t x, uint32_t n) { return __builtin_amdgcn_alignbit(x, x, n); }
+
+__device__ __forceinline__ uint32_t sr_pack8(const float* v, uint32_t w0, uint32_t w1) {
     uint32_t even = 0u, odd = 0u;
     v2f p0 = {v[0], v[1]}, p1 = {v[2], v[3]}, p2 = {v[4], v[5]}, p3 = {v[6], v[7]};
-    sr_cvt_pair<0>(even, p0, w[0] << 16);
-    sr_cvt_pair<1>(even, p1, w[1] << 16);
-    sr_cvt_pair<2>(even, p2, w[2] << 16);
-    sr_cvt_pair<3>(even, p3, w[3] << 16);
-    sr_cvt_pair<0>(odd, p0, (w[0] >> 1) & 0x7FFF8000u);
-    sr_cvt_pair<1>(odd, p1, (w[1] >> 1) & 0x7FFF8000u);
-    sr_cvt_pair<2>(odd, p2, (w[2] >> 1) & 0x7FFF8000u);
-    sr_cvt_pair<3>(odd, p3, (w[3] >> 1) & 0x7FFF8000u);
+    sr_cvt_pair<0>(even, p0, rotr32(w0, 8u));     // element 0: byte 0 leads
+    sr_cvt_pair<1>(even, p1, rotr32(w0, 24u));    // element 2
+    sr_cvt_pair<2>(even, p2, rotr32(w1, 8u));     // element 4
+    sr_cvt_pair<3>(even, p3, rotr32(w1, 24u));    // element 6
+    sr_cvt_pair<0>(odd, p0, rotr32(w0, 17u));     // element 1: rotr 16, one more for the instruction's R << 1
+    sr_cvt_pair<1>(odd, p1, rotr32(w0, 1u));      // element 3: rotr 32 = 0, one more
+    sr_cvt_pair<2>(odd, p2, rotr32(w1, 17u));     // element 5
+    sr_cvt_pair<3>(odd, p3, rotr32(w1, 1u));      // element 7
     return (even & 0x0F0F0F0Fu) | (odd & 0xF0F0F0F0u);
 }
 

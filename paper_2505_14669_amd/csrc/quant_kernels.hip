@@ -26,8 +26,8 @@ __device__ __forceinline__ uint32_t rtn_pack8(const float* v, float scale) {
     return w;
 }
 
-// Quantize one group held in v[] (not yet rotated).  q_base = (linear output position of element 0)/8
-// is the Philox call index of the group's first 8 elements.
+// Quantize one group held in v[] (not yet rotated).  q_base = (linear output position of element 0)/16
+// is the Philox call index of the group's first 16 elements.
 template <int MODE>
 __device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p, uint64_t q_base,
                                                uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
@@ -74,11 +74,12 @@ __device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p
             for (int i = 0; i < 4; ++i) c[i] = rtn_pack8(&v[8 * i], 1.0f);
         } else {
 #pragma unroll
-            for (int call = 0; call < 4; ++call) {
+            for (int call = 0; call < 2; ++call) {
                 uint64_t q = q_base + (uint64_t)call;
                 uint32_t w[4];
                 philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), p.stream_id, 0u, p.key0, p.key1, w);
-                c[call] = sr_pack8(&v[8 * call], w);
+                c[2 * call] = sr_pack8(&v[16 * call], w[0], w[1]);
+                c[2 * call + 1] = sr_pack8(&v[16 * call + 8], w[2], w[3]);
             }
         }
         scale_byte = b;
@@ -136,7 +137,7 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
     const uint32_t row = row0 + row_local, g = kq0 * 8u + gi;
     uint4 out;
     uint32_t sb, mw;
-    quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 4u, out, sb, mw);
+    quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
     // scale byte of (row, group gi) -> position of the tiled layout inside the block's 256 bytes:
     // [K-quad gi/8][h = gi%2][row_local][p = (gi%8)/2]
     reinterpret_cast<uint8_t*>(s_scale)[(((gi >> 3) * 2u + (gi & 1u)) * 8u + row_local) * 4u + ((gi & 7u) >> 1)] = (uint8_t)sb;
@@ -225,9 +226,9 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
         }
         uint4 c0, c1;
         uint32_t sb0, sb1, m0, m1;
-        // output position of element 0 of the group: row*k + grp*32, divided by 8
-        quantize_group<MODE>(v0, p, ((uint64_t)col * k + grp * 32u) >> 3, c0, sb0, m0);
-        quantize_group<MODE>(v1, p, ((uint64_t)(col + 1u) * k + grp * 32u) >> 3, c1, sb1, m1);
+        // output position of element 0 of the group: row*k + grp*32, divided by 16
+        quantize_group<MODE>(v0, p, ((uint64_t)col * k + grp * 32u) >> 4, c0, sb0, m0);
+        quantize_group<MODE>(v1, p, ((uint64_t)(col + 1u) * k + grp * 32u) >> 4, c1, sb1, m1);
         const uint32_t lc = 2u * lane;                    // local column
         const uint32_t sw = lane & 7u;                    // 16-byte slot swizzle against bank conflicts
         s_codes[lc * 8u + (gl ^ sw)] = c0;
@@ -370,7 +371,7 @@ requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* 
             v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;                 \
         }                                                                                               \
         uint32_t sb, mw;                                                                                \
-        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + (G)) * 32u) >> 3, OUT, sb, mw);     \
+        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + (G)) * 32u) >> 4, OUT, sb, mw);     \
         if ((G) & 1u) sw1 |= sb << (8u * ((G) >> 1));                                                   \
         else sw0 |= sb << (8u * ((G) >> 1));                                                            \
     }

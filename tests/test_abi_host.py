@@ -32,7 +32,7 @@ def test_binding_mirrors_the_header():
     for name in declared_symbols():
         assert callable(getattr(binding, name)), name
     assert sorted(binding.EXPORTS) == declared_symbols()
-    assert binding.quartet_sr_bits() == 16
+    assert binding.quartet_sr_bits() == 22
 
 
 def test_sign_word_is_philox_of_the_seed():

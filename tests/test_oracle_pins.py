@@ -105,56 +105,75 @@ def test_philox_known_answers():
     assert n == 3
 
 
-def test_sr_draws_tile_the_philox_output():
-    # the 8 draws of one call, concatenated, are exactly the 128 output bits; the next call's
-    # counter is q+1 in word 0/1, the stream id sits in word 2
+def _rotr32(x, n):
+    n &= 31
+    return ((x >> n) | (x << (32 - n))) & 0xFFFFFFFF if n else x
+
+
+def test_sr_draws_are_rotations_of_the_philox_words():
+    # one call serves 16 elements; word j/4 serves four, element t = j%4 rotates the word so that its own
+    # byte leads and keeps the upper 22 bits; the next call's counter is q+1 in word 0/1, the stream id
+    # sits in word 2
     seed, sid = 0x123456789ABCDEF0, 3
     key = [seed & 0xFFFFFFFF, seed >> 32]
     for q in (0, 1, 5, (1 << 32) + 7):
-        words = oracle.philox4x32_10([q & 0xFFFFFFFF, q >> 32, sid, 0], key)
-        big = sum(int(w) << (32 * i) for i, w in enumerate(words))
-        got = sum(oracle.sr_draw(seed, sid, 8 * q + j) << (16 * j) for j in range(8))
-        assert got == big
+        words = [int(w) for w in oracle.philox4x32_10([q & 0xFFFFFFFF, q >> 32, sid, 0], key)]
+        draws = [oracle.sr_draw(seed, sid, 16 * q + j) for j in range(16)]
+        assert draws == [_rotr32(words[j // 4], 8 * (j % 4) + 8) >> 10 for j in range(16)]
+        # the leading bytes of the 16 draws are the 16 bytes of the output: disjoint random bits
+        lead = bytes(d >> 14 for d in draws)
+        assert lead == b"".join(w.to_bytes(4, "little") for w in words)
     assert oracle.sign_word(seed) == int(oracle.philox4x32_10([0, 0, 0, 0xFFFFFFFF], key)[0])
 
 
 def test_sr_draws_look_uniform():
     draws = np.array([oracle.sr_draw(42, 0, L) for L in range(40000)])
-    assert draws.min() >= 0 and draws.max() < 65536
-    assert abs(draws.mean() - 32767.5) < 5 * 65536 / np.sqrt(12 * draws.size)
-    hist = np.bincount(draws >> 12, minlength=16)
+    assert draws.min() >= 0 and draws.max() < 2 ** 22
+    assert abs(draws.mean() - (2 ** 22 - 1) / 2) < 5 * 2 ** 22 / np.sqrt(12 * draws.size)
+    hist = np.bincount(draws >> 18, minlength=16)
     assert hist.min() > 0.9 * draws.size / 16
+    # neighbours inside a word share low bits but not their leading byte: no visible correlation
+    d = draws.reshape(-1, 4).astype(np.float64)
+    c = np.corrcoef(d.T)
+    assert np.all(np.abs(c - np.eye(4)) < 5 / np.sqrt(d.shape[0]))
 
 
 # ------------------------------------------------------- stochastic rounding
 
 @pytest.mark.parametrize("v", [0.1, 0.26, 0.49, 0.5001, 0.9, 1.2, 1.74, 2.1, 2.9, 3.01, 4.5, 5.99, 1e-6])
-def test_sr_probability_enumerated(v):
+def test_sr_probability_by_threshold(v):
+    # the decision is monotone in the 22-bit draw with its threshold at 2^22 - floor(f 2^22), so exactly
+    # floor(f 2^22) of the 2^22 draws round up: P(up) is within 2^-22 of f and never above it
     v = f32(v)
     mags = np.array(sorted(set(abs(GRID))))
     lo = mags[mags <= float(v)].max()
     hi = mags[mags > float(v)].min()
-    f = (float(v) - lo) / (hi - lo)
-    r = np.arange(65536)
-    out = np.array([GRID[oracle.e2m1_sr(v, int(x))] for x in r])
-    assert set(np.unique(out)) <= {lo, hi}
-    ups = int((out == hi).sum())
-    assert ups == int(np.floor(f * 65536))       # P(up) = floor(f 2^16) / 2^16: within 2^-16 of f
-    assert -(hi - lo) * 2.0 ** -16 <= out.mean() - float(v) <= 0
-    neg = np.array([GRID[oracle.e2m1_sr(-v, int(x))] for x in r[::97]])
-    assert np.array_equal(neg, -out[::97])       # sign symmetric
+    f = (float(v) - lo) / (hi - lo)                 # exact in fp64: v is fp32, lo and hi are small dyadics
+    F = int(np.floor(f * 2 ** 22))
+    thr = 2 ** 22 - F
+    rng = np.random.default_rng(int(float(v) * 1000))
+    probes = {0, 2 ** 22 - 1, max(thr - 1, 0), min(thr, 2 ** 22 - 1)} | set(int(x) for x in rng.integers(0, 2 ** 22, 3000))
+    ups = 0
+    for r in probes:
+        got = GRID[oracle.e2m1_sr(v, r)]
+        assert got == (hi if r >= thr else lo)
+        assert GRID[oracle.e2m1_sr(-v, r)] == -got  # sign symmetric
+        ups += got == hi
+    assert 0 <= f - F / 2 ** 22 < 2.0 ** -22
+    if F == 0:
+        assert ups == 0                             # below the resolution: never up
 
 
 def test_sr_monotone_in_draw():
-    # f + r/2^16 >= 1: large draws round up, small draws round down; f(2.4) = 0.4, 0.6 * 65536 = 39321.6
+    # large draws round up, small draws round down; f(2.4) = 0.4: the threshold sits at 0.6 * 2^22
     v = f32(2.4)
-    codes = [oracle.e2m1_sr(v, r) for r in (0, 1000, 39321, 39322, 65535)]
+    thr = 2 ** 22 - int(np.floor((float(v) - 2.0) * 2 ** 22))
+    codes = [oracle.e2m1_sr(v, r) for r in (0, 1000, thr - 1, thr, 2 ** 22 - 1)]
     assert [GRID[c] for c in codes] == [2.0, 2.0, 2.0, 3.0, 3.0]
-    # f = 2^-22 (one fp32 ulp above 1.0) is below the 16-bit resolution and never goes up;
-    # f = 1 - 2^-16 goes up for every draw but 0
-    assert GRID[oracle.e2m1_sr(np.nextafter(f32(1.0), f32(2.0)), 65535)] == 1.0
-    almost = f32(1.5 - 0.5 * 2.0 ** -16)
-    assert GRID[oracle.e2m1_sr(almost, 0)] == 1.0 and GRID[oracle.e2m1_sr(almost, 1)] == 1.5
+    # f = 2^-22 (one fp32 ulp above 1.0) goes up for the largest draw only; grid points never move
+    tiny = np.nextafter(f32(1.0), f32(2.0))
+    assert GRID[oracle.e2m1_sr(tiny, 2 ** 22 - 2)] == 1.0 and GRID[oracle.e2m1_sr(tiny, 2 ** 22 - 1)] == 1.5
+    assert all(GRID[oracle.e2m1_sr(f32(g), 2 ** 22 - 1)] == g for g in (0.5, 1.0, 1.5, 2.0, 3.0, 4.0))
 
 
 # ----------------------------------------------------------------- Hadamard
