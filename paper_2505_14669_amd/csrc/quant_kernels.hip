@@ -164,14 +164,15 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
     }
 }
 
-// ------------------------------------------------------------------ transposed sources
-// Logical A[rows x k] = S^T where the source S has k rows.  SRC = 0: S is bf16 [k x ldx];
-// SRC = 1: S is MXFP4 [k x rows] (codes [k x rows/2], scales [k x rows/32]), decoded exactly.
-// Block tile: 8 groups (256 source rows) x 128 source columns; wave w owns groups 2w, 2w+1;
-// lane l owns columns 2l, 2l+1.
-template <int MODE, bool MASK, int SRC>
-__global__ void __launch_bounds__(256)
-quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict__ src_scales,
+// ------------------------------------------------------------------ transposed mode, bf16 source
+// Logical A[rows x k] = S^T where the source S is bf16 [k x ldx].
+// Block tile: 8 groups (256 source rows, one K-quad of the output) x 128 source columns; wave w owns
+// groups 2w, 2w+1; lane l owns columns 2l, 2l+1.  Blocks are numbered K-quad first: the blocks that
+// run at the same time then write neighbouring 128-byte lines of the same output rows (measured 10 %
+// faster than column-tile first, where every block's lines lie a whole output row apart).
+template <int MODE, bool MASK>
+__global__ void __launch_bounds__(256, 4)   // 4 waves per SIMD: at most 128 registers
+quant_transposed_kernel(const uint16_t* __restrict__ src,
                         uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
                         uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
     __shared__ uint4 s_codes[128 * 8];
@@ -179,65 +180,48 @@ quant_transposed_kernel(const void* __restrict__ src, const uint8_t* __restrict_
     __shared__ uint32_t s_mask[128 * 8];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
     const uint32_t gk = k >> 5;
-    const uint32_t col0 = blockIdx.x * 128u;
-    const uint32_t grp0 = blockIdx.y * 8u;
+    const uint32_t col0 = blockIdx.y * 128u;
+    const uint32_t grp0 = blockIdx.x * 8u;
     const uint32_t col = col0 + 2u * lane;                // even; rows is even, so col+1 < rows too
-    const bool col_ok = col < rows;
-    // bf16 source: the block's corner through a buffer resource that ends with the last column of the
-    // last source row (unused, with an empty range, for an MXFP4 source)
+    // the block's corner of the source through a buffer resource that ends with the last column of the
+    // last source row
     const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
     const uint32_t src_cols = (rows - col0) < 128u ? (rows - col0) : 128u;
     const __amdgpu_buffer_rsrc_t res_x = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(static_cast<const uint16_t*>(src) + (SRC == 0 ? (size_t)grp0 * 32u * ldx + col0 : 0)), 0,
-        SRC == 0 ? (int)(((src_rows - 1u) * (uint32_t)ldx + src_cols) * 2u) : 0, 0x00020000);
+        const_cast<uint16_t*>(src + (size_t)grp0 * 32u * ldx + col0), 0,
+        (int)(((src_rows - 1u) * (uint32_t)ldx + src_cols) * 2u), 0x00020000);
 
-#pragma unroll 1
+    // all 64 loads of the wave's two groups go out before any arithmetic: the second group's data
+    // arrives while the first is rotated and quantized.  Rows past k read as zeros without a predicate
+    // (the wave-uniform row offset rides in the scalar offset and takes part in the range check);
+    // columns past `rows` inside a source row read whatever lies there, their results are never stored.
+    uint32_t raw[2][32];
+#pragma unroll
     for (uint32_t rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (uint32_t i = 0; i < 32; ++i)
+            raw[rb][i] = __builtin_amdgcn_raw_buffer_load_b32(
+                res_x, (int)(4u * lane), (int)(((2u * wave + rb) * 32u + i) * (uint32_t)ldx * 2u), 2 /* non-temporal */);
+    }
+#pragma unroll
+    for (uint32_t rb = 0; rb < 2; ++rb) {
+        __builtin_amdgcn_sched_barrier(0);
         const uint32_t gl = 2u * wave + rb;               // group inside the block tile
         const uint32_t grp = grp0 + gl;
-        const bool ok = col_ok && grp < gk;
-        float v0[32], v1[32];
-        if (SRC == 0) {
-            // the block's corner of the source through a buffer resource that ends with the last column of
-            // the last source row: rows past k read as zeros without a predicate; columns past `rows`
-            // inside a source row read whatever lies there, their results are never stored
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                // the row part of the address is wave-uniform and rides in the scalar offset
-                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(res_x, (int)(4u * lane), (int)((gl * 32u + i) * (uint32_t)ldx * 2u), 2 /* non-temporal */);
-                v0[i] = u2f(w << 16);
-                v1[i] = u2f(w & 0xFFFF0000u);
-            }
-        } else {
-            const uint8_t* sc = static_cast<const uint8_t*>(src);
-            const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;   // the source's own K-quads
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                uint32_t byte = 0u, sb = 127u;
-                if (ok) {
-                    uint32_t r = grp * 32u + i;
-                    byte = sc[(size_t)r * half + (col >> 1)];
-                    sb = src_scales[scale_tile_offset(r, col >> 5, skq)];
-                }
-                v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(byte, u2f(sb << 23), 0);
-                v0[i] = d[0];
-                v1[i] = d[1];
-            }
-        }
-        uint4 c0, c1;
-        uint32_t sb0, sb1, m0, m1;
-        // output position of element 0 of the group: row*k + grp*32, divided by 16
-        quantize_group<MODE>(v0, p, ((uint64_t)col * k + grp * 32u) >> 4, c0, sb0, m0);
-        quantize_group<MODE>(v1, p, ((uint64_t)(col + 1u) * k + grp * 32u) >> 4, c1, sb1, m1);
-        const uint32_t lc = 2u * lane;                    // local column
         const uint32_t sw = lane & 7u;                    // 16-byte slot swizzle against bank conflicts
-        s_codes[lc * 8u + (gl ^ sw)] = c0;
-        s_codes[(lc + 1u) * 8u + (gl ^ sw)] = c1;
-        s_scales[lc * 8u + gl] = (uint8_t)sb0;
-        s_scales[(lc + 1u) * 8u + gl] = (uint8_t)sb1;
-        if (MASK) {
-            s_mask[lc * 8u + gl] = m0;
-            s_mask[(lc + 1u) * 8u + gl] = m1;
+#pragma unroll
+        for (uint32_t c = 0; c < 2; ++c) {
+            float v[32];
+#pragma unroll
+            for (uint32_t i = 0; i < 32; ++i) v[i] = c ? u2f(raw[rb][i] & 0xFFFF0000u) : u2f(raw[rb][i] << 16);
+            uint4 q;
+            uint32_t sb, m;
+            // output position of element 0 of the group: row*k + grp*32, divided by 16
+            quantize_group<MODE>(v, p, ((uint64_t)(col + c) * k + grp * 32u) >> 4, q, sb, m);
+            const uint32_t lc = 2u * lane + c;            // local column
+            s_codes[lc * 8u + (gl ^ sw)] = q;
+            s_scales[lc * 8u + gl] = (uint8_t)sb;
+            if (MASK) s_mask[lc * 8u + gl] = m;
         }
     }
     __syncthreads();
@@ -464,17 +448,16 @@ static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx
     return hipGetLastError();
 }
 
-template <int MODE, int SRC>
-static hipError_t launch_transposed(const void* src, const uint8_t* src_scales, int64_t rows, int64_t k,
-                                    int64_t ldx, uint8_t* codes, uint8_t* scales, uint32_t* mask,
-                                    const SrParams& p, hipStream_t st) {
+template <int MODE>
+static hipError_t launch_transposed(const void* src, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
+                                    uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
     if (rows == 0 || k == 0) return hipSuccess;
-    dim3 grid((uint32_t)((rows + 127) / 128), (uint32_t)((k / 32 + 7) / 8)), block(256);
+    dim3 grid((uint32_t)((k / 32 + 7) / 8), (uint32_t)((rows + 127) / 128)), block(256);
     if (mask)
-        hipLaunchKernelGGL((quant_transposed_kernel<MODE, true, SRC>), grid, block, 0, st, src, src_scales,
+        hipLaunchKernelGGL((quant_transposed_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)src,
                            (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
     else
-        hipLaunchKernelGGL((quant_transposed_kernel<MODE, false, SRC>), grid, block, 0, st, src, src_scales,
+        hipLaunchKernelGGL((quant_transposed_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)src,
                            (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
     return hipGetLastError();
 }
@@ -489,9 +472,9 @@ hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_
         }
     }
     switch (mode) {
-    case kFwd: return launch_transposed<kFwd, 0>(x, nullptr, rows, k, ldx, codes, scales, mask, p, st);
-    case kBwdRtn: return launch_transposed<kBwdRtn, 0>(x, nullptr, rows, k, ldx, codes, scales, nullptr, p, st);
-    default: return launch_transposed<kBwdSr, 0>(x, nullptr, rows, k, ldx, codes, scales, nullptr, p, st);
+    case kFwd: return launch_transposed<kFwd>(x, rows, k, ldx, codes, scales, mask, p, st);
+    case kBwdRtn: return launch_transposed<kBwdRtn>(x, rows, k, ldx, codes, scales, nullptr, p, st);
+    default: return launch_transposed<kBwdSr>(x, rows, k, ldx, codes, scales, nullptr, p, st);
     }
 }
 
