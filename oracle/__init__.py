@@ -74,6 +74,16 @@ def _declare(L):
     L.quartet_ref_linear_fwd.argtypes = [_p, _p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p]
     L.quartet_ref_linear_bwd.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64,
                                          ctypes.c_int, _p, _p]
+    ci = ctypes.c_int
+    L.quartet_ref_sign_words.argtypes = [_u64, _p]
+    L.quartet_ref_hadamard.argtypes = [_p, ci, _p]
+    L.quartet_ref_quant_fwd_block.argtypes = [_p, _i64, _i64, _i64, ci, ci, _p, _p, _p]
+    L.quartet_ref_quant_bwd_sr_block.argtypes = [_p, _i64, _i64, _i64, ci, ci, _p, _u64, _u32, ci, _p, _p]
+    L.quartet_ref_requant_transpose_sr_block.argtypes = [_p, _p, _i64, _i64, ci, _p, _u64, _u32, ci, _p, _p]
+    L.quartet_ref_grad_epilogue_block.argtypes = [_p, _p, _i64, _i64, ci, ctypes.c_float, _p]
+    L.quartet_ref_linear_fwd_block.argtypes = [_p, _p, _i64, _i64, _i64, ci, _p, _p, _p, _p, _p, _p, _p]
+    L.quartet_ref_linear_bwd_block.argtypes = [_p, _i64, _i64, _i64, ci, _p, _p, _p, _p, _p, _p, _u64,
+                                               ci, _p, _p]
 
 
 def _ptr(a):
@@ -309,4 +319,100 @@ def linear_bwd(dy_bf16, ctx, seed, rounding=0):
                                      _ptr(ctx["xq_codes"]), _ptr(ctx["xq_scales"]), _ptr(ctx["x_mask"]),
                                      _ptr(ctx["wq_codes"]), _ptr(ctx["wq_scales"]), _ptr(ctx["w_mask"]),
                                      int(seed), int(rounding), _ptr(dx), _ptr(dw)), "linear_bwd")
+    return dx, dw
+
+
+# ------------------------------------------ larger Hadamard blocks (32, 64, 128, 256)
+
+def sign_words(seed):
+    """The eight sign words of a backward pass (element i of a block negated iff bit i%32 of word i/32)."""
+    out = np.zeros(8, dtype=np.uint32)
+    lib().quartet_ref_sign_words(int(seed), _ptr(out))
+    return out
+
+
+def hadamard(v, block, sign_words=None):
+    """H_block (d . v) for one block of fp32 values; returns a new array."""
+    out = np.array(v, dtype=np.float32).reshape(block).copy()
+    sw = None if sign_words is None else _c(sign_words, np.uint32)
+    _ok(lib().quartet_ref_hadamard(_ptr(out), int(block), _ptr(sw)), "hadamard")
+    return out
+
+
+def quant_fwd_block(x_bf16, block, transpose=False, want_mask=True):
+    x = _c(x_bf16, np.uint16)
+    rows, k = _logical_shape(x, transpose)
+    cs = np.zeros((rows, k // 2), dtype=np.uint8)
+    ss = np.zeros((rows, k // G), dtype=np.uint8)
+    ms = np.zeros((rows, k // G), dtype=np.uint32) if want_mask else None
+    _ok(lib().quartet_ref_quant_fwd_block(_ptr(x), rows, k, x.shape[1], int(bool(transpose)), int(block),
+                                          _ptr(cs), _ptr(ss), _ptr(ms)), "quant_fwd_block")
+    return cs, ss, ms
+
+
+def quant_bwd_sr_block(x_bf16, block, sign_words, seed, stream_id, rounding=0, transpose=False):
+    x = _c(x_bf16, np.uint16)
+    rows, k = _logical_shape(x, transpose)
+    sw = _c(sign_words, np.uint32)
+    codes = np.zeros((rows, k // 2), dtype=np.uint8)
+    scales = np.zeros((rows, k // G), dtype=np.uint8)
+    _ok(lib().quartet_ref_quant_bwd_sr_block(_ptr(x), rows, k, x.shape[1], int(bool(transpose)), int(block),
+                                             _ptr(sw), int(seed), int(stream_id), int(rounding),
+                                             _ptr(codes), _ptr(scales)), "quant_bwd_sr_block")
+    return codes, scales
+
+
+def requant_transpose_sr_block(src_codes, src_scales, block, sign_words, seed, stream_id, rounding=0):
+    sc = _c(src_codes, np.uint8)
+    ss = _c(src_scales, np.uint8)
+    sw = _c(sign_words, np.uint32)
+    k, rows = sc.shape[0], sc.shape[1] * 2
+    codes = np.zeros((rows, k // 2), dtype=np.uint8)
+    scales = np.zeros((rows, k // G), dtype=np.uint8)
+    _ok(lib().quartet_ref_requant_transpose_sr_block(_ptr(sc), _ptr(ss), rows, k, int(block), _ptr(sw),
+                                                     int(seed), int(stream_id), int(rounding),
+                                                     _ptr(codes), _ptr(scales)), "requant_transpose_sr_block")
+    return codes, scales
+
+
+def grad_epilogue_block(g, mask, block, scale=FL_16_9):
+    gg = _c(g, np.float32)
+    mm = None if mask is None else _c(mask, np.uint32)
+    m, n = gg.shape
+    out = np.zeros((m, n), dtype=np.float32)
+    _ok(lib().quartet_ref_grad_epilogue_block(_ptr(gg), _ptr(mm), m, n, int(block), float(np.float32(scale)),
+                                              _ptr(out)), "grad_epilogue_block")
+    return out
+
+
+def linear_fwd_block(x_bf16, w_bf16, block):
+    x = _c(x_bf16, np.uint16)
+    w = _c(w_bf16, np.uint16)
+    tokens, in_f = x.shape
+    out_f = w.shape[0]
+    if w.shape[1] != in_f:
+        raise ValueError("in features differ")
+    y = np.zeros((tokens, out_f), dtype=np.float32)
+    ctx = dict(
+        xq_codes=np.zeros((tokens, in_f // 2), np.uint8), xq_scales=np.zeros((tokens, in_f // G), np.uint8),
+        x_mask=np.zeros((tokens, in_f // G), np.uint32),
+        wq_codes=np.zeros((out_f, in_f // 2), np.uint8), wq_scales=np.zeros((out_f, in_f // G), np.uint8),
+        w_mask=np.zeros((out_f, in_f // G), np.uint32))
+    _ok(lib().quartet_ref_linear_fwd_block(_ptr(x), _ptr(w), tokens, in_f, out_f, int(block), _ptr(y),
+                                           _ptr(ctx["xq_codes"]), _ptr(ctx["xq_scales"]), _ptr(ctx["x_mask"]),
+                                           _ptr(ctx["wq_codes"]), _ptr(ctx["wq_scales"]), _ptr(ctx["w_mask"])),
+        "linear_fwd_block")
+    return y, ctx
+
+
+def linear_bwd_block(dy_bf16, ctx, block, seed, rounding=0):
+    dy = _c(dy_bf16, np.uint16)
+    tokens, out_f = dy.shape
+    in_f = ctx["xq_codes"].shape[1] * 2
+    dx = np.zeros((tokens, in_f), dtype=np.float32)
+    dw = np.zeros((out_f, in_f), dtype=np.float32)
+    _ok(lib().quartet_ref_linear_bwd_block(_ptr(dy), tokens, in_f, out_f, int(block),
+                                           _ptr(ctx["xq_codes"]), _ptr(ctx["xq_scales"]), _ptr(ctx["x_mask"]),
+                                           _ptr(ctx["wq_codes"]), _ptr(ctx["wq_scales"]), _ptr(ctx["w_mask"]),
+                                           int(seed), int(rounding), _ptr(dx), _ptr(dw)), "linear_bwd_block")
     return dx, dw

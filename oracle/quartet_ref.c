@@ -14,6 +14,8 @@
  *   - GEMM_LP  D = (A x SFA)(B x SFB)^T     : Section 4.4 "Stage 2"
  *   - gradient epilogue 16/9 H^-1(G . M)    : Algorithm 1 Backward
  *   - MXFP8 (E4M3 + E8M0 / 32) comparison format: Section 3; Section 5 "Speedup results"
+ *   - Hadamard blocks of 64, 128, 256 with the MXFP4 group kept at 32 (*_block functions)
+ *                                           : Section 4.4 "Costs and format specialization"
  * Where the paper is silent the reading taken here is stated next to the code.
  *
  * Arithmetic: every fp32 step is a single IEEE-754 binary32 operation, rounded
@@ -24,7 +26,9 @@
  * H H^T = 32 I and the dense-matrix product, Philox known answers, power-of-two
  * scaling equivariance, "nothing saturates" in the backward, stochastic-rounding
  * probabilities fixed through the draw threshold, Gaussian MSE bands of Table 1,
- * exhaustive one-group GEMMs and numpy fp64 matmul of decoded operands.
+ * exhaustive one-group GEMMs and numpy fp64 matmul of decoded operands; the
+ * *_block functions against scipy's Sylvester matrices, their own block = 32 case
+ * and fp64 recomputation of scales, codes and masks from the densely rotated input.
  * Parity unpinned: the QuEST clip constant (the paper prints no value; see
  * QUEST_LOG2_C2 below) -- only the Table 1 MSE band constrains it.
  */
@@ -198,6 +202,54 @@ void quartet_ref_hadamard32(float v[G], uint32_t sign_word) {
     for (int i = 0; i < G; ++i) v[i] = v[i] * c;
 }
 
+/* ---------------------------------------- larger Hadamard blocks (g = 64, 128, 256)
+ * Section 4.4 "Costs and format specialization" prices the rotation at O(g log g) and calls it
+ * negligible up to g = 256; the MXFP4 group stays 32, only the rotated block grows.
+ * Reading: H_g = H_{g/32} (x) H_32 (normalized Sylvester matrix of order g), evaluated as
+ * butterflies in a fixed order: the stages that combine whole 32-element sub-blocks first
+ * (stride 32, 64, ..., g/2), then the stages inside each sub-block (stride 1, 2, 4, 8, 16),
+ * then one multiply by fl(1/sqrt g).  For g = 32 this is exactly quartet_ref_hadamard32. */
+
+static int check_block(int g) { return (g == 32 || g == 64 || g == 128 || g == 256) ? 0 : -1; }
+
+/* Sign words of a backward pass with seed xi for blocks up to 256 wide: words 0..3 are the four
+ * outputs of Philox at counter (0,0,0,0xFFFFFFFF), words 4..7 those at (1,0,0,0xFFFFFFFF); element i
+ * of a block is negated iff bit i%32 of word i/32.  Word 0 is quartet_ref_sign_word(seed). */
+void quartet_ref_sign_words(uint64_t seed, uint32_t out[8]) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (uint32_t c = 0; c < 2; ++c) {
+        uint32_t ctr[4] = {c, 0u, 0u, 0xFFFFFFFFu};
+        quartet_ref_philox4x32_10(ctr, key, out + 4 * c);
+    }
+}
+
+/* v[g] <- H_g (d . v); sign_words = g/32 words (NULL: no sign flips, the fixed H_g) */
+int quartet_ref_hadamard(float *v, int g, const uint32_t *sign_words) {
+    if (check_block(g)) return -1;
+    if (sign_words)
+        for (int i = 0; i < g; ++i)
+            if ((sign_words[i / 32] >> (i % 32)) & 1u) v[i] = -v[i];
+    static const int low[5] = {1, 2, 4, 8, 16};
+    int strides[8], ns = 0;
+    for (int h = 32; h < g; h <<= 1) strides[ns++] = h;
+    for (int j = 0; j < 5; ++j) strides[ns++] = low[j];
+    for (int t = 0; t < ns; ++t) {
+        int h = strides[t];
+        for (int i = 0; i < g; ++i) {
+            if (i & h) continue;
+            float a = v[i], b = v[i + h];
+            v[i] = a + b;
+            v[i + h] = a - b;
+        }
+    }
+    const float c = (g == 32) ? 0.17677669529663687f   /* fl(1/sqrt 32)  = 0x3E3504F3 */
+                  : (g == 64) ? 0.125f
+                  : (g == 128) ? 0.08838834764831845f  /* fl(1/sqrt 128) = 0x3DB504F3 */
+                  : 0.0625f;
+    for (int i = 0; i < g; ++i) v[i] = v[i] * c;
+    return 0;
+}
+
 /* ------------------------------------------------------------- input sources */
 
 /* A quantizer reads a logical matrix A[rows x k] (groups of 32 along k) from
@@ -241,9 +293,16 @@ static void put_code(uint8_t *codes, int64_t idx, uint8_t code) {
  *   scale exponent e = floor((floor(log2 ss) - 5 + log2 c^2) / 2), i.e. 2^e = 2^floor(log2(c sqrt(ss/32)));
  *   v_i = h_i 2^-e (exact); code_i = RTN(v_i) saturating at 6; mask bit i = (|v_i| <= 6).
  * ss zero or subnormal: e = 0. */
+static void quant_fwd_encode(const float h[G], uint8_t code[G], uint8_t *scale_byte, uint32_t *mask_word);
+
 static void quant_fwd_group(float h[G], uint8_t code[G], uint8_t *scale_byte, uint32_t *mask_word) {
-    float t[G], t2[G];
     quartet_ref_hadamard32(h, 0u);
+    quant_fwd_encode(h, code, scale_byte, mask_word);
+}
+
+/* the part after the rotation: h is one MXFP4 group of the rotated block */
+static void quant_fwd_encode(const float h[G], uint8_t code[G], uint8_t *scale_byte, uint32_t *mask_word) {
+    float t[G], t2[G];
     for (int i = 0; i < G; ++i) t[i] = h[i] * h[i];
     for (int s = 1; s < G; s <<= 1) {
         for (int i = 0; i < G; ++i) t2[i] = t[i] + t[i ^ s];
@@ -308,6 +367,34 @@ int quartet_ref_quant_fwd_rows(const uint16_t *x, int64_t rows, int64_t k, int64
     return 0;
 }
 
+/* Forward quantizer with a Hadamard block of hb = 32, 64, 128 or 256 elements: every block of hb
+ * consecutive elements along k is rotated by H_hb, then each of its 32-element MXFP4 groups gets its
+ * own QuEST scale, codes and mask word exactly as above.  k % hb == 0. */
+int quartet_ref_quant_fwd_block(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                                int hb, uint8_t *codes, uint8_t *scales, uint32_t *mask) {
+    if (check_quant_args(rows, k) || check_block(hb) || (k % hb) != 0) return -1;
+    Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
+    int64_t gk = k / G, nb = k / hb;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t b = 0; b < nb; ++b) {
+            float h[256];
+            for (int i = 0; i < hb; ++i) h[i] = src_get(&s, r, b * hb + i);
+            quartet_ref_hadamard(h, hb, NULL);
+            for (int j = 0; j < hb / G; ++j) {
+                uint8_t code[G], sb;
+                uint32_t mw;
+                int64_t g = b * (hb / G) + j;
+                quant_fwd_encode(h + j * G, code, &sb, &mw);
+                for (int i = 0; i < G; ++i) put_code(codes, r * k + g * G + i, code[i]);
+                scales[r * gk + g] = sb;
+                if (mask) mask[r * gk + g] = mw;
+            }
+        }
+    }
+    return 0;
+}
+
 /* ----------------------------------------------------- backward quantizer */
 
 /* One group of the backward quantizer, Algorithm 1 Backward:
@@ -317,9 +404,19 @@ int quartet_ref_quant_fwd_rows(const uint16_t *x, int64_t rows, int64_t k, int64
  *   code_i = RTN(v_i) (rounding = 1, Algorithm 1 as printed) or SR(v_i, draw) (rounding = 0).
  * The stored scale is 2^e; the 3/4 is undone by the 16/9 of the gradient epilogue.
  * m zero or subnormal: e = 0. */
+static void quant_bwd_encode(const float h[G], int rounding, uint64_t seed, uint32_t stream_id,
+                             uint64_t L0, uint8_t code[G], uint8_t *scale_byte);
+
 static void quant_bwd_group(float h[G], uint32_t sign_word, int rounding, uint64_t seed,
                             uint32_t stream_id, uint64_t L0, uint8_t code[G], uint8_t *scale_byte) {
     quartet_ref_hadamard32(h, sign_word);
+    quant_bwd_encode(h, rounding, seed, stream_id, L0, code, scale_byte);
+}
+
+/* the part after the rotation: h is one MXFP4 group of the rotated block, L0 its first element's
+ * output position */
+static void quant_bwd_encode(const float h[G], int rounding, uint64_t seed, uint32_t stream_id,
+                             uint64_t L0, uint8_t code[G], uint8_t *scale_byte) {
     float m = 0.0f;
     for (int i = 0; i < G; ++i)
         if (fabsf(h[i]) > m) m = fabsf(h[i]);
@@ -354,6 +451,48 @@ static int quant_bwd_src(const Src *s, uint32_t sign_word, uint64_t seed, uint32
         }
     }
     return 0;
+}
+
+/* Backward quantizer with a Hadamard block of hb elements: every block of hb consecutive elements
+ * along k is rotated by H_hb (d . x) with the hb-wide sign vector sign_words[0 .. hb/32), then each
+ * of its 32-element groups is scaled and rounded exactly as above (draw positions unchanged). */
+static int quant_bwd_src_block(const Src *s, int hb, const uint32_t *sign_words, uint64_t seed,
+                               uint32_t stream_id, int rounding, uint8_t *codes, uint8_t *scales) {
+    int64_t rows = s->rows, k = s->k, gk = k / G, nb = k / hb;
+    if (rounding != 0 && rounding != 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t b = 0; b < nb; ++b) {
+            float h[256];
+            for (int i = 0; i < hb; ++i) h[i] = src_get(s, r, b * hb + i);
+            quartet_ref_hadamard(h, hb, sign_words);
+            for (int j = 0; j < hb / G; ++j) {
+                uint8_t code[G], sb;
+                int64_t g = b * (hb / G) + j;
+                quant_bwd_encode(h + j * G, rounding, seed, stream_id, (uint64_t)(r * k + g * G), code, &sb);
+                for (int i = 0; i < G; ++i) put_code(codes, r * k + g * G + i, code[i]);
+                scales[r * gk + g] = sb;
+            }
+        }
+    }
+    return 0;
+}
+
+int quartet_ref_quant_bwd_sr_block(const uint16_t *x, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                                   int hb, const uint32_t *sign_words, uint64_t seed, uint32_t stream_id,
+                                   int rounding, uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k) || check_block(hb) || (k % hb) != 0 || !sign_words) return -1;
+    Src s = {transpose ? SRC_BF16_T : SRC_BF16, x, ldx, 0, 0, rows, k};
+    return quant_bwd_src_block(&s, hb, sign_words, seed, stream_id, rounding, codes, scales);
+}
+
+int quartet_ref_requant_transpose_sr_block(const uint8_t *src_codes, const uint8_t *src_scales,
+                                           int64_t rows, int64_t k, int hb, const uint32_t *sign_words,
+                                           uint64_t seed, uint32_t stream_id, int rounding,
+                                           uint8_t *codes, uint8_t *scales) {
+    if (check_quant_args(rows, k) || (rows % G) != 0 || check_block(hb) || (k % hb) != 0 || !sign_words) return -1;
+    Src s = {SRC_MX_T, 0, 0, src_codes, src_scales, rows, k};
+    return quant_bwd_src_block(&s, hb, sign_words, seed, stream_id, rounding, codes, scales);
 }
 
 /* rounding: 0 = stochastic, 1 = nearest.  Layout of x and outputs as in quartet_ref_quant_fwd. */
@@ -567,6 +706,26 @@ int quartet_ref_grad_epilogue(const float *g, const uint32_t *mask, int64_t m, i
     return 0;
 }
 
+/* The same with a Hadamard block of hb elements along n (n % hb == 0); the mask words stay per
+ * 32-element group. */
+int quartet_ref_grad_epilogue_block(const float *g, const uint32_t *mask, int64_t m, int64_t n, int hb,
+                                    float scale, float *out) {
+    if (check_quant_args(m, n) || check_block(hb) || (n % hb) != 0) return -1;
+    int64_t gn = n / G, nb = n / hb;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < m; ++r)
+        for (int64_t b = 0; b < nb; ++b) {
+            float t[256];
+            for (int i = 0; i < hb; ++i) {
+                uint32_t mw = mask ? mask[r * gn + (b * hb + i) / G] : 0xFFFFFFFFu;
+                t[i] = ((mw >> (i % G)) & 1u) ? g[r * n + b * hb + i] : 0.0f;
+            }
+            quartet_ref_hadamard(t, hb, NULL);
+            for (int i = 0; i < hb; ++i) out[r * n + b * hb + i] = t[i] * scale;
+        }
+    return 0;
+}
+
 /* ------------------------------------------------------ linear layer fwd/bwd */
 
 static void round_to_f32(const double *src, float *dst, int64_t n) {
@@ -626,6 +785,60 @@ int quartet_ref_linear_bwd(const uint16_t *dy, int64_t tokens, int64_t in, int64
     if (rc) goto done;
     round_to_f32(acc, accf, out * in);
     rc |= quartet_ref_grad_epilogue(accf, w_mask, out, in, c169, dw);
+done:
+    free(gq); free(gs); free(wt); free(ws); free(gt); free(gts); free(xt); free(xs); free(acc); free(accf);
+    return rc;
+}
+
+/* Algorithm 1 with a Hadamard block of hb = 32, 64, 128 or 256 elements (MXFP4 group 32 throughout).
+ * hb = 32 gives exactly quartet_ref_linear_fwd / quartet_ref_linear_bwd. */
+int quartet_ref_linear_fwd_block(const uint16_t *x, const uint16_t *w, int64_t tokens, int64_t in, int64_t out,
+                                 int hb, float *y, uint8_t *xq_codes, uint8_t *xq_scales, uint32_t *x_mask,
+                                 uint8_t *wq_codes, uint8_t *wq_scales, uint32_t *w_mask) {
+    if (tokens < 0 || in < 0 || out < 0 || check_block(hb) || (in % hb) != 0) return -1;
+    if (quartet_ref_quant_fwd_block(x, tokens, in, in, 0, hb, xq_codes, xq_scales, x_mask)) return -1;
+    if (quartet_ref_quant_fwd_block(w, out, in, in, 0, hb, wq_codes, wq_scales, w_mask)) return -1;
+    double *d = (double *)malloc(sizeof(double) * (size_t)(tokens * out + 1));
+    if (!d) return -2;
+    int rc = quartet_ref_mxfp4_gemm(xq_codes, xq_scales, wq_codes, wq_scales, tokens, out, in, 1.0, d);
+    if (!rc) round_to_f32(d, y, tokens * out);
+    free(d);
+    return rc;
+}
+
+int quartet_ref_linear_bwd_block(const uint16_t *dy, int64_t tokens, int64_t in, int64_t out, int hb,
+                                 const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,
+                                 const uint8_t *wq_codes, const uint8_t *wq_scales, const uint32_t *w_mask,
+                                 uint64_t seed, int rounding, float *dx, float *dw) {
+    if (tokens < 0 || in < 0 || out < 0 || check_block(hb)) return -1;
+    if ((in % hb) != 0 || (out % hb) != 0 || (tokens % hb) != 0) return -1;
+    const float c169 = 1.7777777777777777f; /* fl(16/9) = 0x3FE38E39 */
+    uint32_t sw[8];
+    quartet_ref_sign_words(seed, sw);
+    int rc = 0;
+    size_t sz_g = (size_t)(tokens * out), sz_w = (size_t)(in * out), sz_x = (size_t)(tokens * in);
+    uint8_t *gq = malloc(sz_g / 2 + 1), *gs = malloc(sz_g / G + 1);
+    uint8_t *wt = malloc(sz_w / 2 + 1), *ws = malloc(sz_w / G + 1);
+    uint8_t *gt = malloc(sz_g / 2 + 1), *gts = malloc(sz_g / G + 1);
+    uint8_t *xt = malloc(sz_x / 2 + 1), *xs = malloc(sz_x / G + 1);
+    size_t big = sz_x > sz_w ? sz_x : sz_w;
+    double *acc = malloc(sizeof(double) * (big + 1));
+    float *accf = malloc(sizeof(float) * (big + 1));
+    if (!gq || !gs || !wt || !ws || !gt || !gts || !xt || !xs || !acc || !accf) { rc = -2; goto done; }
+
+    rc |= quartet_ref_quant_bwd_sr_block(dy, tokens, out, out, 0, hb, sw, seed, 0u, rounding, gq, gs);
+    rc |= quartet_ref_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, wt, ws);
+    rc |= quartet_ref_mxfp4_gemm(gq, gs, wt, ws, tokens, in, out, 1.0, acc);
+    if (rc) goto done;
+    round_to_f32(acc, accf, tokens * in);
+    rc |= quartet_ref_grad_epilogue_block(accf, x_mask, tokens, in, hb, c169, dx);
+
+    rc |= quartet_ref_quant_bwd_sr_block(dy, out, tokens, out, 1, hb, sw, seed, 2u, rounding, gt, gts);
+    rc |= quartet_ref_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, xt, xs);
+    rc |= quartet_ref_mxfp4_gemm(gt, gts, xt, xs, out, in, tokens, 1.0, acc);
+    if (rc) goto done;
+    round_to_f32(acc, accf, out * in);
+    rc |= quartet_ref_grad_epilogue_block(accf, w_mask, out, in, hb, c169, dw);
 done:
     free(gq); free(gs); free(wt); free(ws); free(gt); free(gts); free(xt); free(xs); free(acc); free(accf);
     return rc;
