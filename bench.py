@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="workload: configuration 1..4")
     ap.add_argument("--rounding", type=int, default=0, help="backward rounding: 0 = stochastic, 1 = nearest")
+    ap.add_argument("--hadamard-block", type=int, default=32,
+                    help="Hadamard block in elements (32 = the method; 64, 128, 256: the wider rotations)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
     ap.add_argument("--fp8-compare", action="store_true",
@@ -40,7 +42,8 @@ def parse():
 
 
 class Layer:
-    def __init__(self, q, torch, L):
+    def __init__(self, q, torch, L, block=32):
+        self.block = block
         t, i, o = L["tokens"], L["in_features"], L["out_features"]
         self.t, self.i, self.o, self.name = t, i, o, L["name"]
         dev = L["x"].device
@@ -57,10 +60,18 @@ class Layer:
                                                       torch.empty((o, i // 32), **i32))
         self.dx = torch.empty((t, i), **f32)
         self.dw = torch.empty((o, i), **f32)
-        self.ws_bytes = q.quartet_linear_workspace_bytes(t, i, o)
+        self.ws_bytes = q.quartet_linear_workspace_bytes_block(t, i, o, block)
         self.flops = 6.0 * t * i * o
 
     def step(self, q, ws, seed, rounding):
+        if self.block != 32:
+            q.check(q.quartet_linear_fwd_block(self.x, self.w, self.t, self.i, self.o, self.block, self.y,
+                                               q.QUARTET_DTYPE_F32, self.xq_codes, self.xq_scales, self.x_mask,
+                                               self.wq_codes, self.wq_scales, self.w_mask))
+            q.check(q.quartet_linear_bwd_block(self.dy, self.t, self.i, self.o, self.block, self.xq_codes,
+                                               self.xq_scales, self.x_mask, self.wq_codes, self.wq_scales, self.w_mask,
+                                               seed, rounding, self.dx, self.dw, q.QUARTET_DTYPE_F32, ws, self.ws_bytes))
+            return
         q.check(q.quartet_linear_fwd(self.x, self.w, self.t, self.i, self.o, self.y, q.QUARTET_DTYPE_F32,
                                      self.xq_codes, self.xq_scales, self.x_mask,
                                      self.wq_codes, self.wq_scales, self.w_mask))
@@ -226,11 +237,11 @@ def main():
     torch.cuda.set_device(0)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     cfg = synth.CONFIGS[args.config]
-    layers = [Layer(q, torch, synth.device_layer(args.config, li)) for li in range(len(cfg["layers"]))]
+    layers = [Layer(q, torch, synth.device_layer(args.config, li), args.hadamard_block) for li in range(len(cfg["layers"]))]
     ws_bytes = max(l.ws_bytes for l in layers)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     flops_step = sum(l.flops for l in layers)
-    launches_per_step = 9 * len(layers)    # 2 + 1 forward, (2 + 1) x 2 backward
+    launches_per_step = 11 * len(layers)   # capacity: 2 + 1 forward, (2 + 1) x 2 backward, + 2 epilogue kernels for Hadamard blocks above 32
 
     def one_step(step):
         for l in layers:
@@ -288,7 +299,8 @@ def main():
         "dtype": "mxfp4 (E2M1 x E8M0/32) operands, fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg['name']}, {len(layers)} linear layers fwd+bwd, "
-                               f"backward rounding {'stochastic' if args.rounding == 0 else 'nearest'}",
+                               f"backward rounding {'stochastic' if args.rounding == 0 else 'nearest'}"
+                               + ("" if args.hadamard_block == 32 else f", Hadamard block {args.hadamard_block}"),
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
         "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_ring_kernel (all three GEMMs of every layer)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",

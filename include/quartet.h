@@ -235,6 +235,49 @@ int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t 
 /* sign word quartet_linear_bwd derives from a seed (host computation, no GPU work). */
 uint32_t quartet_sign_word(uint64_t seed);
 
+/*
+ * Larger Hadamard blocks (Section 4.4, "Costs and format specialization": the rotation costs
+ * O(g log g) and stays negligible up to g = 256).  hadamard_block = 32, 64, 128 or 256 elements; the
+ * MXFP4 group stays 32, so scales, masks, draw positions and every layout are those of the functions
+ * above, and hadamard_block = 32 gives exactly those functions.  H_g = H_{g/32} (x) H_32 is the
+ * normalized Sylvester matrix of order g, evaluated as butterflies in this order: the stages that
+ * combine whole 32-element groups first (stride 32, 64, ..., g/2), then stride 1, 2, 4, 8, 16 inside
+ * each group, then one multiply by fl(1/sqrt g).  The dimension the blocks run along must be a
+ * multiple of hadamard_block.
+ *
+ * Sign vector of the randomized rotation: g/32 words, element i of a block negated iff bit i%32 of
+ * word i/32.  quartet_sign_words (host computation, no GPU work) writes the eight words a seed
+ * stands for: words 0..3 are the outputs of Philox4x32-10 at counter (0,0,0,0xFFFFFFFF) under the
+ * seed's key, words 4..7 those at counter (1,0,0,0xFFFFFFFF); word 0 = quartet_sign_word(seed).
+ * sign_words arguments are HOST pointers to at least hadamard_block/32 words.
+ *
+ * The gradient GEMM with the epilogue inside (quartet_mxfp4_gemm_grad) exists for blocks of 32 only;
+ * quartet_linear_bwd_block runs the plain GEMM into its workspace and quartet_grad_epilogue_block
+ * after it when hadamard_block > 32 (quartet_linear_workspace_bytes_block accounts for that).
+ */
+int quartet_sign_words(uint64_t seed, uint32_t *out8);
+int quartet_quant_fwd_block(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                            int hadamard_block, uint8_t *codes, uint8_t *scales, uint32_t *mask, void *stream);
+int quartet_quant_bwd_sr_block(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                               int hadamard_block, const uint32_t *sign_words, uint64_t seed,
+                               uint32_t stream_id, int rounding, uint8_t *codes, uint8_t *scales, void *stream);
+int quartet_requant_transpose_sr_block(const uint8_t *src_codes, const uint8_t *src_scales,
+                                       int64_t rows, int64_t k, int hadamard_block,
+                                       const uint32_t *sign_words, uint64_t seed, uint32_t stream_id,
+                                       int rounding, uint8_t *codes, uint8_t *scales, void *stream);
+int quartet_grad_epilogue_block(const float *g, const uint32_t *mask, int64_t m, int64_t n, int hadamard_block,
+                                float scale, void *out, int out_dtype, void *stream);
+int quartet_linear_fwd_block(const void *x_bf16, const void *w_bf16, int64_t tokens, int64_t in, int64_t out,
+                             int hadamard_block, void *y, int y_dtype,
+                             uint8_t *xq_codes, uint8_t *xq_scales, uint32_t *x_mask,
+                             uint8_t *wq_codes, uint8_t *wq_scales, uint32_t *w_mask, void *stream);
+size_t quartet_linear_workspace_bytes_block(int64_t tokens, int64_t in, int64_t out, int hadamard_block);
+int quartet_linear_bwd_block(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out, int hadamard_block,
+                             const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,
+                             const uint8_t *wq_codes, const uint8_t *wq_scales, const uint32_t *w_mask,
+                             uint64_t seed, int rounding, void *dx, void *dw, int grad_dtype,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,9 @@ EXPORTS = [
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr",
     "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
+    "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
+    "quartet_requant_transpose_sr_block", "quartet_grad_epilogue_block", "quartet_linear_fwd_block",
+    "quartet_linear_workspace_bytes_block", "quartet_linear_bwd_block",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -60,6 +63,16 @@ _lib.quartet_linear_workspace_bytes.restype = ctypes.c_size_t
 _lib.quartet_linear_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.quartet_linear_bwd.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64, _int, _p, _p, _int,
                                     _p, ctypes.c_size_t, _p]
+_lib.quartet_sign_words.argtypes = [_u64, _p]
+_lib.quartet_quant_fwd_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p]
+_lib.quartet_quant_bwd_sr_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_requant_transpose_sr_block.argtypes = [_p, _p, _i64, _i64, _int, _p, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_grad_epilogue_block.argtypes = [_p, _p, _i64, _i64, _int, _f, _p, _int, _p]
+_lib.quartet_linear_fwd_block.argtypes = [_p, _p, _i64, _i64, _i64, _int, _p, _int, _p, _p, _p, _p, _p, _p, _p]
+_lib.quartet_linear_workspace_bytes_block.restype = ctypes.c_size_t
+_lib.quartet_linear_workspace_bytes_block.argtypes = [_i64, _i64, _i64, _int]
+_lib.quartet_linear_bwd_block.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _u64, _int, _p, _p, _int,
+                                          _p, ctypes.c_size_t, _p]
 for _name in EXPORTS:
     getattr(_lib, _name)  # AttributeError here = the library does not export what the header declares
 
@@ -193,3 +206,65 @@ def quartet_linear_bwd(dy_bf16, tokens, in_features, out_features, xq_codes, xq_
                                    _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales),
                                    _ptr(w_mask), seed, rounding, _ptr(dx), _ptr(dw), grad_dtype,
                                    _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+# ---- Hadamard blocks of 32, 64, 128 or 256 elements (sign_words: sequence of host integers)
+
+def _host_words(sign_words):
+    words = [int(w) & 0xFFFFFFFF for w in sign_words]
+    if len(words) < 8:
+        words = words + [0] * (8 - len(words))
+    return (ctypes.c_uint32 * len(words))(*words)
+
+
+def quartet_sign_words(seed):
+    """The eight sign words of a seed as a list of Python ints."""
+    out = (ctypes.c_uint32 * 8)()
+    check(_lib.quartet_sign_words(seed, ctypes.cast(out, _p)))
+    return list(out)
+
+
+def quartet_quant_fwd_block(x_bf16, rows, k, ldx, transpose, hadamard_block, codes, scales, mask, stream=None):
+    return _lib.quartet_quant_fwd_block(_ptr(x_bf16), rows, k, ldx, int(transpose), hadamard_block, _ptr(codes),
+                                        _ptr(scales), _ptr(mask), _stream(stream))
+
+
+def quartet_quant_bwd_sr_block(x_bf16, rows, k, ldx, transpose, hadamard_block, sign_words, seed, stream_id,
+                               rounding, codes, scales, stream=None):
+    sw = _host_words(sign_words)
+    return _lib.quartet_quant_bwd_sr_block(_ptr(x_bf16), rows, k, ldx, int(transpose), hadamard_block,
+                                           ctypes.cast(sw, _p), seed, stream_id, rounding, _ptr(codes), _ptr(scales),
+                                           _stream(stream))
+
+
+def quartet_requant_transpose_sr_block(src_codes, src_scales, rows, k, hadamard_block, sign_words, seed, stream_id,
+                                       rounding, codes, scales, stream=None):
+    sw = _host_words(sign_words)
+    return _lib.quartet_requant_transpose_sr_block(_ptr(src_codes), _ptr(src_scales), rows, k, hadamard_block,
+                                                   ctypes.cast(sw, _p), seed, stream_id, rounding, _ptr(codes),
+                                                   _ptr(scales), _stream(stream))
+
+
+def quartet_grad_epilogue_block(g, mask, m, n, hadamard_block, scale, out, out_dtype, stream=None):
+    return _lib.quartet_grad_epilogue_block(_ptr(g), _ptr(mask), m, n, hadamard_block, scale, _ptr(out), out_dtype,
+                                            _stream(stream))
+
+
+def quartet_linear_fwd_block(x_bf16, w_bf16, tokens, in_f, out_f, hadamard_block, y, y_dtype, xq_codes, xq_scales,
+                             x_mask, wq_codes, wq_scales, w_mask, stream=None):
+    return _lib.quartet_linear_fwd_block(_ptr(x_bf16), _ptr(w_bf16), tokens, in_f, out_f, hadamard_block, _ptr(y),
+                                         y_dtype, _ptr(xq_codes), _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes),
+                                         _ptr(wq_scales), _ptr(w_mask), _stream(stream))
+
+
+def quartet_linear_workspace_bytes_block(tokens, in_f, out_f, hadamard_block):
+    return _lib.quartet_linear_workspace_bytes_block(tokens, in_f, out_f, hadamard_block)
+
+
+def quartet_linear_bwd_block(dy_bf16, tokens, in_f, out_f, hadamard_block, xq_codes, xq_scales, x_mask, wq_codes,
+                             wq_scales, w_mask, seed, rounding, dx, dw, grad_dtype, workspace, workspace_bytes,
+                             stream=None):
+    return _lib.quartet_linear_bwd_block(_ptr(dy_bf16), tokens, in_f, out_f, hadamard_block, _ptr(xq_codes),
+                                         _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales),
+                                         _ptr(w_mask), seed, rounding, _ptr(dx), _ptr(dw), grad_dtype,
+                                         _ptr(workspace), workspace_bytes, _stream(stream))

@@ -46,6 +46,20 @@ int check_quant_shape(int64_t rows, int64_t k, int64_t ldx, int transpose) {
     return QUARTET_OK;
 }
 
+// Hadamard block in elements -> groups per block (0 if unsupported)
+uint32_t block_groups(int hb) { return (hb == 32 || hb == 64 || hb == 128 || hb == 256) ? (uint32_t)hb / 32u : 0u; }
+
+quartet::SrParams make_params(uint32_t nb, const uint32_t* sign_words, uint64_t seed, uint32_t stream_id) {
+    quartet::SrParams p = {};
+    p.nb = nb;
+    p.key0 = (uint32_t)seed;
+    p.key1 = (uint32_t)(seed >> 32);
+    p.stream_id = stream_id;
+    for (uint32_t j = 0; j < 8u; ++j) p.sign_words[j] = (sign_words && j < nb) ? sign_words[j] : 0u;
+    p.sign_word = p.sign_words[0];
+    return p;
+}
+
 // ---- optional launch profiling: a pair of events around every kernel launch of the library
 struct ProfileState {
     bool enabled = false;
@@ -90,10 +104,12 @@ size_t scale_bytes(int64_t rows, int64_t k) {
 }
 
 struct BwdWorkspace {
-    size_t g_codes, g_scales, b_codes, b_scales, total;
+    size_t g_codes, g_scales, b_codes, b_scales, acc, total;
 };
 
-BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
+// with_acc: room for the fp32 product of the larger gradient GEMM (Hadamard blocks above 32 apply the
+// gradient epilogue in a kernel of its own)
+BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out, bool with_acc = false) {
     BwdWorkspace w;
     size_t to = (size_t)tokens * (size_t)out;
     size_t bmax = (size_t)in * (size_t)(out > tokens ? out : tokens);
@@ -104,6 +120,8 @@ BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out) {
     w.g_scales = off; off += align256(gs > gts ? gs : gts);
     w.b_codes = off; off += align256(bmax / 2);
     w.b_scales = off; off += align256(bs > bts ? bs : bts);
+    w.acc = off;
+    if (with_acc) off += align256(sizeof(float) * (size_t)in * (size_t)(out > tokens ? out : tokens));
     w.total = off;
     return w;
 }
@@ -170,14 +188,31 @@ uint32_t quartet_sign_word(uint64_t seed) {
     return w[0];
 }
 
+int quartet_sign_words(uint64_t seed, uint32_t* out8) {
+    if (!out8) return QUARTET_EINVAL;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (uint32_t c = 0; c < 2u; ++c) {
+        const uint32_t ctr[4] = {c, 0u, 0u, 0xFFFFFFFFu};
+        philox_host(ctr, key, out8 + 4 * c);
+    }
+    return QUARTET_OK;
+}
+
 int quartet_quant_fwd(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
                       uint8_t* codes, uint8_t* scales, uint32_t* mask, void* stream) {
+    return quartet_quant_fwd_block(x_bf16, rows, k, ldx, transpose, 32, codes, scales, mask, stream);
+}
+
+int quartet_quant_fwd_block(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose, int hadamard_block,
+                            uint8_t* codes, uint8_t* scales, uint32_t* mask, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u || k < 0 || (k % hadamard_block) != 0) return QUARTET_EINVAL;
     if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
     if (!aligned16(x_bf16) || !aligned16(codes) || (mask && !aligned16(mask))) return QUARTET_EINVAL;
     if (reinterpret_cast<uintptr_t>(scales) & 3u) return QUARTET_EINVAL;
     int rc = check_quant_shape(rows, k, ldx, transpose);
     if (rc) return rc;
-    SrParams p = {0u, 0u, 0u, 0u};
+    SrParams p = make_params(nb, nullptr, 0u, 0u);
     ProfileScope prof(QUARTET_KIND_QUANT_FWD, (hipStream_t)stream);
     hipError_t e = quartet::launch_quant(quartet::kFwd, x_bf16, rows, k, ldx, transpose, p, codes, scales,
                                          mask, (hipStream_t)stream);
@@ -187,12 +222,21 @@ int quartet_quant_fwd(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, 
 int quartet_quant_bwd_sr(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
                          uint32_t sign_word, uint64_t seed, uint32_t stream_id, int rounding,
                          uint8_t* codes, uint8_t* scales, void* stream) {
+    return quartet_quant_bwd_sr_block(x_bf16, rows, k, ldx, transpose, 32, &sign_word, seed, stream_id, rounding, codes,
+                                      scales, stream);
+}
+
+int quartet_quant_bwd_sr_block(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
+                               int hadamard_block, const uint32_t* sign_words, uint64_t seed, uint32_t stream_id,
+                               int rounding, uint8_t* codes, uint8_t* scales, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u || !sign_words || k < 0 || (k % hadamard_block) != 0) return QUARTET_EINVAL;
     if (!x_bf16 || !codes || !scales) return QUARTET_EINVAL;
     if (!aligned16(x_bf16) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     int rc = check_quant_shape(rows, k, ldx, transpose);
     if (rc) return rc;
-    SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    SrParams p = make_params(nb, sign_words, seed, stream_id);
     int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
     ProfileScope prof(QUARTET_KIND_QUANT_BWD, (hipStream_t)stream);
     hipError_t e = quartet::launch_quant(mode, x_bf16, rows, k, ldx, transpose, p, codes, scales, nullptr,
@@ -204,6 +248,16 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
                                  int64_t rows, int64_t k, uint32_t sign_word, uint64_t seed,
                                  uint32_t stream_id, int rounding,
                                  uint8_t* codes, uint8_t* scales, void* stream) {
+    return quartet_requant_transpose_sr_block(src_codes, src_scales, rows, k, 32, &sign_word, seed, stream_id, rounding,
+                                              codes, scales, stream);
+}
+
+int quartet_requant_transpose_sr_block(const uint8_t* src_codes, const uint8_t* src_scales,
+                                       int64_t rows, int64_t k, int hadamard_block, const uint32_t* sign_words,
+                                       uint64_t seed, uint32_t stream_id, int rounding,
+                                       uint8_t* codes, uint8_t* scales, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u || !sign_words || k < 0 || (k % hadamard_block) != 0) return QUARTET_EINVAL;
     if (!src_codes || !src_scales || !codes || !scales) return QUARTET_EINVAL;
     if (!aligned16(src_codes) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
@@ -211,7 +265,7 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
     if (rows >= ((int64_t)1 << 24)) return QUARTET_ENOTSUP;   // 256 source rows of rows/2 bytes must fit a 32-bit byte range
     int rc = check_quant_shape(rows, k, (rows + 7) / 8 * 8, 1);
     if (rc) return rc;
-    SrParams p = {sign_word, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    SrParams p = make_params(nb, sign_words, seed, stream_id);
     int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
     ProfileScope prof(QUARTET_KIND_REQUANT, (hipStream_t)stream);
     hipError_t e = quartet::launch_requant_transpose(mode, src_codes, src_scales, rows, k, p, codes, scales,
@@ -284,6 +338,13 @@ int quartet_mxfp8_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 
 int quartet_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, float scale,
                           void* out, int out_dtype, void* stream) {
+    return quartet_grad_epilogue_block(g, mask, m, n, 32, scale, out, out_dtype, stream);
+}
+
+int quartet_grad_epilogue_block(const float* g, const uint32_t* mask, int64_t m, int64_t n, int hadamard_block,
+                                float scale, void* out, int out_dtype, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u || n < 0 || (n % hadamard_block) != 0) return QUARTET_EINVAL;
     if (!g || !out) return QUARTET_EINVAL;
     if (!aligned16(g) || !aligned16(out)) return QUARTET_EINVAL;
     if (m < 0 || n < 0 || (n % 32) != 0) return QUARTET_EINVAL;
@@ -291,7 +352,7 @@ int quartet_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64
     if (out_dtype == QUARTET_DTYPE_BF16 && out == (const void*)g) return QUARTET_EINVAL;
     if (m > 0 && (n / 32) >= kMaxGroups / m) return QUARTET_ENOTSUP;
     ProfileScope prof(QUARTET_KIND_EPILOGUE, (hipStream_t)stream);
-    hipError_t e = quartet::launch_grad_epilogue(g, mask, m, n, scale, out, out_dtype == QUARTET_DTYPE_BF16,
+    hipError_t e = quartet::launch_grad_epilogue(g, mask, m, n, nb, scale, out, out_dtype == QUARTET_DTYPE_BF16,
                                                  (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
@@ -311,21 +372,36 @@ int quartet_linear_fwd(const void* x_bf16, const void* w_bf16, int64_t tokens, i
                        uint8_t* xq_codes, uint8_t* xq_scales, uint32_t* x_mask,
                        uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
                        void* stream) {
+    return quartet_linear_fwd_block(x_bf16, w_bf16, tokens, in, out, 32, y, y_dtype, xq_codes, xq_scales, x_mask,
+                                    wq_codes, wq_scales, w_mask, stream);
+}
+
+int quartet_linear_fwd_block(const void* x_bf16, const void* w_bf16, int64_t tokens, int64_t in, int64_t out,
+                             int hadamard_block, void* y, int y_dtype,
+                             uint8_t* xq_codes, uint8_t* xq_scales, uint32_t* x_mask,
+                             uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
+                             void* stream) {
     if (!x_bf16 || !w_bf16 || !y || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask)
         return QUARTET_EINVAL;
-    if (tokens < 0 || in < 0 || out < 0 || (in % 32) != 0) return QUARTET_EINVAL;
-    int rc = quartet_quant_fwd(x_bf16, tokens, in, in, 0, xq_codes, xq_scales, x_mask, stream);
+    if (block_groups(hadamard_block) == 0u) return QUARTET_EINVAL;
+    if (tokens < 0 || in < 0 || out < 0 || (in % hadamard_block) != 0) return QUARTET_EINVAL;
+    int rc = quartet_quant_fwd_block(x_bf16, tokens, in, in, 0, hadamard_block, xq_codes, xq_scales, x_mask, stream);
     if (rc) return rc;
-    rc = quartet_quant_fwd(w_bf16, out, in, in, 0, wq_codes, wq_scales, w_mask, stream);
+    rc = quartet_quant_fwd_block(w_bf16, out, in, in, 0, hadamard_block, wq_codes, wq_scales, w_mask, stream);
     if (rc) return rc;
     return quartet_mxfp4_gemm(xq_codes, xq_scales, wq_codes, wq_scales, tokens, out, in, 1.0f, y, y_dtype,
                               out, stream);
 }
 
 size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out) {
+    return quartet_linear_workspace_bytes_block(tokens, in, out, 32);
+}
+
+size_t quartet_linear_workspace_bytes_block(int64_t tokens, int64_t in, int64_t out, int hadamard_block) {
+    if (block_groups(hadamard_block) == 0u) return 0;
     if (tokens < 0 || in < 0 || out < 0) return 0;
-    if ((tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return 0;
-    return plan_bwd(tokens, in, out).total;
+    if ((tokens % hadamard_block) != 0 || (in % hadamard_block) != 0 || (out % hadamard_block) != 0) return 0;
+    return plan_bwd(tokens, in, out, hadamard_block > 32).total;
 }
 
 int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
@@ -334,34 +410,60 @@ int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t 
                        uint64_t seed, int rounding,
                        void* dx, void* dw, int grad_dtype,
                        void* workspace, size_t workspace_bytes, void* stream) {
+    return quartet_linear_bwd_block(dy_bf16, tokens, in, out, 32, xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask,
+                                    seed, rounding, dx, dw, grad_dtype, workspace, workspace_bytes, stream);
+}
+
+int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out, int hadamard_block,
+                             const uint8_t* xq_codes, const uint8_t* xq_scales, const uint32_t* x_mask,
+                             const uint8_t* wq_codes, const uint8_t* wq_scales, const uint32_t* w_mask,
+                             uint64_t seed, int rounding,
+                             void* dx, void* dw, int grad_dtype,
+                             void* workspace, size_t workspace_bytes, void* stream) {
     if (!dy_bf16 || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask || !dx || !dw)
         return QUARTET_EINVAL;
+    const int hb = hadamard_block;
+    if (block_groups(hb) == 0u) return QUARTET_EINVAL;
     if (tokens < 0 || in < 0 || out < 0) return QUARTET_EINVAL;
-    if ((tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return QUARTET_EINVAL;
+    if ((tokens % hb) != 0 || (in % hb) != 0 || (out % hb) != 0) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     if (grad_dtype != QUARTET_DTYPE_F32 && grad_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
-    const BwdWorkspace w = plan_bwd(tokens, in, out);
+    const bool big = hb > 32;
+    const BwdWorkspace w = plan_bwd(tokens, in, out, big);
     if (w.total > 0 && (!workspace || workspace_bytes < w.total)) return QUARTET_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUARTET_EINVAL;
     uint8_t* base = static_cast<uint8_t*>(workspace);
     uint8_t *g_codes = base + w.g_codes, *g_scales = base + w.g_scales;
     uint8_t *b_codes = base + w.b_codes, *b_scales = base + w.b_scales;
-    const uint32_t sw = quartet_sign_word(seed);
+    float* acc = reinterpret_cast<float*>(base + w.acc);
+    uint32_t sw[8];
+    quartet_sign_words(seed, sw);
     const float c169 = 16.0f / 9.0f;
     int rc;
     // dx = 16/9 H( (Q(dy) Q(W_q^T)^T) . M_x ), inner dimension = out
-    rc = quartet_quant_bwd_sr(dy_bf16, tokens, out, out, 0, sw, seed, 0u, rounding, g_codes, g_scales, stream);
+    rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
     if (rc) return rc;
-    rc = quartet_requant_transpose_sr(wq_codes, wq_scales, in, out, sw, seed, 1u, rounding, b_codes, b_scales, stream);
+    rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
-    rc = quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, tokens, in, out, x_mask, c169, dx, grad_dtype, in, stream);
+    if (!big) {
+        rc = quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, tokens, in, out, x_mask, c169, dx, grad_dtype, in, stream);
+    } else {
+        // blocks above 32 span more columns than the GEMM's in-kernel epilogue handles: fp32 product, then the epilogue kernel
+        rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+        if (rc) return rc;
+        rc = quartet_grad_epilogue_block(acc, x_mask, tokens, in, hb, c169, dx, grad_dtype, stream);
+    }
     if (rc) return rc;
     // dW = 16/9 H( (Q(dy^T) Q(X_q^T)^T) . M_w ), inner dimension = tokens
-    rc = quartet_quant_bwd_sr(dy_bf16, out, tokens, out, 1, sw, seed, 2u, rounding, g_codes, g_scales, stream);
+    rc = quartet_quant_bwd_sr_block(dy_bf16, out, tokens, out, 1, hb, sw, seed, 2u, rounding, g_codes, g_scales, stream);
     if (rc) return rc;
-    rc = quartet_requant_transpose_sr(xq_codes, xq_scales, in, tokens, sw, seed, 3u, rounding, b_codes, b_scales, stream);
+    rc = quartet_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
-    return quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, out, in, tokens, w_mask, c169, dw, grad_dtype, in, stream);
+    if (!big)
+        return quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, out, in, tokens, w_mask, c169, dw, grad_dtype, in, stream);
+    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+    if (rc) return rc;
+    return quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);
 }
 
 }  // extern "C"

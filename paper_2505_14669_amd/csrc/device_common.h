@@ -53,9 +53,9 @@ __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
 // Five butterfly stages of the 32-point Walsh-Hadamard transform in natural (Sylvester) order,
-// stride 1,2,4,8,16, then the normalization multiply (Section 3, "Outlier mitigation").  Each
-// stage is a separate fp32 add/sub: the build disables FMA contraction.
-__device__ __forceinline__ void fwht32(float (&v)[32]) {
+// stride 1,2,4,8,16 (Section 3, "Outlier mitigation").  Each stage is a separate fp32 add/sub: the
+// build disables FMA contraction.  The normalization multiply is the caller's.
+__device__ __forceinline__ void fwht32_unscaled(float (&v)[32]) {
 #pragma unroll
     for (int h = 1; h < 32; h <<= 1) {
 #pragma unroll
@@ -67,8 +67,48 @@ __device__ __forceinline__ void fwht32(float (&v)[32]) {
             }
         }
     }
+}
+__device__ __forceinline__ void fwht32(float (&v)[32]) {
+    fwht32_unscaled(v);
 #pragma unroll
     for (int i = 0; i < 32; ++i) v[i] = v[i] * kInvSqrt32;
+}
+
+// Hadamard blocks of nb = 2, 4 or 8 groups (64, 128, 256 elements; Section 4.4, "Costs and format
+// specialization"): H_{32 nb} = H_nb (x) H_32, evaluated as the butterflies that combine whole groups
+// first (stride 32, 64, 128 elements), then fwht32_unscaled inside each group, then one multiply by
+// fl(1/sqrt(32 nb)).
+__device__ __forceinline__ float block_norm(uint32_t nb) {
+    return nb == 1u ? kInvSqrt32 : nb == 2u ? 0.125f : nb == 4u ? 0.08838834764831845f /* fl(1/sqrt 128) */ : 0.0625f;
+}
+
+// value of lane (l ^ XOR), XOR = 1, 2 or 4
+template <int XOR> __device__ __forceinline__ float lane_xor(float x);
+template <> __device__ __forceinline__ float lane_xor<1>(float x) {
+    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true));
+}
+template <> __device__ __forceinline__ float lane_xor<2>(float x) {
+    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), 0x4E /* quad_perm [2,3,0,1] */, 0xF, 0xF, true));
+}
+template <> __device__ __forceinline__ float lane_xor<4>(float x) {
+    return u2f((uint32_t)__builtin_amdgcn_ds_swizzle((int)f2u(x), 0x101F /* bit mode: and 0x1F, or 0, xor 4 */));
+}
+
+// One group-combining stage when the groups of a block sit in consecutive lanes (group j of the block
+// in lane l with l % nb == j): the lower lane of a pair keeps a + b, the upper one a - b, a being the
+// lower lane's value.  Every lane of the wave must take part.
+template <int XOR> __device__ __forceinline__ void cross_lane_stage(float (&v)[32], uint32_t lane) {
+    const bool upper = (lane & (uint32_t)XOR) != 0u;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const float other = lane_xor<XOR>(v[i]);
+        v[i] = upper ? other - v[i] : v[i] + other;
+    }
+}
+__device__ __forceinline__ void cross_lane_stages(float (&v)[32], uint32_t lane, uint32_t nb) {
+    if (nb > 1u) cross_lane_stage<1>(v, lane);
+    if (nb > 2u) cross_lane_stage<2>(v, lane);
+    if (nb > 4u) cross_lane_stage<4>(v, lane);
 }
 
 // Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> four 32-bit words.

@@ -13,10 +13,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2_rne(float lo, float hi) {
     return (a >> 16) | (b & 0xFFFF0000u);
 }
 
-template <bool OUT_BF16, bool MASK>
+// NB > 1: the Hadamard block spans nb = 2, 4 or 8 groups held by consecutive lanes (a row's groups start
+// at a multiple of nb), combined across lanes before the 32-point stages.
+template <bool OUT_BF16, bool MASK, bool BIG>
 __global__ void __launch_bounds__(256)
 grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t n_groups,
-                     float scale, void* out) {
+                     float scale, void* out, uint32_t nb) {
     __shared__ uint4 stage[4][512];
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     const uint32_t base_group = (blockIdx.x * 4u + wave) * 64u;
@@ -41,7 +43,15 @@ grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t
 #pragma unroll
         for (int i = 0; i < 32; ++i) v[i] = ((mw >> i) & 1u) ? v[i] : 0.0f;
     }
-    fwht32(v);
+    if (BIG) {
+        cross_lane_stages(v, lane, nb);
+        fwht32_unscaled(v);
+        const float c = block_norm(nb);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
+    } else {
+        fwht32(v);
+    }
 #pragma unroll
     for (int i = 0; i < 32; ++i) v[i] = v[i] * scale;
     if (grp >= n_groups) return;
@@ -58,19 +68,27 @@ grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t
     }
 }
 
-hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, float scale,
+template <bool OUT_BF16, bool MASK>
+static void launch_epilogue_nb(dim3 grid, hipStream_t st, const uint4* gp, const uint32_t* mask, uint32_t n_groups,
+                               float scale, void* out, uint32_t nb) {
+    dim3 block(256);
+    if (nb > 1u) hipLaunchKernelGGL((grad_epilogue_kernel<OUT_BF16, MASK, true>), grid, block, 0, st, gp, mask, n_groups, scale, out, nb);
+    else hipLaunchKernelGGL((grad_epilogue_kernel<OUT_BF16, MASK, false>), grid, block, 0, st, gp, mask, n_groups, scale, out, nb);
+}
+
+hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, uint32_t nb, float scale,
                                 void* out, int out_bf16, hipStream_t st) {
     uint64_t n_groups = (uint64_t)m * (uint64_t)(n / 32);
     if (n_groups == 0) return hipSuccess;
     uint32_t tiles = (uint32_t)((n_groups + 63) / 64);
-    dim3 grid((tiles + 3) / 4), block(256);
+    dim3 grid((tiles + 3) / 4);
     const uint4* gp = reinterpret_cast<const uint4*>(g);
     if (out_bf16) {
-        if (mask) hipLaunchKernelGGL((grad_epilogue_kernel<true, true>), grid, block, 0, st, gp, mask, (uint32_t)n_groups, scale, out);
-        else hipLaunchKernelGGL((grad_epilogue_kernel<true, false>), grid, block, 0, st, gp, mask, (uint32_t)n_groups, scale, out);
+        if (mask) launch_epilogue_nb<true, true>(grid, st, gp, mask, (uint32_t)n_groups, scale, out, nb);
+        else launch_epilogue_nb<true, false>(grid, st, gp, mask, (uint32_t)n_groups, scale, out, nb);
     } else {
-        if (mask) hipLaunchKernelGGL((grad_epilogue_kernel<false, true>), grid, block, 0, st, gp, mask, (uint32_t)n_groups, scale, out);
-        else hipLaunchKernelGGL((grad_epilogue_kernel<false, false>), grid, block, 0, st, gp, mask, (uint32_t)n_groups, scale, out);
+        if (mask) launch_epilogue_nb<false, true>(grid, st, gp, mask, (uint32_t)n_groups, scale, out, nb);
+        else launch_epilogue_nb<false, false>(grid, st, gp, mask, (uint32_t)n_groups, scale, out, nb);
     }
     return hipGetLastError();
 }

@@ -5,11 +5,13 @@
 
 namespace quartet {
 
-// randomized-Hadamard sign word and Philox key/stream of one quantizer call
+// randomized-Hadamard sign words, Philox key/stream and Hadamard block of one quantizer call
 struct SrParams {
-    uint32_t sign_word;
+    uint32_t sign_word;        // sign bits of a 32-element block (= sign_words[0])
     uint32_t key0, key1;
     uint32_t stream_id;
+    uint32_t nb;               // groups per Hadamard block: 1 (the method's g = 32), 2, 4 or 8
+    uint32_t sign_words[8];    // sign bits of a block of 32 nb elements, word j for its group j
 };
 
 hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_t ldx, int transpose,
@@ -22,7 +24,7 @@ hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t r
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                        int d_bf16, int64_t ldd, int fused, const uint32_t* mask, hipStream_t st);
-hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, float scale,
+hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, uint32_t nb, float scale,
                                 void* out, int out_bf16, hipStream_t st);
 
 // MXFP8 comparison path (E4M3 elements, E8M0 scale per 32)

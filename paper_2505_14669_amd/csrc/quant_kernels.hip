@@ -26,16 +26,49 @@ __device__ __forceinline__ uint32_t rtn_pack8(const float* v, float scale) {
     return w;
 }
 
-// Quantize one group held in v[] (not yet rotated).  q_base = (linear output position of element 0)/16
-// is the Philox call index of the group's first 16 elements.
+// Encode one rotated group held in v[]: scale, codes, mask.  q_base = (linear output position of
+// element 0)/16 is the Philox call index of the group's first 16 elements.
+template <int MODE>
+__device__ __forceinline__ void encode_group(float (&v)[32], const SrParams& p, uint64_t q_base,
+                                             uint4& codes, uint32_t& scale_byte, uint32_t& mask_word);
+
+__device__ __forceinline__ void flip_signs(float (&v)[32], uint32_t sign_word) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = u2f(f2u(v[i]) ^ (((sign_word >> i) & 1u) << 31));
+}
+
+// Quantize one group held in v[] (not yet rotated), Hadamard block = the group.
 template <int MODE>
 __device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p, uint64_t q_base,
                                                uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
-    if (MODE != kFwd) {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = u2f(f2u(v[i]) ^ (((p.sign_word >> i) & 1u) << 31));
-    }
+    if (MODE != kFwd) flip_signs(v, p.sign_word);
     fwht32(v);
+    encode_group<MODE>(v, p, q_base, codes, scale_byte, mask_word);
+}
+
+// The same when the Hadamard block spans p.nb groups held by consecutive lanes (lane % nb = the
+// group's place in its block): signs, the group-combining stages across lanes, the stages inside the
+// group, one normalization.  Every lane of the wave must call it.
+template <int MODE>
+__device__ __forceinline__ void quantize_group_lanes(float (&v)[32], const SrParams& p, uint32_t lane, uint64_t q_base,
+                                                     uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
+    if (MODE != kFwd) {
+        uint32_t sw = p.sign_words[0];
+#pragma unroll
+        for (uint32_t j = 1; j < 8; ++j) sw = ((lane & (p.nb - 1u)) == j) ? p.sign_words[j] : sw;
+        flip_signs(v, sw);
+    }
+    cross_lane_stages(v, lane, p.nb);
+    fwht32_unscaled(v);
+    const float c = block_norm(p.nb);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
+    encode_group<MODE>(v, p, q_base, codes, scale_byte, mask_word);
+}
+
+template <int MODE>
+__device__ __forceinline__ void encode_group(float (&v)[32], const SrParams& p, uint64_t q_base,
+                                             uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
     uint32_t c[4] = {0u, 0u, 0u, 0u};
     if (MODE == kFwd) {
         // QuEST: scale from the group RMS, round to nearest, remember what clipped
@@ -101,7 +134,9 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
 // through LDS so each lane ends up with its own group's 64 bytes.  Codes leave as 512 contiguous
 // bytes per row, mask words as 128; the 256 scale bytes of the block are exchanged through LDS and
 // leave as whole 32-byte runs of the scale tiles (8 rows x one dword), never as single bytes.
-template <int MODE, bool MASK>
+// BIG: the Hadamard block spans p.nb = 2, 4 or 8 groups; they sit in consecutive lanes (a row's groups
+// start at a multiple of 8 in every block), so the group-combining stages are lane exchanges.
+template <int MODE, bool MASK, bool BIG>
 __global__ void __launch_bounds__(256)
 quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
                  uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
@@ -137,7 +172,8 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
     const uint32_t row = row0 + row_local, g = kq0 * 8u + gi;
     uint4 out;
     uint32_t sb, mw;
-    quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
+    if (BIG) quantize_group_lanes<MODE>(v, p, lane, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
+    else quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
     // scale byte of (row, group gi) -> position of the tiled layout inside the block's 256 bytes:
     // [K-quad gi/8][h = gi%2][row_local][p = (gi%8)/2]
     reinterpret_cast<uint8_t*>(s_scale)[(((gi >> 3) * 2u + (gi & 1u)) * 8u + row_local) * 4u + ((gi & 7u) >> 1)] = (uint8_t)sb;
@@ -160,6 +196,54 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
                 for (uint32_t q = 0; q < 4; ++q)
                     if (kq * 8u + 2u * q + h < gk) dst[q] = (uint8_t)(w >> (8u * q));
             }
+        }
+    }
+}
+
+// Store phase of the transposed kernels: the tile's codes, scale bytes and mask words gathered in LDS
+// ([local column][group], codes with a 16-byte slot swizzle) leave as full 128-byte lines of codes,
+// 32-byte runs of mask words and whole dwords of the scale tiles.
+template <bool MASK>
+__device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, const uint8_t* s_scales, const uint32_t* s_mask,
+                                                      uint32_t col0, uint32_t grp0, uint32_t rows, uint32_t gk, uint32_t k,
+                                                      uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                                      uint32_t* __restrict__ mask) {
+    // full 128-byte lines of codes: 8 lanes per output row
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        uint32_t id = threadIdx.x + 256u * j;
+        uint32_t lc = id >> 3, part = id & 7u;
+        uint32_t r = col0 + lc, grp = grp0 + part;
+        if (r < rows && grp < gk) {
+            uint4 q = s_codes[lc * 8u + (part ^ ((lc >> 1) & 7u))];
+            store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, q);
+        }
+    }
+    if (MASK) {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+            uint32_t id = threadIdx.x + 256u * j;
+            uint32_t lc = id >> 3, part = id & 7u;
+            uint32_t r = col0 + lc, grp = grp0 + part;
+            if (r < rows && grp < gk) mask[(size_t)r * gk + grp] = s_mask[lc * 8u + part];
+        }
+    }
+    // scales: the block's 8 groups are one K-quad, so each 32-row block of the tile is one 256-byte
+    // scale tile; thread t writes dword t%64 of tile t/64 (bytes = groups h, 2+h, 4+h, 6+h of its row)
+    const uint32_t t = threadIdx.x, lc = (t >> 6) * 32u + (t & 31u), h = (t >> 5) & 1u;
+    const uint32_t r = col0 + lc;
+    if (r < rows) {
+        uint32_t w = 0u;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) w |= (uint32_t)s_scales[lc * 8u + 2u * q + h] << (8u * q);
+        const uint32_t kq = (gk + 7u) >> 3;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(r, grp0 + h, kq));
+        if (grp0 + 6u + h < gk) {
+            *dst = w;
+        } else {
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q)
+                if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
         }
     }
 }
@@ -225,46 +309,93 @@ quant_transposed_kernel(const uint16_t* __restrict__ src,
         }
     }
     __syncthreads();
-    // full 128-byte lines of codes: 8 lanes per output row
+    transposed_store_tile<MASK>(s_codes, s_scales, s_mask, col0, grp0, rows, gk, k, codes, scales, mask);
+}
+
+// The same tile for Hadamard blocks of NB = 2, 4 or 8 groups.  The groups of a block are whole source
+// row groups, so the group-combining stages come first and work on raw values: for its two groups
+// (places j, j+1 of one block) a wave reads all NB groups of the block for one column of its pair at a
+// time (the other waves of the block read the same lines: the extra reads are cache hits), forms the
+// two outputs of the butterfly tree per source row, and only then runs the 32-point stages.
+template <int MODE, bool MASK, int NB>
+__global__ void __launch_bounds__(256)
+quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, uint32_t k, int64_t ldx,
+                              uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                              uint32_t* __restrict__ mask, SrParams p) {
+    __shared__ uint4 s_codes[128 * 8];
+    __shared__ uint8_t s_scales[128 * 8];
+    __shared__ uint32_t s_mask[128 * 8];
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
+    const uint32_t gk = k >> 5;
+    const uint32_t col0 = blockIdx.y * 128u;
+    const uint32_t grp0 = blockIdx.x * 8u;
+    const uint32_t col = col0 + 2u * lane;
+    const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
+    const uint32_t src_cols = (rows - col0) < 128u ? (rows - col0) : 128u;
+    const __amdgpu_buffer_rsrc_t res_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(src + (size_t)grp0 * 32u * ldx + col0), 0,
+        (int)(((src_rows - 1u) * (uint32_t)ldx + src_cols) * 2u), 0x00020000);
+    const uint32_t pitch = (uint32_t)ldx * 2u;
+    const uint32_t gl0 = 2u * wave;                          // the wave's groups gl0, gl0+1 inside the tile
+    const uint32_t jb = gl0 & ~((uint32_t)NB - 1u);           // first group of their Hadamard block
+    const uint32_t j = gl0 - jb;                              // even place of gl0 in the block
+    const uint32_t neg2 = (j & 2u) << 30, neg4 = (j & 4u) << 29;   // sign of the upper operand at the 64- and 128-stages
+    const float norm = block_norm((uint32_t)NB);
+    const uint32_t sw = lane & 7u;                            // 16-byte slot swizzle against bank conflicts
+#pragma unroll 1
+    for (uint32_t c = 0; c < 2; ++c) {
+        float va[32], vb[32];                                 // group gl0 and gl0+1 of column col+c, after the group stages
 #pragma unroll
-    for (uint32_t j = 0; j < 4; ++j) {
-        uint32_t id = threadIdx.x + 256u * j;
-        uint32_t lc = id >> 3, part = id & 7u;
-        uint32_t r = col0 + lc, grp = grp0 + part;
-        if (r < rows && grp < gk) {
-            uint4 q = s_codes[lc * 8u + (part ^ ((lc >> 1) & 7u))];
-            store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, q);
-        }
-    }
-    if (MASK) {
+        for (uint32_t i = 0; i < 32; ++i) {
+            // at most four source rows of every group in flight: without the fence all 32 NB loads are
+            // hoisted to the top and the kernel runs out of registers
+            if ((i & 3u) == 0u) __builtin_amdgcn_sched_barrier(0);
+            float x[NB];
 #pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) {
-            uint32_t id = threadIdx.x + 256u * j;
-            uint32_t lc = id >> 3, part = id & 7u;
-            uint32_t r = col0 + lc, grp = grp0 + part;
-            if (r < rows && grp < gk) mask[(size_t)r * gk + grp] = s_mask[lc * 8u + part];
-        }
-    }
-    // scales: the block's 8 groups are one K-quad, so each 32-row block of the tile is one 256-byte
-    // scale tile; thread t writes dword t%64 of tile t/64 (bytes = groups h, 2+h, 4+h, 6+h of its row)
-    {
-        const uint32_t t = threadIdx.x, lc = (t >> 6) * 32u + (t & 31u), h = (t >> 5) & 1u;
-        const uint32_t r = col0 + lc;
-        if (r < rows) {
-            uint32_t w = 0u;
-#pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) w |= (uint32_t)s_scales[lc * 8u + 2u * q + h] << (8u * q);
-            const uint32_t kq = (gk + 7u) >> 3;
-            uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(r, grp0 + h, kq));
-            if (grp0 + 6u + h < gk) {
-                *dst = w;
-            } else {
-#pragma unroll
-                for (uint32_t q = 0; q < 4; ++q)
-                    if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
+            for (uint32_t jj = 0; jj < (uint32_t)NB; ++jj) {
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(res_x, (int)(4u * lane), (int)(((jb + jj) * 32u + i) * pitch), 0);
+                uint32_t bits = c ? (w & 0xFFFF0000u) : (w << 16);
+                if (MODE != kFwd) bits ^= ((p.sign_words[jj] >> i) & 1u) << 31;
+                x[jj] = u2f(bits);
             }
+            float sa[NB / 2], sb[NB / 2];                     // 32-stage: sums feed place j, differences place j+1
+#pragma unroll
+            for (uint32_t m = 0; m < (uint32_t)NB / 2u; ++m) {
+                sa[m] = x[2 * m] + x[2 * m + 1];
+                sb[m] = x[2 * m] - x[2 * m + 1];
+            }
+            if (NB >= 4) {
+#pragma unroll
+                for (uint32_t m = 0; m < (uint32_t)NB / 4u; ++m) {
+                    sa[m] = sa[2 * m] + u2f(f2u(sa[2 * m + 1]) ^ neg2);
+                    sb[m] = sb[2 * m] + u2f(f2u(sb[2 * m + 1]) ^ neg2);
+                }
+            }
+            if (NB >= 8) {
+                sa[0] = sa[0] + u2f(f2u(sa[1]) ^ neg4);
+                sb[0] = sb[0] + u2f(f2u(sb[1]) ^ neg4);
+            }
+            va[i] = sa[0];
+            vb[i] = sb[0];
+        }
+#pragma unroll
+        for (uint32_t rb = 0; rb < 2; ++rb) {
+            float (&v)[32] = rb ? vb : va;
+            fwht32_unscaled(v);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[i] = v[i] * norm;
+            const uint32_t gl = gl0 + rb;
+            uint4 q;
+            uint32_t sbyte, m;
+            encode_group<MODE>(v, p, ((uint64_t)(col + c) * k + (grp0 + gl) * 32u) >> 4, q, sbyte, m);
+            const uint32_t lc = 2u * lane + c;
+            s_codes[lc * 8u + (gl ^ sw)] = q;
+            s_scales[lc * 8u + gl] = (uint8_t)sbyte;
+            if (MASK) s_mask[lc * 8u + gl] = m;
         }
     }
+    __syncthreads();
+    transposed_store_tile<MASK>(s_codes, s_scales, s_mask, col0, grp0, rows, gk, k, codes, scales, mask);
 }
 
 // ------------------------------------------------------------------ MXFP4 source, other dimension
@@ -401,6 +532,120 @@ requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* 
     }
 }
 
+// Re-quantization for Hadamard blocks of NB = 2, 4 or 8 groups (same tile, same stage).  The groups of
+// a block are whole groups of source rows, so the group-combining stages come first, on the decoded
+// values: for output group G (place j in its block) a lane decodes its 32 columns of the NB source
+// rows (block group jj, row rl), eight values at a time, flips their signs and folds them through the
+// butterfly tree down to place j; the 32-point stages follow after the transposition as usual.
+template <int MODE, int NB>
+__global__ void __launch_bounds__(256)
+requant_transposed_block_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
+                                uint32_t rows, uint32_t k, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                                SrParams p) {
+    __shared__ float s_stage[4][64 * kStageStride];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    float* stage = s_stage[wave];
+    const uint32_t gk = k >> 5, okq = (k + 255u) >> 8;
+    const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;
+    const uint32_t c0 = blockIdx.x * 256u + wave * 64u, kq = blockIdx.y, grp0 = kq * 8u;
+    const uint32_t rl = lane >> 1, ch = lane & 1u, cg = wave * 2u + ch;
+    const uint32_t cb0 = blockIdx.x * 256u;
+    const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
+    const uint32_t src_cols = (rows - cb0) < 256u ? (rows - cb0) : 256u;
+    const __amdgpu_buffer_rsrc_t res_c = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(src_codes + (size_t)grp0 * 32u * half + (cb0 >> 1)), 0,
+        (int)((src_rows - 1u) * half + (src_cols >> 1)), 0x00020000);
+    const size_t tile0 = ((size_t)grp0 * skq + (cb0 >> 8)) * 256u;
+    const __amdgpu_buffer_rsrc_t res_s = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(src_scales + tile0), 0, (int)((size_t)gk * skq * 256u - tile0), 0x00020000);
+    const uint32_t code_off = rl * half + ((wave * 64u + 32u * ch) >> 1);
+    const uint32_t scale_off = (((cg & 1u) << 5) + rl) * 4u + (cg >> 1);
+    const uint32_t code_step = 32u * half, scale_step = skq * 256u;
+    const uint32_t wr = (rl + 8u * ch) & 31u;
+    const uint32_t out_row = c0 + lane, rot = (8u * (lane >> 5)) & 31u;
+    const float norm = block_norm((uint32_t)NB);
+    uint32_t sw0 = 0u, sw1 = 0u;
+    uint8_t* crow = codes + (size_t)out_row * (k >> 1) + (size_t)grp0 * 16u;
+#pragma unroll 1
+    for (uint32_t g = 0; g < 8; ++g) {
+        const uint32_t jb = g & ~((uint32_t)NB - 1u), j = g - jb;
+        const uint32_t neg1 = (j & 1u) << 31, neg2 = (j & 2u) << 30, neg4 = (j & 4u) << 29;
+        v4u_t cw[NB];
+        float sc[NB];
+        uint32_t flip[NB];
+#pragma unroll
+        for (uint32_t jj = 0; jj < (uint32_t)NB; ++jj) {
+            cw[jj] = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, (int)((jb + jj) * code_step), 0);
+            const uint32_t sbyte = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, (int)((jb + jj) * scale_step), 0);
+            sc[jj] = u2f(sbyte << 23);
+            flip[jj] = ((p.sign_words[jj] >> rl) & 1u) << 31;   // element rl of block group jj
+        }
+        float f[32];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            __builtin_amdgcn_sched_barrier(0);               // one dword of codes per group at a time
+            float x[NB][8];
+#pragma unroll
+            for (uint32_t jj = 0; jj < (uint32_t)NB; ++jj) {
+                const uint32_t w = cw[jj][q];
+                v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, sc[jj], 0);
+                v2f b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, sc[jj], 1);
+                v2f c = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, sc[jj], 2);
+                v2f d = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w, sc[jj], 3);
+                const float t[8] = {a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+#pragma unroll
+                for (uint32_t e = 0; e < 8; ++e) x[jj][e] = u2f(f2u(t[e]) ^ flip[jj]);
+            }
+#pragma unroll
+            for (uint32_t e = 0; e < 8; ++e) {
+                float y[NB / 2];
+#pragma unroll
+                for (uint32_t m = 0; m < (uint32_t)NB / 2u; ++m) y[m] = x[2 * m][e] + u2f(f2u(x[2 * m + 1][e]) ^ neg1);
+                if (NB >= 4) {
+#pragma unroll
+                    for (uint32_t m = 0; m < (uint32_t)NB / 4u; ++m) y[m] = y[2 * m] + u2f(f2u(y[2 * m + 1]) ^ neg2);
+                }
+                if (NB >= 8) y[0] = y[0] + u2f(f2u(y[1]) ^ neg4);
+                f[8 * q + e] = y[0];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (uint32_t jx = 0; jx < 32; ++jx) stage[(32u * ch + jx) * kStageStride + wr] = f[jx];
+        __builtin_amdgcn_wave_barrier();
+        float v[32];
+#pragma unroll
+        for (uint32_t q = 0; q < 8; ++q) {
+            const float4 xx = *reinterpret_cast<const float4*>(&stage[lane * kStageStride + ((4u * q + rot) & 31u)]);
+            v[4 * q] = xx.x; v[4 * q + 1] = xx.y; v[4 * q + 2] = xx.z; v[4 * q + 3] = xx.w;
+        }
+        __builtin_amdgcn_wave_barrier();
+        fwht32_unscaled(v);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * norm;
+        uint4 out;
+        uint32_t sb, mw;
+        encode_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + g) * 32u) >> 4, out, sb, mw);
+        if (g & 1u) sw1 |= sb << (8u * (g >> 1));
+        else sw0 |= sb << (8u * (g >> 1));
+        if (out_row < rows && grp0 + g < gk) *reinterpret_cast<uint4*>(crow + 16u * g) = out;
+    }
+    if (out_row >= rows) return;
+#pragma unroll
+    for (uint32_t h = 0; h < 2; ++h) {
+        const uint32_t w = h ? sw1 : sw0;
+        if (grp0 + h >= gk) continue;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(scales + scale_tile_offset(out_row, grp0 + h, okq));
+        if (grp0 + 6u + h < gk) {
+            *dst = w;
+        } else {
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q)
+                if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
+        }
+    }
+}
+
 // ------------------------------------------------------------------ MXFP4 -> fp32
 __global__ void __launch_bounds__(256)
 dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, uint32_t n_groups,
@@ -432,33 +677,50 @@ static FastDiv make_fast_div(uint32_t d) {
     return FastDiv{(uint32_t)mul, l};
 }
 
+template <int MODE, bool MASK>
+static void launch_row_big(bool big, dim3 grid, hipStream_t st, const void* x, int64_t rows, uint32_t gk, int64_t ldx,
+                           uint8_t* codes, uint8_t* scales, uint32_t* mask, const SrParams& p, uint32_t k_blocks) {
+    dim3 block(256);
+    if (big)
+        hipLaunchKernelGGL((quant_row_kernel<MODE, MASK, true>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
+                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
+    else
+        hipLaunchKernelGGL((quant_row_kernel<MODE, MASK, false>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
+                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
+}
+
 template <int MODE>
 static hipError_t launch_row(const void* x, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
                              uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
     if (rows == 0 || k == 0) return hipSuccess;
     const uint32_t gk = (uint32_t)(k / 32);
     const uint32_t k_blocks = (gk + 31) / 32;
-    dim3 grid((uint32_t)((rows + 7) / 8) * k_blocks), block(256);
-    if (mask)
-        hipLaunchKernelGGL((quant_row_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
-                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
-    else
-        hipLaunchKernelGGL((quant_row_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)x, (uint32_t)rows,
-                           gk, ldx, (uint4*)codes, scales, mask, p, k_blocks, make_fast_div(k_blocks));
+    dim3 grid((uint32_t)((rows + 7) / 8) * k_blocks);
+    if (mask) launch_row_big<MODE, true>(p.nb > 1u, grid, st, x, rows, gk, ldx, codes, scales, mask, p, k_blocks);
+    else launch_row_big<MODE, false>(p.nb > 1u, grid, st, x, rows, gk, ldx, codes, scales, mask, p, k_blocks);
     return hipGetLastError();
+}
+
+template <int MODE, bool MASK>
+static void launch_transposed_nb(dim3 grid, hipStream_t st, const void* src, int64_t rows, int64_t k, int64_t ldx,
+                                 uint8_t* codes, uint8_t* scales, uint32_t* mask, const SrParams& p) {
+    dim3 block(256);
+    const uint16_t* s = (const uint16_t*)src;
+    switch (p.nb) {
+    case 1u: hipLaunchKernelGGL((quant_transposed_kernel<MODE, MASK>), grid, block, 0, st, s, (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p); break;
+    case 2u: hipLaunchKernelGGL((quant_transposed_block_kernel<MODE, MASK, 2>), grid, block, 0, st, s, (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p); break;
+    case 4u: hipLaunchKernelGGL((quant_transposed_block_kernel<MODE, MASK, 4>), grid, block, 0, st, s, (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p); break;
+    default: hipLaunchKernelGGL((quant_transposed_block_kernel<MODE, MASK, 8>), grid, block, 0, st, s, (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p); break;
+    }
 }
 
 template <int MODE>
 static hipError_t launch_transposed(const void* src, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes,
                                     uint8_t* scales, uint32_t* mask, const SrParams& p, hipStream_t st) {
     if (rows == 0 || k == 0) return hipSuccess;
-    dim3 grid((uint32_t)((k / 32 + 7) / 8), (uint32_t)((rows + 127) / 128)), block(256);
-    if (mask)
-        hipLaunchKernelGGL((quant_transposed_kernel<MODE, true>), grid, block, 0, st, (const uint16_t*)src,
-                           (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
-    else
-        hipLaunchKernelGGL((quant_transposed_kernel<MODE, false>), grid, block, 0, st, (const uint16_t*)src,
-                           (uint32_t)rows, (uint32_t)k, ldx, codes, scales, mask, p);
+    dim3 grid((uint32_t)((k / 32 + 7) / 8), (uint32_t)((rows + 127) / 128));
+    if (mask) launch_transposed_nb<MODE, true>(grid, st, src, rows, k, ldx, codes, scales, mask, p);
+    else launch_transposed_nb<MODE, false>(grid, st, src, rows, k, ldx, codes, scales, mask, p);
     return hipGetLastError();
 }
 
@@ -478,17 +740,25 @@ hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_
     }
 }
 
+template <int MODE>
+static void launch_requant_nb(dim3 grid, hipStream_t st, const uint8_t* src_codes, const uint8_t* src_scales, int64_t rows,
+                              int64_t k, const SrParams& p, uint8_t* codes, uint8_t* scales) {
+    dim3 block(256);
+    switch (p.nb) {
+    case 1u: hipLaunchKernelGGL((requant_transposed_kernel<MODE>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
+    case 2u: hipLaunchKernelGGL((requant_transposed_block_kernel<MODE, 2>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
+    case 4u: hipLaunchKernelGGL((requant_transposed_block_kernel<MODE, 4>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
+    default: hipLaunchKernelGGL((requant_transposed_block_kernel<MODE, 8>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
+    }
+}
+
 hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const uint8_t* src_scales,
                                     int64_t rows, int64_t k, const SrParams& p, uint8_t* codes,
                                     uint8_t* scales, hipStream_t st) {
     if (rows == 0 || k == 0) return hipSuccess;
-    dim3 grid((uint32_t)((rows + 255) / 256), (uint32_t)((k + 255) / 256)), block(256);
-    if (mode == kBwdRtn)
-        hipLaunchKernelGGL((requant_transposed_kernel<kBwdRtn>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows,
-                           (uint32_t)k, codes, scales, p);
-    else
-        hipLaunchKernelGGL((requant_transposed_kernel<kBwdSr>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows,
-                           (uint32_t)k, codes, scales, p);
+    dim3 grid((uint32_t)((rows + 255) / 256), (uint32_t)((k + 255) / 256));
+    if (mode == kBwdRtn) launch_requant_nb<kBwdRtn>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
+    else launch_requant_nb<kBwdSr>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
     return hipGetLastError();
 }
 

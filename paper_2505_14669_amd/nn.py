@@ -4,8 +4,8 @@ Argument marshalling only: every arithmetic step runs in the library's kernels
 (quartet_linear_fwd / quartet_linear_bwd).  torch provides device memory, streams and the autograd
 graph.  There is no fallback: without a GPU or without the built library these calls raise.
 
-Shapes: the flattened token count, in_features and out_features must be multiples of 32 (the MXFP4
-group and the Hadamard block of the method).
+Shapes: the flattened token count, in_features and out_features must be multiples of the Hadamard
+block (32, the MXFP4 group, unless a layer asks for 64, 128 or 256).
 """
 import torch
 
@@ -29,10 +29,11 @@ class _Workspace:
 class QuartetLinearFunction(torch.autograd.Function):
     """y = x W^T with MXFP4 operands (Algorithm 1 Forward); the backward pass returns the gradients of
     Algorithm 1 Backward.  x: [..., in] bf16, weight: [out, in] bf16, seed: python int naming the
-    stochastic-rounding draws of this call's backward pass, rounding: 0 stochastic / 1 nearest."""
+    stochastic-rounding draws of this call's backward pass, rounding: 0 stochastic / 1 nearest,
+    hadamard_block: 32 (the method), 64, 128 or 256."""
 
     @staticmethod
-    def forward(ctx, x, weight, seed, rounding):
+    def forward(ctx, x, weight, seed, rounding, hadamard_block=32):
         if x.dtype != torch.bfloat16 or weight.dtype != torch.bfloat16:
             raise TypeError("QuartetLinearFunction takes bf16 activations and weights")
         if not (x.is_cuda and weight.is_cuda):
@@ -41,8 +42,11 @@ class QuartetLinearFunction(torch.autograd.Function):
         x2 = x.reshape(-1, in_f).contiguous()
         w2 = weight.contiguous()
         tokens = x2.shape[0]
-        if tokens % 32 or in_f % 32 or out_f % 32:
-            raise ValueError("tokens, in_features and out_features must be multiples of 32")
+        hb = int(hadamard_block)
+        if hb not in (32, 64, 128, 256):
+            raise ValueError("hadamard_block must be 32, 64, 128 or 256")
+        if tokens % hb or in_f % hb or out_f % hb:
+            raise ValueError(f"tokens, in_features and out_features must be multiples of {hb}")
         dev = x.device
         u8 = dict(dtype=torch.uint8, device=dev)
         y = torch.empty((tokens, out_f), dtype=torch.bfloat16, device=dev)
@@ -52,26 +56,26 @@ class QuartetLinearFunction(torch.autograd.Function):
         wq_codes = torch.empty((out_f, in_f // 2), **u8)
         wq_scales = torch.empty((q.quartet_scale_bytes(out_f, in_f),), **u8)
         w_mask = torch.empty((out_f, in_f // 32), dtype=torch.int32, device=dev)
-        q.check(q.quartet_linear_fwd(x2, w2, tokens, in_f, out_f, y, q.QUARTET_DTYPE_BF16,
-                                     xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask))
+        q.check(q.quartet_linear_fwd_block(x2, w2, tokens, in_f, out_f, hb, y, q.QUARTET_DTYPE_BF16,
+                                           xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask))
         ctx.save_for_backward(xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask)
-        ctx.dims = (tokens, in_f, out_f, tuple(x.shape), int(seed), int(rounding))
+        ctx.dims = (tokens, in_f, out_f, tuple(x.shape), int(seed), int(rounding), hb)
         return y.reshape(*x.shape[:-1], out_f)
 
     @staticmethod
     def backward(ctx, dy):
         xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask = ctx.saved_tensors
-        tokens, in_f, out_f, x_shape, seed, rounding = ctx.dims
+        tokens, in_f, out_f, x_shape, seed, rounding, hb = ctx.dims
         dy2 = dy.reshape(tokens, out_f).to(torch.bfloat16).contiguous()
         dev = dy.device
         dx = torch.empty((tokens, in_f), dtype=torch.bfloat16, device=dev)
         dw = torch.empty((out_f, in_f), dtype=torch.bfloat16, device=dev)
-        nbytes = q.quartet_linear_workspace_bytes(tokens, in_f, out_f)
+        nbytes = q.quartet_linear_workspace_bytes_block(tokens, in_f, out_f, hb)
         ws = _Workspace.get(dev, nbytes)
-        q.check(q.quartet_linear_bwd(dy2, tokens, in_f, out_f, xq_codes, xq_scales, x_mask,
-                                     wq_codes, wq_scales, w_mask, seed, rounding,
-                                     dx, dw, q.QUARTET_DTYPE_BF16, ws, nbytes))
-        return dx.reshape(x_shape), dw, None, None
+        q.check(q.quartet_linear_bwd_block(dy2, tokens, in_f, out_f, hb, xq_codes, xq_scales, x_mask,
+                                           wq_codes, wq_scales, w_mask, seed, rounding,
+                                           dx, dw, q.QUARTET_DTYPE_BF16, ws, nbytes))
+        return dx.reshape(x_shape), dw, None, None, None
 
 
 class QuartetLinear(torch.nn.Module):
@@ -81,8 +85,9 @@ class QuartetLinear(torch.nn.Module):
     _next_id = 0
 
     def __init__(self, in_features, out_features, bias=False, seed=0, rounding=0, device="cuda",
-                 weight_dtype=torch.bfloat16):
+                 weight_dtype=torch.bfloat16, hadamard_block=32):
         super().__init__()
+        self.hadamard_block = hadamard_block
         self.in_features, self.out_features = in_features, out_features
         w = torch.randn(out_features, in_features, device=device) * (in_features ** -0.5)
         # weight_dtype=torch.float32 keeps fp32 master weights; the kernels always see a bf16 copy
@@ -97,5 +102,5 @@ class QuartetLinear(torch.nn.Module):
     def forward(self, x):
         seed = (self.base_seed << 48) | (self.layer_id << 32) | (self.calls & 0xFFFFFFFF)
         self.calls += 1
-        y = QuartetLinearFunction.apply(x, self.weight.to(torch.bfloat16), seed, self.rounding)
+        y = QuartetLinearFunction.apply(x, self.weight.to(torch.bfloat16), seed, self.rounding, self.hadamard_block)
         return y if self.bias is None else y + self.bias

@@ -149,3 +149,66 @@ class Linear:
                     x_mask=to_host(self.x_mask, np.uint32), wq_codes=to_host(self.wq_codes, np.uint8),
                     wq_scales=scales_from_tiled(to_host(self.wq_scales, np.uint8), self.o, self.i),
                     w_mask=to_host(self.w_mask, np.uint32))
+
+
+# ---- Hadamard blocks of 64, 128, 256 elements
+
+def quant_fwd_block(x_u16, block, transpose=False, want_mask=True):
+    x = to_dev(x_u16)
+    rows, k = (x_u16.shape[1], x_u16.shape[0]) if transpose else x_u16.shape
+    codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
+    mask = dev_empty((rows, k // 32), np.uint32, 0x5A5A5A5A) if want_mask else None
+    q.check(q.quartet_quant_fwd_block(x, rows, k, x_u16.shape[1], transpose, block, codes, scales, mask))
+    return (to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k),
+            to_host(mask, np.uint32) if want_mask else None)
+
+
+def quant_bwd_sr_block(x_u16, block, sign_words, seed, stream_id, rounding=0, transpose=False):
+    x = to_dev(x_u16)
+    rows, k = (x_u16.shape[1], x_u16.shape[0]) if transpose else x_u16.shape
+    codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
+    q.check(q.quartet_quant_bwd_sr_block(x, rows, k, x_u16.shape[1], transpose, block, list(sign_words), seed,
+                                         stream_id, rounding, codes, scales))
+    return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
+
+
+def requant_transpose_sr_block(src_codes, src_scales, block, sign_words, seed, stream_id, rounding=0):
+    k, rows = src_codes.shape[0], src_codes.shape[1] * 2
+    sc, ss = to_dev(src_codes), to_dev(scales_to_tiled(src_scales))
+    codes = dev_empty((rows, k // 2), np.uint8, 0xEE)
+    scales = dev_empty((max(q.quartet_scale_bytes(rows, k), 4),), np.uint8, 0xFF)
+    q.check(q.quartet_requant_transpose_sr_block(sc, ss, rows, k, block, list(sign_words), seed, stream_id, rounding,
+                                                 codes, scales))
+    return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
+
+
+def grad_epilogue_block(g, mask, block, scale, bf16=False):
+    m, n = g.shape
+    gd = to_dev(g)
+    md = None if mask is None else to_dev(mask)
+    out = dev_empty((m, n), np.uint16, 0) if bf16 else dev_empty((m, n), np.float32, float("nan"))
+    q.check(q.quartet_grad_epilogue_block(gd, md, m, n, block, float(scale), out,
+                                          q.QUARTET_DTYPE_BF16 if bf16 else q.QUARTET_DTYPE_F32))
+    return to_host(out, np.uint16 if bf16 else np.float32)
+
+
+class LinearBlock(Linear):
+    """The same layer with a Hadamard block of `block` elements."""
+
+    def __init__(self, x_u16, w_u16, block):
+        super().__init__(x_u16, w_u16)
+        self.block = block
+        self.ws_bytes = q.quartet_linear_workspace_bytes_block(self.t, self.i, self.o, block)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=DEV)
+
+    def fwd(self):
+        q.check(q.quartet_linear_fwd_block(self.x, self.w, self.t, self.i, self.o, self.block, self.y,
+                                           q.QUARTET_DTYPE_F32, self.xq_codes, self.xq_scales, self.x_mask,
+                                           self.wq_codes, self.wq_scales, self.w_mask))
+
+    def bwd(self, dy_dev, seed, rounding=0):
+        q.check(q.quartet_linear_bwd_block(dy_dev, self.t, self.i, self.o, self.block, self.xq_codes, self.xq_scales,
+                                           self.x_mask, self.wq_codes, self.wq_scales, self.w_mask, seed, rounding,
+                                           self.dx, self.dw, q.QUARTET_DTYPE_F32, self.ws, self.ws_bytes))

@@ -53,6 +53,26 @@ def test_autograd_function_matches_oracle(qnn):
     bf16_close(wt.grad, dw_ref)
 
 
+def test_autograd_function_with_a_wider_hadamard_block_matches_oracle(qnn):
+    x = synth.small_matrix(21, 128, 256, "outliers")
+    w = synth.small_matrix(22, 384, 256, "normal", 0.02)
+    dy = synth.small_matrix(23, 128, 384, "normal", 1e-3)
+    seed, block = 77, 128
+    xt = _bf16_tensor(x).requires_grad_(True)
+    wt = _bf16_tensor(w).requires_grad_(True)
+    y = qnn.QuartetLinearFunction.apply(xt, wt, seed, 0, block)
+    y.backward(_bf16_tensor(dy))
+    y_ref, ctx = oracle.linear_fwd_block(x, w, block)
+    dx_ref, dw_ref = oracle.linear_bwd_block(dy, ctx, block, seed, 0)
+    for got, want in ((y, y_ref), (xt.grad, dx_ref), (wt.grad, dw_ref)):
+        got, want = _to_f32(got), synth.bf16_to_f32(synth.f32_to_bf16(want.astype(np.float32)))
+        err = np.abs(got - want)
+        assert np.all(err <= np.abs(want) * 2.0 ** -7 + 1e-30)      # at most one bf16 step, on few elements
+        assert np.mean(err > 0) < 0.02
+    with pytest.raises(ValueError):
+        qnn.QuartetLinearFunction.apply(xt, wt, seed, 0, 48)
+
+
 def test_leading_dimensions_are_flattened(qnn):
     lin = qnn.QuartetLinear(64, 96, bias=True, seed=3)
     x = torch.randn(2, 16, 64, device="cuda:0").to(torch.bfloat16).requires_grad_(True)
