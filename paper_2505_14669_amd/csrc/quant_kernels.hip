@@ -255,7 +255,7 @@ __device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, cons
 // run at the same time then write neighbouring 128-byte lines of the same output rows (measured 10 %
 // faster than column-tile first, where every block's lines lie a whole output row apart).
 template <int MODE, bool MASK>
-__global__ void __launch_bounds__(256, 4)   // 4 waves per SIMD: at most 128 registers
+__global__ void __launch_bounds__(256, MODE == kBwdSr ? 3 : 4)
 quant_transposed_kernel(const uint16_t* __restrict__ src,
                         uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
                         uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
