@@ -85,3 +85,30 @@ def test_empty_problems_are_accepted_without_a_gpu():
     assert q.quartet_quant_bwd_sr(P, 0, 64, 64, 0, 0, 0, 0, 0, P, P, 0) == 0
     assert q.quartet_mxfp4_gemm(P, P, P, P, 0, 8, 64, 1.0, P, 0, 8, 0) == 0
     assert q.quartet_grad_epilogue(P, None, 0, 64, 1.0, P, 0, 0) == 0
+
+
+def test_block_entry_points_reject_bad_arguments_on_the_host():
+    import oracle
+    from paper_2505_14669_amd import binding as q
+    P = 0x10000
+    E = q.QUARTET_EINVAL
+    sw = [0] * 8
+    for seed in (0, 9, 2 ** 63 + 5):
+        assert q.quartet_sign_words(seed) == [int(w) for w in oracle.sign_words(seed)]
+    assert q.quartet_quant_fwd_block(P, 4, 128, 128, 0, 48, P, P, P, 0) == E          # unsupported block
+    assert q.quartet_quant_fwd_block(P, 4, 96, 96, 0, 64, P, P, P, 0) == E            # k % block
+    assert q.quartet_quant_fwd_block(None, 4, 128, 128, 0, 64, P, P, P, 0) == E
+    assert q.quartet_quant_bwd_sr_block(P, 4, 192, 192, 0, 128, sw, 0, 0, 0, P, P, 0) == E    # k % block
+    assert q.quartet_quant_bwd_sr_block(P, 4, 256, 256, 0, 128, sw, 0, 0, 3, P, P, 0) == E    # rounding
+    assert q.quartet_requant_transpose_sr_block(P, P, 64, 96, 64, sw, 0, 0, 0, P, P, 0) == E  # k % block
+    assert q.quartet_requant_transpose_sr_block(P, P, 48, 128, 64, sw, 0, 0, 0, P, P, 0) == E # rows % 32
+    assert q.quartet_grad_epilogue_block(P, None, 4, 96, 64, 1.0, P, 0, 0) == E
+    assert q.quartet_grad_epilogue_block(P, None, 4, 128, 16, 1.0, P, 0, 0) == E
+    assert q.quartet_linear_fwd_block(P, P, 64, 96, 64, 64, P, 0, P, P, P, P, P, P, 0) == E   # in % block
+    assert q.quartet_linear_workspace_bytes_block(64, 64, 96, 64) == 0                         # out % block
+    assert q.quartet_linear_workspace_bytes_block(64, 64, 64, 32) == q.quartet_linear_workspace_bytes(64, 64, 64)
+    need = q.quartet_linear_workspace_bytes_block(128, 128, 256, 128)
+    assert need > q.quartet_linear_workspace_bytes(128, 128, 256)    # room for the fp32 product
+    assert q.quartet_linear_bwd_block(P, 128, 128, 256, 128, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need - 1, 0) == E
+    assert q.quartet_linear_bwd_block(P, 128, 128, 192, 128, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need, 0) == E
+    assert q.quartet_last_hip_error() == 0
