@@ -2,8 +2,10 @@
 //
 // One lane owns one group of 32 values end to end: the five butterfly stages, the group
 // reduction (sum of squares or absmax), the scale and the 32 codes all stay in that lane's
-// registers, so nothing crosses lanes and the fp32 operation order is fixed.  HBM traffic is
-// made wave-coalesced on both sides by staging through LDS:
+// registers, so nothing crosses lanes and the fp32 operation order is fixed (Hadamard blocks of
+// 64, 128 or 256 elements add the stages that combine whole groups in front: lane exchanges in row
+// mode, a butterfly tree over the block's source-row groups in the transposed kernels).  HBM traffic
+// is made wave-coalesced on both sides by staging through LDS:
 //   row mode        : a wave loads 4 KB (64 groups) with 16-byte lane-contiguous loads, swizzles it
 //                     through LDS so each lane gets its own 64 bytes; codes leave as one 16-byte
 //                     store per lane.
