@@ -227,7 +227,7 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
 // vector-memory counter managed by hand: the compiler cannot tell which LDS reads alias an
 // LDS-direct load in flight, so it would otherwise drain every outstanding load before each
 // fragment read (and before each barrier), which serializes the copy and the matrix-core work.
-template <bool OUT_BF16, bool FUSED>
+template <bool OUT_BF16, bool FUSED, int SCHED>
 __global__ void __launch_bounds__(256)
 gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                        const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
@@ -325,6 +325,13 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
             XB[j] = ((sbuf_[sb_base + j * 64u] >> sh_) & keep_) | (0x7F7Fu & ~keep_);                   \
     }
+// the raw scale dwords of a stage's K-quad
+#define RING_READ_SCALES_RAW(ST, RA, RB)                                                                \
+    {                                                                                                   \
+        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[((ST) % kRing) * STAGE]);        \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) RA[i] = sbuf_[sa_base + i * 64u];           \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) RB[j] = sbuf_[sb_base + j * 64u];           \
+    }
 #define RING_MFMA_ROW(S, FA, FB, I)                                                                     \
     _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                                 \
         acc[I][j] = mfma_fp4<S>(FA[I], FB[j], acc[I][j], sa[I], sb[j]);
@@ -333,6 +340,97 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
     _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[I][j]));
 #define RING_FENCE() __builtin_amdgcn_sched_barrier(0);
 
+    if (SCHED == 2) {
+        // Two stages per trip.  A scale-tile dword holds the four K-steps of a K-quad, i.e. of an even stage
+        // and the odd stage after it: it is read once per pair and each matrix-core instruction picks its
+        // byte (op_sel), so there are no byte moves; the scale tiles travel with even stages only
+        // (17 loads per pair of stages instead of 18).  Otherwise the one-instruction-per-slot order.
+        constexpr uint32_t KEEP2 = 17u;                    // loads of one even and one odd stage stay in flight
+        constexpr uint32_t WAIT2 = 0x0F70u | (KEEP2 & 15u) | ((KEEP2 >> 4) << 14);
+#pragma unroll
+        for (uint32_t s0 = 0; s0 < D; ++s0) {
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; ++j) RING_ISSUE(s0, j)
+            if ((s0 & 1u) == 0u) RING_ISSUE(s0, 8u)
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT2);
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(0u, 0u, fa0, i) RING_FRAG_B(0u, 0u, fb0, i) }
+        const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
+// scale dwords of the K-quad that starts with (even) stage ST; bytes of groups past k/32 become 2^0
+#define RING2_SCALES(ST, XA, XB)                                                                        \
+        {                                                                                               \
+            uint32_t ra_[TM], rb_[TN];                                                                  \
+            RING_READ_SCALES_RAW(ST, ra_, rb_)                                                          \
+            uint32_t keep_ = 0xFFFFFFFFu;                                                               \
+            if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */         \
+                const uint32_t done_ = (ST) * 2u;                                                       \
+                const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
+                keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                            \
+            }                                                                                           \
+            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        }
+        RING2_SCALES(0u, sa, sb)
+#define RING_MF(S, FA, FB, I, J)                                                                        \
+        acc[I][J] = mfma_fp4<S>(FA[I], FB[J], acc[I][J], sa[I], sb[J]);                                 \
+        asm volatile("" : "+a"(acc[I][J]));                                                             \
+        RING_FENCE()
+#define RING2_BODY(PAR, ST)                                                                             \
+        {                                                                                               \
+            const uint32_t st_b = (ST);                                                                 \
+            RING_MF(2 * PAR, fa0, fb0, 0, 0) RING_FRAG_B(st_b, 1u, fb1, 0) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 0, 1) RING_FRAG_B(st_b, 1u, fb1, 1) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 0, 2) RING_FRAG_B(st_b, 1u, fb1, 2) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 0, 3) RING_FRAG_B(st_b, 1u, fb1, 3) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 1, 0) RING_FRAG_A(st_b, 1u, fa1, 0) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 1, 1) RING_FRAG_A(st_b, 1u, fa1, 1) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 1, 2) RING_FRAG_A(st_b, 1u, fa1, 2) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 1, 3) RING_FRAG_A(st_b, 1u, fa1, 3) RING_FENCE()                 \
+            RING_MF(2 * PAR, fa0, fb0, 2, 0) RING_ISSUE(st_b + D, 0u) RING_FENCE()                      \
+            RING_MF(2 * PAR, fa0, fb0, 2, 1)                                                            \
+            RING_MF(2 * PAR, fa0, fb0, 2, 2) RING_ISSUE(st_b + D, 1u) RING_FENCE()                      \
+            RING_MF(2 * PAR, fa0, fb0, 2, 3)                                                            \
+            RING_MF(2 * PAR, fa0, fb0, 3, 0) RING_ISSUE(st_b + D, 2u) RING_FENCE()                      \
+            RING_MF(2 * PAR, fa0, fb0, 3, 1)                                                            \
+            RING_MF(2 * PAR, fa0, fb0, 3, 2) RING_ISSUE(st_b + D, 3u) RING_FENCE()                      \
+            RING_MF(2 * PAR, fa0, fb0, 3, 3)                                                            \
+            RING_MF(2 * PAR + 1, fa1, fb1, 0, 0) RING_ISSUE(st_b + D, 4u) RING_FENCE()                  \
+            RING_MF(2 * PAR + 1, fa1, fb1, 0, 1)                                                        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 0, 2) RING_ISSUE(st_b + D, 5u) RING_FENCE()                  \
+            RING_MF(2 * PAR + 1, fa1, fb1, 0, 3)                                                        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 1, 0) RING_ISSUE(st_b + D, 6u) RING_FENCE()                  \
+            RING_MF(2 * PAR + 1, fa1, fb1, 1, 1)                                                        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 1, 2) RING_ISSUE(st_b + D, 7u) RING_FENCE()                  \
+            RING_MF(2 * PAR + 1, fa1, fb1, 1, 3)                                                        \
+            if (PAR == 1) { RING_ISSUE(st_b + D, 8u) RING_FENCE() }   /* st_b + D is even */            \
+            __builtin_amdgcn_s_waitcnt(WAIT2);                                                          \
+            __builtin_amdgcn_s_barrier();                                                               \
+            RING_FENCE()                                                                                \
+            RING_MF(2 * PAR + 1, fa1, fb1, 2, 0) RING_FRAG_A(st_b + 1u, 0u, fa0, 0) RING_FRAG_B(st_b + 1u, 0u, fb0, 0) RING_FENCE() \
+            RING_MF(2 * PAR + 1, fa1, fb1, 2, 1) RING_FRAG_B(st_b + 1u, 0u, fb0, 1) RING_FRAG_B(st_b + 1u, 0u, fb0, 2) RING_FENCE() \
+            RING_MF(2 * PAR + 1, fa1, fb1, 2, 2) RING_FRAG_B(st_b + 1u, 0u, fb0, 3) RING_FENCE()        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 2, 3) RING_FRAG_A(st_b + 1u, 0u, fa0, 1) RING_FENCE()        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 3, 0) RING_FRAG_A(st_b + 1u, 0u, fa0, 2) RING_FENCE()        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 3, 1) RING_FRAG_A(st_b + 1u, 0u, fa0, 3) RING_FENCE()        \
+            if (PAR == 1) { RING2_SCALES(st_b + 1u, sa_n, sb_n) RING_FENCE() }                          \
+            RING_MF(2 * PAR + 1, fa1, fb1, 3, 2)                                                        \
+            RING_MF(2 * PAR + 1, fa1, fb1, 3, 3)                                                        \
+            if (PAR == 1) {                                                                             \
+                _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                    \
+                _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                    \
+            }                                                                                           \
+        }
+        // an odd number of stages is rounded up: the extra stage is zero-filled (codes of +0) and adds nothing
+        for (uint32_t st = 0; st < stages; st += 2u) {
+            RING2_BODY(0, st)
+            RING2_BODY(1, st + 1u)
+        }
+#undef RING2_BODY
+#undef RING_MF
+#undef RING2_SCALES
+    } else {
     // prologue: always issue D stages, wait for stage 0
 #pragma unroll
     for (uint32_t s0 = 0; s0 < D; ++s0) {
@@ -402,11 +500,13 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
 #pragma unroll
         for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
     }
+    }   // SCHED != 2
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the zero-filled stages issued past the end
 #undef RING_ISSUE
 #undef RING_FRAG_A
 #undef RING_FRAG_B
 #undef RING_READ_SCALES
+#undef RING_READ_SCALES_RAW
 #undef RING_MFMA_ROW
 #undef RING_PIN_ROW
 #undef RING_FENCE
@@ -418,12 +518,12 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
                                         alpha, m0 + wm0, n0 + wn0, m, n, lane);
 }
 
-template <bool OUT_BF16, bool FUSED>
+template <int SCHED, bool OUT_BF16, bool FUSED>
 static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                           const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                           int64_t ldd, const uint32_t* mask, hipStream_t st) {
     uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
-    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
+    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED, SCHED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
                        tiles_m, tiles_n);
 }
@@ -439,8 +539,10 @@ static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, co
                        tiles_m, tiles_n);
 }
 
-// Variants: 0 = 256x256 block, ring of 4 LDS stages (large problems); 1 = 128x128 block, two LDS
-// buffers (problems too small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.
+// Variants: 0 = 256x256 block, ring of 4 LDS stages, two stages per trip with the scale byte picked by
+// op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too small to fill the chip with
+// big tiles); 2 = 256x256 block, two LDS buffers; 3 = the ring with one stage per trip and scale bytes
+// moved into place by vector-ALU instructions (the earlier schedule, kept for comparison: 2-6 % slower).
 // QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
 // fused != 0: D = alpha * H_32_along_n((A B^T) . mask) (mask may be null = all ones), n % 32 == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
@@ -462,7 +564,8 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st);      \
                else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }         \
     } while (0)
-    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, );
+    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, 2, );
+    else if (variant == 3) QUARTET_DISPATCH(launch_ring_t, 0, );
     else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
     else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
 #undef QUARTET_DISPATCH
