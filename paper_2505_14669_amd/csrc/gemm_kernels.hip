@@ -232,7 +232,7 @@ __global__ void __launch_bounds__(256)
 gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                        const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                        uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n) {
+                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
@@ -253,7 +253,7 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
         const uint32_t per = nb >> 3, rem = nb & 7u;
         tile = xcd * per + (xcd < rem ? xcd : rem) + q;
     }
-    constexpr uint32_t GM = 8;
+    const uint32_t GM = band_height;
     const uint32_t band = tile / (GM * tiles_n);
     const uint32_t band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
     const uint32_t in_band = tile - band * GM * tiles_n;
@@ -523,9 +523,16 @@ static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const
                           const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                           int64_t ldd, const uint32_t* mask, hipStream_t st) {
     uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
+    // Height of the bands of tile rows an XCD walks (its 32 CUs then work on gm x 32/gm tiles at a time).  Measured on
+    // the Llama shapes: 4 is never worse than 8 (+0-7 %); with 40 or more tile columns 2 is better still
+    // (16384 x 11008 x 4096: 3.39 against 2.96 PFLOP/s with 8), unless the tile rows do not pair up.
+    // QUARTET_GEMM_BAND overrides (tuning aid).
+    const char* e = getenv("QUARTET_GEMM_BAND");
+    uint32_t gm = (tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
+    if (e && *e && atoi(e) > 0) gm = (uint32_t)atoi(e);
     hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED, SCHED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, gm);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
