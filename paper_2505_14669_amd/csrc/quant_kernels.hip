@@ -316,9 +316,9 @@ quant_transposed_kernel(const uint16_t* __restrict__ src,
 
 // The same tile for Hadamard blocks of NB = 2, 4 or 8 groups.  The groups of a block are whole source
 // row groups, so the group-combining stages come first and work on raw values: for its two groups
-// (places j, j+1 of one block) a wave reads all NB groups of the block for one column of its pair at a
-// time (the other waves of the block read the same lines: the extra reads are cache hits), forms the
-// two outputs of the butterfly tree per source row, and only then runs the 32-point stages.
+// (places j, j+1 of one block) and each column of its pair a wave reads all NB groups of the block (the
+// other waves of the block read the same lines: the extra reads are cache hits), folds them through the
+// butterfly tree down to that place, and only then runs the 32-point stages.
 template <int MODE, bool MASK, int NB>
 __global__ void __launch_bounds__(256)
 quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, uint32_t k, int64_t ldx,
@@ -344,9 +344,19 @@ quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, u
     const uint32_t neg2 = (j & 2u) << 30, neg4 = (j & 4u) << 29;   // sign of the upper operand at the 64- and 128-stages
     const float norm = block_norm((uint32_t)NB);
     const uint32_t sw = lane & 7u;                            // 16-byte slot swizzle against bank conflicts
+    // one output group of one column at a time: 32 results and four source rows of every group in flight keep the
+    // kernel at four waves per SIMD (holding both groups of a column pair took all 512 registers of a lane)
 #pragma unroll 1
-    for (uint32_t c = 0; c < 2; ++c) {
-        float va[32], vb[32];                                 // group gl0 and gl0+1 of column col+c, after the group stages
+    for (uint32_t pass = 0; pass < 4; ++pass) {
+        const uint32_t c = pass & 1u, rb = pass >> 1;
+        const uint32_t neg1 = rb << 31;                       // place j + rb: the 32-stage is a sum (rb = 0) or a difference
+        // The loads do not depend on the pass, so the compiler lifts all 32 NB of them out of this loop and keeps
+        // them in registers: good for NB = 2 and 4 (64 and 128 registers, every line read once), too much for
+        // NB = 8 (all 512 registers of a lane, one wave per SIMD), where an offset it cannot see through keeps
+        // them inside the pass.
+        uint32_t lane_off = 4u * lane;
+        if (NB > 4) asm volatile("" : "+v"(lane_off));
+        float v[32];
 #pragma unroll
         for (uint32_t i = 0; i < 32; ++i) {
             // at most four source rows of every group in flight: without the fence all 32 NB loads are
@@ -355,46 +365,32 @@ quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, u
             float x[NB];
 #pragma unroll
             for (uint32_t jj = 0; jj < (uint32_t)NB; ++jj) {
-                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(res_x, (int)(4u * lane), (int)(((jb + jj) * 32u + i) * pitch), 0);
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(res_x, (int)lane_off, (int)(((jb + jj) * 32u + i) * pitch), 0);
                 uint32_t bits = c ? (w & 0xFFFF0000u) : (w << 16);
                 if (MODE != kFwd) bits ^= ((p.sign_words[jj] >> i) & 1u) << 31;
                 x[jj] = u2f(bits);
             }
-            float sa[NB / 2], sb[NB / 2];                     // 32-stage: sums feed place j, differences place j+1
+            float y[NB / 2];
 #pragma unroll
-            for (uint32_t m = 0; m < (uint32_t)NB / 2u; ++m) {
-                sa[m] = x[2 * m] + x[2 * m + 1];
-                sb[m] = x[2 * m] - x[2 * m + 1];
-            }
+            for (uint32_t m = 0; m < (uint32_t)NB / 2u; ++m) y[m] = x[2 * m] + u2f(f2u(x[2 * m + 1]) ^ neg1);
             if (NB >= 4) {
 #pragma unroll
-                for (uint32_t m = 0; m < (uint32_t)NB / 4u; ++m) {
-                    sa[m] = sa[2 * m] + u2f(f2u(sa[2 * m + 1]) ^ neg2);
-                    sb[m] = sb[2 * m] + u2f(f2u(sb[2 * m + 1]) ^ neg2);
-                }
+                for (uint32_t m = 0; m < (uint32_t)NB / 4u; ++m) y[m] = y[2 * m] + u2f(f2u(y[2 * m + 1]) ^ neg2);
             }
-            if (NB >= 8) {
-                sa[0] = sa[0] + u2f(f2u(sa[1]) ^ neg4);
-                sb[0] = sb[0] + u2f(f2u(sb[1]) ^ neg4);
-            }
-            va[i] = sa[0];
-            vb[i] = sb[0];
+            if (NB >= 8) y[0] = y[0] + u2f(f2u(y[1]) ^ neg4);
+            v[i] = y[0];
         }
+        fwht32_unscaled(v);
 #pragma unroll
-        for (uint32_t rb = 0; rb < 2; ++rb) {
-            float (&v)[32] = rb ? vb : va;
-            fwht32_unscaled(v);
-#pragma unroll
-            for (int i = 0; i < 32; ++i) v[i] = v[i] * norm;
-            const uint32_t gl = gl0 + rb;
-            uint4 q;
-            uint32_t sbyte, m;
-            encode_group<MODE>(v, p, ((uint64_t)(col + c) * k + (grp0 + gl) * 32u) >> 4, q, sbyte, m);
-            const uint32_t lc = 2u * lane + c;
-            s_codes[lc * 8u + (gl ^ sw)] = q;
-            s_scales[lc * 8u + gl] = (uint8_t)sbyte;
-            if (MASK) s_mask[lc * 8u + gl] = m;
-        }
+        for (int i = 0; i < 32; ++i) v[i] = v[i] * norm;
+        const uint32_t gl = gl0 + rb;
+        uint4 q;
+        uint32_t sbyte, m;
+        encode_group<MODE>(v, p, ((uint64_t)(col + c) * k + (grp0 + gl) * 32u) >> 4, q, sbyte, m);
+        const uint32_t lc = 2u * lane + c;
+        s_codes[lc * 8u + (gl ^ sw)] = q;
+        s_scales[lc * 8u + gl] = (uint8_t)sbyte;
+        if (MASK) s_mask[lc * 8u + gl] = m;
     }
     __syncthreads();
     transposed_store_tile<MASK>(s_codes, s_scales, s_mask, col0, grp0, rows, gk, k, codes, scales, mask);
@@ -585,6 +581,9 @@ requant_transposed_block_kernel(const uint8_t* __restrict__ src_codes, const uin
             cw[jj] = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, (int)((jb + jj) * code_step), 0);
             const uint32_t sbyte = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, (int)((jb + jj) * scale_step), 0);
             sc[jj] = u2f(sbyte << 23);
+            // the loads of a whole block may stay in registers across the steps that share it, the decoded values may
+            // not (NB x 32 floats): a scale the compiler cannot see through keeps the decoding inside the step
+            asm volatile("" : "+v"(sc[jj]));
             flip[jj] = ((p.sign_words[jj] >> rl) & 1u) << 31;   // element rl of block group jj
         }
         float f[32];
