@@ -221,13 +221,13 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
 // 128 elements (64 code bytes per row) at a time through a ring of kRing LDS stages that is filled
 // kRing-1 stages ahead, so roughly 100 KB per CU are in flight and no wait ever falls on loads that
 // were just issued.  A stage is [A codes 16 KB][B codes 16 KB][16 scale tiles 4 KB], all written by
-// LDS-direct loads (9 per wave per stage).
+// LDS-direct loads (8 per wave per stage, and one more for the scale tiles with every even stage).
 //
 // The LDS-direct loads are issued from inline assembly and the barrier is a bare s_barrier, with the
 // vector-memory counter managed by hand: the compiler cannot tell which LDS reads alias an
 // LDS-direct load in flight, so it would otherwise drain every outstanding load before each
 // fragment read (and before each barrier), which serializes the copy and the matrix-core work.
-template <bool OUT_BF16, bool FUSED, int SCHED>
+template <bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
 gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                        const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
@@ -237,10 +237,6 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
     constexpr uint32_t D = kRing - 1;                    // prefetch distance in stages
-    constexpr uint32_t LOADS = 9;                        // vector-memory operations per wave per stage
-    // s_waitcnt: wait until at most (D-1)*LOADS vector-memory operations are outstanding
-    constexpr uint32_t KEEP = (D - 1) * LOADS;
-    constexpr uint32_t WAIT_STAGE = 0x0F70u | (KEEP & 15u) | ((KEEP >> 4) << 14);
     __shared__ uint4 lds[kRing * STAGE];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -311,20 +307,6 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
     }
 #define RING_FRAG_A(ST, S, FA, I) FA[I] = lds[((ST) % kRing) * STAGE + fa_base + (I) * 128u + ((2u * (S) + lhalf) ^ swz)];
 #define RING_FRAG_B(ST, S, FB, J) FB[J] = lds[((ST) % kRing) * STAGE + fb_base + (J) * 128u + ((2u * (S) + lhalf) ^ swz)];
-// scale dwords of the stage's K-quad, moved so that this stage's two K-steps are bytes 0 and 1
-#define RING_READ_SCALES(ST, XA, XB)                                                                    \
-    {                                                                                                   \
-        const uint32_t st_ = (ST);                                                                      \
-        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(st_ % kRing) * STAGE]);         \
-        const uint32_t sh_ = (st_ & 1u) * 16u;                                                          \
-        uint32_t keep_ = 0u;    /* ragged K: neutralize the scale bytes of groups past k/32 */          \
-        if (st_ * 4u + lhalf < gk) keep_ |= 0xFFu;                                                      \
-        if (st_ * 4u + 2u + lhalf < gk) keep_ |= 0xFF00u;                                               \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                             \
-            XA[i] = ((sbuf_[sa_base + i * 64u] >> sh_) & keep_) | (0x7F7Fu & ~keep_);                   \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
-            XB[j] = ((sbuf_[sb_base + j * 64u] >> sh_) & keep_) | (0x7F7Fu & ~keep_);                   \
-    }
 // the raw scale dwords of a stage's K-quad
 #define RING_READ_SCALES_RAW(ST, RA, RB)                                                                \
     {                                                                                                   \
@@ -332,15 +314,9 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
         _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) RA[i] = sbuf_[sa_base + i * 64u];           \
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) RB[j] = sbuf_[sb_base + j * 64u];           \
     }
-#define RING_MFMA_ROW(S, FA, FB, I)                                                                     \
-    _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                                 \
-        acc[I][j] = mfma_fp4<S>(FA[I], FB[j], acc[I][j], sa[I], sb[j]);
-// zero-instruction pin: row I of the accumulators holds every result issued so far
-#define RING_PIN_ROW(I)                                                                                 \
-    _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[I][j]));
 #define RING_FENCE() __builtin_amdgcn_sched_barrier(0);
 
-    if (SCHED == 2) {
+    {
         // Two stages per trip.  A scale-tile dword holds the four K-steps of a K-quad, i.e. of an even stage
         // and the odd stage after it: it is read once per pair and each matrix-core instruction picks its
         // byte (op_sel), so there are no byte moves; the scale tiles travel with even stages only
@@ -430,85 +406,12 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
 #undef RING2_BODY
 #undef RING_MF
 #undef RING2_SCALES
-    } else {
-    // prologue: always issue D stages, wait for stage 0
-#pragma unroll
-    for (uint32_t s0 = 0; s0 < D; ++s0) {
-#pragma unroll
-        for (uint32_t j = 0; j < LOADS; ++j) RING_ISSUE(s0, j)
     }
-    __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
-    __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(0u, 0u, fa0, i) RING_FRAG_B(0u, 0u, fb0, i) }
-    RING_READ_SCALES(0u, sa, sb)
-
-    for (uint32_t st = 0; st < stages; ++st) {
-        // K-step 0 on fragment set 0; fragment set 1 is read and 4 loads of stage st+D are issued meanwhile
-#define RING_K0_ROW(I)                                                                                  \
-        RING_FENCE()                                                                                    \
-        RING_ISSUE(st + D, I)                                                                           \
-        RING_FENCE()                                                                                    \
-        if ((I) < 2) { RING_FRAG_B(st, 1u, fb1, 2 * (I)) RING_FRAG_B(st, 1u, fb1, 2 * (I) + 1) }        \
-        else { RING_FRAG_A(st, 1u, fa1, 2 * (I) - 4) RING_FRAG_A(st, 1u, fa1, 2 * (I) - 3) }            \
-        RING_MFMA_ROW(0, fa0, fb0, I)                                                                   \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                              \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                              \
-        RING_PIN_ROW(I)
-        RING_K0_ROW(0)
-        RING_K0_ROW(1)
-        RING_K0_ROW(2)
-        RING_K0_ROW(3)
-#undef RING_K0_ROW
-        // first half of K-step 1 with the remaining 5 loads
-        RING_FENCE()
-        RING_ISSUE(st + D, 4u)
-        RING_ISSUE(st + D, 5u)
-        RING_FENCE()
-        RING_MFMA_ROW(1, fa1, fb1, 0)
-        RING_PIN_ROW(0)
-        RING_FENCE()
-        RING_ISSUE(st + D, 6u)
-        RING_ISSUE(st + D, 7u)
-        RING_ISSUE(st + D, 8u)
-        RING_FENCE()
-        RING_MFMA_ROW(1, fa1, fb1, 1)
-        RING_PIN_ROW(1)
-        RING_FENCE()
-        // stage st+1 has landed in LDS (stages st+2 .. st+D stay in flight)
-        __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
-        __builtin_amdgcn_s_barrier();
-        RING_FENCE()
-        // second half of K-step 1 over the LDS latency of the next stage's first fragments
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(st + 1u, 0u, fa0, i) RING_FRAG_B(st + 1u, 0u, fb0, i) }
-        RING_READ_SCALES(st + 1u, sa_n, sb_n)
-        RING_MFMA_ROW(1, fa1, fb1, 2)
-        RING_MFMA_ROW(1, fa1, fb1, 3)
-#pragma unroll
-        for (uint32_t g_ = 0; g_ < 8; ++g_) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        }
-        RING_PIN_ROW(2)
-        RING_PIN_ROW(3)
-        RING_FENCE()
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];
-#pragma unroll
-        for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
-    }
-    }   // SCHED != 2
     __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the zero-filled stages issued past the end
 #undef RING_ISSUE
 #undef RING_FRAG_A
 #undef RING_FRAG_B
-#undef RING_READ_SCALES
 #undef RING_READ_SCALES_RAW
-#undef RING_MFMA_ROW
-#undef RING_PIN_ROW
 #undef RING_FENCE
 
     // every wave is done reading the ring (and the zero-filled stages have landed): reuse it as the
@@ -518,7 +421,7 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
                                         alpha, m0 + wm0, n0 + wn0, m, n, lane);
 }
 
-template <int SCHED, bool OUT_BF16, bool FUSED>
+template <bool OUT_BF16, bool FUSED>
 static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                           const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                           int64_t ldd, const uint32_t* mask, hipStream_t st) {
@@ -530,7 +433,7 @@ static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const
     const char* e = getenv("QUARTET_GEMM_BAND");
     uint32_t gm = (tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
     if (e && *e && atoi(e) > 0) gm = (uint32_t)atoi(e);
-    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED, SCHED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
+    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
                        tiles_m, tiles_n, gm);
 }
@@ -548,8 +451,7 @@ static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, co
 
 // Variants: 0 = 256x256 block, ring of 4 LDS stages, two stages per trip with the scale byte picked by
 // op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too small to fill the chip with
-// big tiles); 2 = 256x256 block, two LDS buffers; 3 = the ring with one stage per trip and scale bytes
-// moved into place by vector-ALU instructions (the earlier schedule, kept for comparison: 2-6 % slower).
+// big tiles); 2 = 256x256 block, two LDS buffers.
 // QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
 // fused != 0: D = alpha * H_32_along_n((A B^T) . mask) (mask may be null = all ones), n % 32 == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
@@ -571,8 +473,7 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st);      \
                else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }         \
     } while (0)
-    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, 2, );
-    else if (variant == 3) QUARTET_DISPATCH(launch_ring_t, 0, );
+    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, );
     else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
     else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
 #undef QUARTET_DISPATCH

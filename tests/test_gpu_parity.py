@@ -166,7 +166,7 @@ def test_gemm_exhaustive_code_pairs_bit_exact(G):
     assert np.array_equal(got.astype(np.float64), oracle.mxfp4_gemm(ac, one_a, bc, one_b))
 
 
-@pytest.fixture(params=["auto", "0", "1", "2", "3"])
+@pytest.fixture(params=["auto", "0", "1", "2"])
 def gemm_variant(request, monkeypatch):
     # every tile shape of the GEMM kernel is checked, not only the one the size heuristic picks
     if request.param == "auto":
