@@ -251,9 +251,10 @@ uint32_t quartet_sign_word(uint64_t seed);
  * seed's key, words 4..7 those at counter (1,0,0,0xFFFFFFFF); word 0 = quartet_sign_word(seed).
  * sign_words arguments are HOST pointers to at least hadamard_block/32 words.
  *
- * The gradient GEMM with the epilogue inside (quartet_mxfp4_gemm_grad) exists for blocks of 32 only;
- * quartet_linear_bwd_block runs the plain GEMM into its workspace and quartet_grad_epilogue_block
- * after it when hadamard_block > 32 (quartet_linear_workspace_bytes_block accounts for that).
+ * quartet_mxfp4_gemm_grad_block is quartet_mxfp4_gemm_grad for blocks of 32, 64 or 128 columns (n a
+ * multiple of the block); a block of 256 spans the tiles of two waves and returns QUARTET_ENOTSUP:
+ * quartet_linear_bwd_block then runs the plain GEMM into its workspace and quartet_grad_epilogue_block
+ * after it (quartet_linear_workspace_bytes_block accounts for that).
  */
 int quartet_sign_words(uint64_t seed, uint32_t *out8);
 int quartet_quant_fwd_block(const void *x_bf16, int64_t rows, int64_t k, int64_t ldx, int transpose,
@@ -265,6 +266,10 @@ int quartet_requant_transpose_sr_block(const uint8_t *src_codes, const uint8_t *
                                        int64_t rows, int64_t k, int hadamard_block,
                                        const uint32_t *sign_words, uint64_t seed, uint32_t stream_id,
                                        int rounding, uint8_t *codes, uint8_t *scales, void *stream);
+int quartet_mxfp4_gemm_grad_block(const uint8_t *a_codes, const uint8_t *a_scales,
+                                  const uint8_t *b_codes, const uint8_t *b_scales,
+                                  int64_t m, int64_t n, int64_t k, int hadamard_block, const uint32_t *mask,
+                                  float scale, void *d, int d_dtype, int64_t ldd, void *stream);
 int quartet_grad_epilogue_block(const float *g, const uint32_t *mask, int64_t m, int64_t n, int hadamard_block,
                                 float scale, void *out, int out_dtype, void *stream);
 int quartet_linear_fwd_block(const void *x_bf16, const void *w_bf16, int64_t tokens, int64_t in, int64_t out,

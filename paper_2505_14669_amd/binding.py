@@ -28,7 +28,7 @@ EXPORTS = [
     "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
     "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
-    "quartet_requant_transpose_sr_block", "quartet_grad_epilogue_block", "quartet_linear_fwd_block",
+    "quartet_requant_transpose_sr_block", "quartet_mxfp4_gemm_grad_block", "quartet_grad_epilogue_block", "quartet_linear_fwd_block",
     "quartet_linear_workspace_bytes_block", "quartet_linear_bwd_block",
 ]
 
@@ -67,6 +67,7 @@ _lib.quartet_sign_words.argtypes = [_u64, _p]
 _lib.quartet_quant_fwd_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p]
 _lib.quartet_quant_bwd_sr_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _u64, _u32, _int, _p, _p, _p]
 _lib.quartet_requant_transpose_sr_block.argtypes = [_p, _p, _i64, _i64, _int, _p, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_mxfp4_gemm_grad_block.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _int, _p, _f, _p, _int, _i64, _p]
 _lib.quartet_grad_epilogue_block.argtypes = [_p, _p, _i64, _i64, _int, _f, _p, _int, _p]
 _lib.quartet_linear_fwd_block.argtypes = [_p, _p, _i64, _i64, _i64, _int, _p, _int, _p, _p, _p, _p, _p, _p, _p]
 _lib.quartet_linear_workspace_bytes_block.restype = ctypes.c_size_t
@@ -243,6 +244,12 @@ def quartet_requant_transpose_sr_block(src_codes, src_scales, rows, k, hadamard_
     return _lib.quartet_requant_transpose_sr_block(_ptr(src_codes), _ptr(src_scales), rows, k, hadamard_block,
                                                    ctypes.cast(sw, _p), seed, stream_id, rounding, _ptr(codes),
                                                    _ptr(scales), _stream(stream))
+
+
+def quartet_mxfp4_gemm_grad_block(a_codes, a_scales, b_codes, b_scales, m, n, k, hadamard_block, mask, scale, d, d_dtype,
+                                  ldd, stream=None):
+    return _lib.quartet_mxfp4_gemm_grad_block(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
+                                              hadamard_block, _ptr(mask), scale, _ptr(d), d_dtype, ldd, _stream(stream))
 
 
 def quartet_grad_epilogue_block(g, mask, m, n, hadamard_block, scale, out, out_dtype, stream=None):

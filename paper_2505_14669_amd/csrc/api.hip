@@ -295,7 +295,7 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     if (rc) return rc;
     ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
     hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d,
-                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 0, nullptr, (hipStream_t)stream);
+                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 0, nullptr, 1u, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
@@ -303,13 +303,24 @@ int quartet_mxfp4_gemm_grad(const uint8_t* a_codes, const uint8_t* a_scales,
                             const uint8_t* b_codes, const uint8_t* b_scales,
                             int64_t m, int64_t n, int64_t k, const uint32_t* mask, float scale,
                             void* d, int d_dtype, int64_t ldd, void* stream) {
+    return quartet_mxfp4_gemm_grad_block(a_codes, a_scales, b_codes, b_scales, m, n, k, 32, mask, scale, d, d_dtype, ldd,
+                                         stream);
+}
+
+int quartet_mxfp4_gemm_grad_block(const uint8_t* a_codes, const uint8_t* a_scales,
+                                  const uint8_t* b_codes, const uint8_t* b_scales,
+                                  int64_t m, int64_t n, int64_t k, int hadamard_block, const uint32_t* mask,
+                                  float scale, void* d, int d_dtype, int64_t ldd, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u) return QUARTET_EINVAL;
+    if (nb > 4u) return QUARTET_ENOTSUP;     // a block of 256 columns spans two waves' tiles: plain GEMM + quartet_grad_epilogue_block
     int rc = check_gemm_args(a_codes, a_scales, b_codes, b_scales, m, n, k, d, d_dtype, ldd);
     if (rc) return rc;
-    if ((n % 32) != 0) return QUARTET_EINVAL;
+    if ((n % hadamard_block) != 0) return QUARTET_EINVAL;
     if (mask && (reinterpret_cast<uintptr_t>(mask) & 3u)) return QUARTET_EINVAL;
     ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
     hipError_t e = quartet::launch_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, scale, d,
-                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 1, mask, (hipStream_t)stream);
+                                        d_dtype == QUARTET_DTYPE_BF16, ldd, 1, mask, nb, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
@@ -401,7 +412,7 @@ size_t quartet_linear_workspace_bytes_block(int64_t tokens, int64_t in, int64_t 
     if (block_groups(hadamard_block) == 0u) return 0;
     if (tokens < 0 || in < 0 || out < 0) return 0;
     if ((tokens % hadamard_block) != 0 || (in % hadamard_block) != 0 || (out % hadamard_block) != 0) return 0;
-    return plan_bwd(tokens, in, out, hadamard_block > 32).total;
+    return plan_bwd(tokens, in, out, hadamard_block > 128).total;
 }
 
 int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
@@ -428,7 +439,7 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
     if ((tokens % hb) != 0 || (in % hb) != 0 || (out % hb) != 0) return QUARTET_EINVAL;
     if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
     if (grad_dtype != QUARTET_DTYPE_F32 && grad_dtype != QUARTET_DTYPE_BF16) return QUARTET_EINVAL;
-    const bool big = hb > 32;
+    const bool big = hb > 128;     // the GEMM applies the gradient epilogue itself for blocks up to 128
     const BwdWorkspace w = plan_bwd(tokens, in, out, big);
     if (w.total > 0 && (!workspace || workspace_bytes < w.total)) return QUARTET_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUARTET_EINVAL;
@@ -446,9 +457,9 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
     rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
     if (!big) {
-        rc = quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, tokens, in, out, x_mask, c169, dx, grad_dtype, in, stream);
+        rc = quartet_mxfp4_gemm_grad_block(g_codes, g_scales, b_codes, b_scales, tokens, in, out, hb, x_mask, c169, dx, grad_dtype, in, stream);
     } else {
-        // blocks above 32 span more columns than the GEMM's in-kernel epilogue handles: fp32 product, then the epilogue kernel
+        // a block of 256 columns spans two waves' tiles: fp32 product, then the epilogue kernel
         rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
         if (rc) return rc;
         rc = quartet_grad_epilogue_block(acc, x_mask, tokens, in, hb, c169, dx, grad_dtype, stream);
@@ -460,7 +471,7 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
     rc = quartet_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, b_codes, b_scales, stream);
     if (rc) return rc;
     if (!big)
-        return quartet_mxfp4_gemm_grad(g_codes, g_scales, b_codes, b_scales, out, in, tokens, w_mask, c169, dw, grad_dtype, in, stream);
+        return quartet_mxfp4_gemm_grad_block(g_codes, g_scales, b_codes, b_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
     rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
     if (rc) return rc;
     return quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);

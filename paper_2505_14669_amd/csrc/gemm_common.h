@@ -123,12 +123,140 @@ __device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf
     }
 }
 
+// The same epilogue walking the tile by blocks of 32 rows instead of slices of 32 columns: a pass takes one row
+// block of all TN accumulators through LDS (32 rows x TN*32 columns), so a lane holds the same 4-column chunk of
+// all TN slices of a row at once.  That is what Hadamard blocks of nb = 2 or 4 groups (64 or 128 columns) need: the
+// stages that combine whole groups (stride 32, 64) are then additions inside the lane, done first, before the
+// 32-point stages of each slice, and the normalization is fl(1/sqrt(32 nb)).  nb = 1 gives the same bits as
+// store_tile_body (measured equally fast; the column-slice form stays the default).
+template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
+__device__ __forceinline__ void store_tile_body_rows(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
+                                                     const uint32_t* mask, float alpha, uint32_t row_base,
+                                                     uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane,
+                                                     uint32_t nb) {
+    constexpr uint32_t STRIDE = TN * 32u + 4u;   // floats per LDS row: 16-byte aligned, rows shifted by 4 banks
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
+    const uint32_t up4 = (c & 1u) << 31, up8 = (c & 2u) << 30, up16 = (c & 4u) << 29;
+    const bool wide = FULL || (ldd & 3u) == 0u;
+    const uint32_t mask_ld = n >> 5;
+#pragma unroll
+    for (uint32_t i = 0; i < TM; ++i) {
+        uint32_t mw[4][TN];
+        if (FUSED) {
+#pragma unroll
+            for (uint32_t it = 0; it < 4; ++it)
+#pragma unroll
+                for (uint32_t j = 0; j < TN; ++j) {
+                    const uint32_t grow = row_base + i * 32u + it * 8u + sub, gcol = col_base + j * 32u;
+                    if (FULL) mw[it][j] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
+                    else mw[it][j] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
+                }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j)
+#pragma unroll
+            for (uint32_t r = 0; r < 16; ++r)
+                wbuf[((r >> 2) * 8u + lhalf * 4u + (r & 3u)) * STRIDE + j * 32u + lrow] = acc[i][j][r];
+        float4 sl[4][TN];
+#pragma unroll
+        for (uint32_t it = 0; it < 4; ++it)
+#pragma unroll
+            for (uint32_t j = 0; j < TN; ++j)
+                sl[it][j] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * STRIDE + j * 32u + 4u * c]);
+        const float norm = block_norm(nb);
+#pragma unroll
+        for (uint32_t it = 0; it < 4; ++it) {
+            const uint32_t grow = row_base + i * 32u + it * 8u + sub;
+            float vv[TN][4];
+#pragma unroll
+            for (uint32_t j = 0; j < TN; ++j) {
+                vv[j][0] = sl[it][j].x; vv[j][1] = sl[it][j].y; vv[j][2] = sl[it][j].z; vv[j][3] = sl[it][j].w;
+                if (FUSED) {
+                    // bit clear -> +0: and with the bit spread over the word
+                    const int32_t bits = (int32_t)(mw[it][j] >> (4u * c));
+#pragma unroll
+                    for (uint32_t e = 0; e < 4; ++e)
+                        vv[j][e] = __uint_as_float(__float_as_uint(vv[j][e]) & (uint32_t)((bits << (31 - (int)e)) >> 31));
+                }
+            }
+            if (FUSED && nb >= 2u) {          // stride 32: slices (0,1), (2,3)
+#pragma unroll
+                for (uint32_t j = 0; j + 1u < TN; j += 2)
+#pragma unroll
+                    for (uint32_t e = 0; e < 4; ++e) {
+                        const float a = vv[j][e], b = vv[j + 1][e];
+                        vv[j][e] = a + b;
+                        vv[j + 1][e] = a - b;
+                    }
+            }
+            if (FUSED && nb >= 4u && TN >= 4) {   // stride 64: slices (0,2), (1,3)
+#pragma unroll
+                for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+                    for (uint32_t e = 0; e < 4; ++e) {
+                        const float a = vv[j][e], b = vv[(j + 2u) % TN][e];
+                        vv[j][e] = a + b;
+                        vv[(j + 2u) % TN][e] = a - b;
+                    }
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < TN; ++j) {
+                const uint32_t gcol = col_base + j * 32u;
+                float v0 = vv[j][0], v1 = vv[j][1], v2 = vv[j][2], v3 = vv[j][3];
+                if (FUSED) {
+                    const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
+                    v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
+                    v0 = butterfly_across<kDppXor1>(v0, up4); v1 = butterfly_across<kDppXor1>(v1, up4);   // stride 4
+                    v2 = butterfly_across<kDppXor1>(v2, up4); v3 = butterfly_across<kDppXor1>(v3, up4);
+                    v0 = butterfly_across<kDppXor2>(v0, up8); v1 = butterfly_across<kDppXor2>(v1, up8);   // stride 8
+                    v2 = butterfly_across<kDppXor2>(v2, up8); v3 = butterfly_across<kDppXor2>(v3, up8);
+                    v0 = butterfly_across<kDppHalfMirror>(v0, up16); v1 = butterfly_across<kDppHalfMirror>(v1, up16);   // stride 16
+                    v2 = butterfly_across<kDppHalfMirror>(v2, up16); v3 = butterfly_across<kDppHalfMirror>(v3, up16);
+                    v0 = v0 * norm; v1 = v1 * norm; v2 = v2 * norm; v3 = v3 * norm;
+                }
+                v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
+                if (!FULL && grow >= m) continue;
+                const uint32_t col = gcol + 4u * c;
+                const size_t at = (size_t)grow * ldd + col;
+                if (OUT_BF16) {
+                    uint16_t* dst = static_cast<uint16_t*>(d) + at;
+                    const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
+                    if (FULL || (wide && col + 4u <= n)) {
+                        *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                    } else {
+                        if (col < n) dst[0] = (uint16_t)h0;
+                        if (col + 1u < n) dst[1] = (uint16_t)h1;
+                        if (col + 2u < n) dst[2] = (uint16_t)h2;
+                        if (col + 3u < n) dst[3] = (uint16_t)h3;
+                    }
+                } else {
+                    float* dst = static_cast<float*>(d) + at;
+                    if (FULL || (wide && col + 4u <= n)) {
+                        *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                    } else {
+                        if (col < n) dst[0] = v0;
+                        if (col + 1u < n) dst[1] = v1;
+                        if (col + 2u < n) dst[2] = v2;
+                        if (col + 3u < n) dst[3] = v3;
+                    }
+                }
+            }
+        }
+    }
+}
+
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
 __device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
                                            const uint32_t* mask, float alpha, uint32_t row_base,
-                                           uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+                                           uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane, uint32_t nb = 1u) {
     const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n &&
                       (!FUSED || mask != nullptr);   // wave-uniform
+    if (FUSED && nb > 1u) {     // Hadamard blocks of 64 or 128 columns: the row-block form
+        if (full) store_tile_body_rows<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_body_rows<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        return;
+    }
     if (full) store_tile_body<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
     else store_tile_body<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
 }

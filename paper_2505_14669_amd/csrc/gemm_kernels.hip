@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(256)
 gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                   const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                   uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                  const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n) {
+                  const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t nb) {
     constexpr uint32_t BM = 2 * TM * 32, BN = 2 * TN * 32;
     constexpr uint32_t LA = BM / 32, LB = BN / 32;      // 1 KB (64 lanes x 16 B) loads per wave per stage
     constexpr uint32_t STAGE = (BM + BN) * 8;           // 16-byte chunks per LDS buffer
@@ -213,7 +213,7 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
     // every wave is done reading the stage buffers: reuse them as the epilogue's scratch
     __syncthreads();
     store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
-                                        alpha, m0 + wm0, n0 + wn0, m, n, lane);
+                                        alpha, m0 + wm0, n0 + wn0, m, n, lane, nb);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -232,7 +232,7 @@ __global__ void __launch_bounds__(256)
 gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                        const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                        uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height) {
+                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
@@ -418,13 +418,13 @@ gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
     // epilogue's scratch
     __builtin_amdgcn_s_barrier();
     store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
-                                        alpha, m0 + wm0, n0 + wn0, m, n, lane);
+                                        alpha, m0 + wm0, n0 + wn0, m, n, lane, nb);
 }
 
 template <bool OUT_BF16, bool FUSED>
 static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                           const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                          int64_t ldd, const uint32_t* mask, hipStream_t st) {
+                          int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
     // Height of the bands of tile rows an XCD walks (its 32 CUs then work on gm x 32/gm tiles at a time).  Measured on
     // the Llama shapes: 4 is never worse than 8 (+0-7 %); with 40 or more tile columns 2 is better still
@@ -435,28 +435,29 @@ static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const
     if (e && *e && atoi(e) > 0) gm = (uint32_t)atoi(e);
     hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, gm);
+                       tiles_m, tiles_n, gm, nb);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
 static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                              const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                             int64_t ldd, const uint32_t* mask, hipStream_t st) {
+                             int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
     hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, nb);
 }
 
 // Variants: 0 = 256x256 block, ring of 4 LDS stages, two stages per trip with the scale byte picked by
 // op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too small to fill the chip with
 // big tiles); 2 = 256x256 block, two LDS buffers.
 // QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
-// fused != 0: D = alpha * H_32_along_n((A B^T) . mask) (mask may be null = all ones), n % 32 == 0.
+// fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
+// be null = all ones), n % (32 nb) == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                       int d_bf16, int64_t ldd, int fused, const uint32_t* mask, hipStream_t st) {
+                       int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     if (m == 0 || n == 0) return hipSuccess;
     const char* env = getenv("QUARTET_GEMM_VARIANT");
     int variant = (env && *env) ? atoi(env) : -1;
@@ -466,12 +467,13 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         // 176 (5632 x 2048 x 8192) are 1.75 x faster as 256 x 256 tiles even though they leave 80 CUs idle
         variant = big_tiles >= 160 ? 0 : 1;
     }
+    if (fused && nb >= 4u && variant == 1) variant = 2;   // a block of 128 columns needs the 128-column wave tile
 #define QUARTET_DISPATCH(FN, ...)                                                                     \
     do {                                                                                              \
-        if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); \
-                      else FN<__VA_ARGS__ true, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }   \
-        else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st);      \
-               else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, st); }         \
+        if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); \
+                      else FN<__VA_ARGS__ true, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); }   \
+        else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st);      \
+               else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); }         \
     } while (0)
     if (variant == 0) QUARTET_DISPATCH(launch_ring_t, );
     else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );

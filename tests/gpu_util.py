@@ -184,6 +184,17 @@ def requant_transpose_sr_block(src_codes, src_scales, block, sign_words, seed, s
     return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
 
 
+def gemm_grad_block(a_codes, a_scales, b_codes, b_scales, block, mask, scale, bf16=False):
+    m, k = a_codes.shape[0], a_codes.shape[1] * 2
+    n = b_codes.shape[0]
+    d = dev_empty((m, n), np.uint16, 0x7FC0) if bf16 else dev_empty((m, n), np.float32, float("nan"))
+    q.check(q.quartet_mxfp4_gemm_grad_block(to_dev(a_codes), to_dev(scales_to_tiled(a_scales)), to_dev(b_codes),
+                                            to_dev(scales_to_tiled(b_scales)), m, n, k, block,
+                                            None if mask is None else to_dev(mask), scale, d,
+                                            q.QUARTET_DTYPE_BF16 if bf16 else q.QUARTET_DTYPE_F32, n))
+    return to_host(d, np.uint16 if bf16 else np.float32)
+
+
 def grad_epilogue_block(g, mask, block, scale, bf16=False):
     m, n = g.shape
     gd = to_dev(g)

@@ -107,8 +107,12 @@ def test_block_entry_points_reject_bad_arguments_on_the_host():
     assert q.quartet_linear_fwd_block(P, P, 64, 96, 64, 64, P, 0, P, P, P, P, P, P, 0) == E   # in % block
     assert q.quartet_linear_workspace_bytes_block(64, 64, 96, 64) == 0                         # out % block
     assert q.quartet_linear_workspace_bytes_block(64, 64, 64, 32) == q.quartet_linear_workspace_bytes(64, 64, 64)
-    need = q.quartet_linear_workspace_bytes_block(128, 128, 256, 128)
-    assert need > q.quartet_linear_workspace_bytes(128, 128, 256)    # room for the fp32 product
-    assert q.quartet_linear_bwd_block(P, 128, 128, 256, 128, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need - 1, 0) == E
+    assert q.quartet_linear_workspace_bytes_block(128, 128, 256, 128) == q.quartet_linear_workspace_bytes(128, 128, 256)
+    need = q.quartet_linear_workspace_bytes_block(256, 256, 512, 256)
+    assert need > q.quartet_linear_workspace_bytes(256, 256, 512)    # blocks of 256: room for the fp32 product
+    assert q.quartet_linear_bwd_block(P, 256, 256, 512, 256, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need - 1, 0) == E
     assert q.quartet_linear_bwd_block(P, 128, 128, 192, 128, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need, 0) == E
+    assert q.quartet_mxfp4_gemm_grad_block(P, P, P, P, 4, 128, 64, 256, None, 1.0, P, 0, 128, 0) == q.QUARTET_ENOTSUP
+    assert q.quartet_mxfp4_gemm_grad_block(P, P, P, P, 4, 96, 64, 64, None, 1.0, P, 0, 96, 0) == E      # n % block
+    assert q.quartet_mxfp4_gemm_grad_block(P, P, P, P, 4, 128, 64, 48, None, 1.0, P, 0, 128, 0) == E    # unsupported block
     assert q.quartet_last_hip_error() == 0

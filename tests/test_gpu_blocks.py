@@ -105,6 +105,42 @@ def test_grad_epilogue_block(G, block):
         assert np.array_equal(got_nm.view(np.uint32), oracle.grad_epilogue_block(g, None, block, 1.0).view(np.uint32))
 
 
+@pytest.fixture(params=["auto", "0", "1", "2"])
+def gemm_variant(request, monkeypatch):
+    # every tile shape of the GEMM kernel; a block of 128 columns does not fit the 64-column wave tile of variant 1,
+    # the library switches to variant 2 by itself
+    if request.param == "auto":
+        monkeypatch.delenv("QUARTET_GEMM_VARIANT", raising=False)
+    else:
+        monkeypatch.setenv("QUARTET_GEMM_VARIANT", request.param)
+    return request.param
+
+
+@pytest.mark.parametrize("block", (64, 128))
+@pytest.mark.parametrize("mnk", [(1, 128, 32), (130, 256, 96), (257, 384, 160), (64, 1280, 1024), (520, 640, 800)])
+def test_gemm_grad_block_fused(G, mnk, block, gemm_variant):
+    # GEMM_LP with the gradient epilogue for Hadamard blocks of 64 or 128 columns in the same kernel against the
+    # oracle's two steps, and bit for bit against the stand-alone epilogue kernel on the library's own product
+    m, n, k = mnk
+    rng = np.random.default_rng(m * 1000 + n + block)
+    ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
+    bc = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    asc = rng.integers(117, 137, size=(m, k // 32), dtype=np.uint8)
+    bsc = rng.integers(117, 137, size=(n, k // 32), dtype=np.uint8)
+    mask = rng.integers(0, 2 ** 32, size=(m, n // 32), dtype=np.uint32)
+    acc = oracle.mxfp4_gemm(ac, asc, bc, bsc).astype(np.float32)
+    want = oracle.grad_epilogue_block(acc, mask, block)
+    got = G.gemm_grad_block(ac, asc, bc, bsc, block, mask, oracle.FL_16_9)
+    assert rel_fro(got, want) < FRO_TOL
+    plain = G.gemm(ac, asc, bc, bsc)
+    two_steps = G.grad_epilogue_block(plain, mask, block, oracle.FL_16_9)
+    assert np.array_equal(got.view(np.uint32), two_steps.view(np.uint32))
+    got_bf = G.gemm_grad_block(ac, asc, bc, bsc, block, mask, oracle.FL_16_9, bf16=True)
+    assert np.array_equal(got_bf, synth.f32_to_bf16(got))
+    got_nomask = G.gemm_grad_block(ac, asc, bc, bsc, block, None, 1.0)
+    assert rel_fro(got_nomask, oracle.grad_epilogue_block(acc, None, block, 1.0)) < FRO_TOL
+
+
 @pytest.mark.parametrize("block", BLOCKS)
 def test_linear_block(G, block):
     t, i, o = 256, 512, 768
@@ -146,3 +182,4 @@ def test_block_argument_errors(G):
     assert q.quartet_quant_fwd_block(x, 8, 96, 96, 0, 48, codes, scales, None) == q.QUARTET_EINVAL   # unsupported block
     assert q.quartet_linear_workspace_bytes_block(64, 64, 96, 64) == 0
     assert q.quartet_linear_workspace_bytes_block(256, 256, 256, 256) > q.quartet_linear_workspace_bytes(256, 256, 256)
+    assert q.quartet_linear_workspace_bytes_block(256, 256, 256, 128) == q.quartet_linear_workspace_bytes(256, 256, 256)
