@@ -420,8 +420,20 @@ requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* 
     __shared__ float s_stage[WPB][64 * kStageStride];
     const uint32_t lane = threadIdx.x & 63u;
     float* stage = s_stage[threadIdx.x >> 6];
-    const uint32_t gwave = blockIdx.x * (uint32_t)WPB + (threadIdx.x >> 6);   // wave of the whole launch along the columns
-    const uint32_t wave = gwave & 3u, quad = gwave >> 2;        // its place in a 256-column stretch, and the stretch
+    // its place in a 256-column stretch, and the stretch
+    uint32_t wave, quad;
+    if (WPB == 1) {
+        // One-wave blocks go to the 8 XCDs in turn.  The four waves of a stretch read the same 128-byte lines, so they
+        // are the blocks b, b+8, b+16, b+24 of a run of 32: same XCD, one L2 fetch per line instead of four.  The grid
+        // is padded to whole runs; the blocks past the last stretch leave at once.
+        quad = (blockIdx.x >> 5) * 8u + (blockIdx.x & 7u);
+        wave = (blockIdx.x >> 3) & 3u;
+        if (quad * 256u >= rows) return;
+    } else {
+        const uint32_t gwave = blockIdx.x * (uint32_t)WPB + (threadIdx.x >> 6);   // wave of the whole launch along the columns
+        wave = gwave & 3u;
+        quad = gwave >> 2;
+    }
     const uint32_t gk = k >> 5, okq = (k + 255u) >> 8;          // output groups per row, output K-quads
     const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;  // source row pitch in bytes, source K-quads
     const uint32_t c0 = quad * 256u + wave * 64u, kq = blockIdx.y, grp0 = kq * 8u;
@@ -753,8 +765,9 @@ static void launch_requant_nb(dim3 grid, hipStream_t st, const uint8_t* src_code
     switch (p.nb) {
     case 1u:
         // one wave per block (the waves never cooperate): measured equal to four-wave blocks on the large tensors and
-        // 8-20 % faster on weight-sized ones, where it spreads the same waves over four times as many CUs
-        hipLaunchKernelGGL((requant_transposed_kernel<MODE, 1>), dim3(grid.x * 4u, grid.y), dim3(64), 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p);
+        // 8-20 % faster on weight-sized ones, where it spreads the same waves over four times as many CUs; runs of 32
+        // blocks = 8 stretches x 4 waves, see the kernel
+        hipLaunchKernelGGL((requant_transposed_kernel<MODE, 1>), dim3(((grid.x + 7u) / 8u) * 32u, grid.y), dim3(64), 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p);
         break;
     case 2u: hipLaunchKernelGGL((requant_transposed_block_kernel<MODE, 2>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
     case 4u: hipLaunchKernelGGL((requant_transposed_block_kernel<MODE, 4>), grid, block, 0, st, src_codes, src_scales, (uint32_t)rows, (uint32_t)k, codes, scales, p); break;
