@@ -100,8 +100,21 @@ def cpu_baseline(config):
     _, ctx = oracle.linear_fwd(x, w)
     oracle.linear_bwd(dy, ctx, 0, 0)
     dt = time.perf_counter() - t0
-    return dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=oracle.num_threads(), kind="oracle",
-                sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s")
+    cores = oracle.num_threads()
+    # the same code on one thread, on the first tokens/cores rows of the same sample (about the same wall time)
+    t1 = int(max(32, (ts // max(cores, 1)) // 32 * 32))
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        _, ctx1 = oracle.linear_fwd(x[:t1], w)
+        oracle.linear_bwd(dy[:t1], ctx1, 0, 0)
+        dt1 = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(cores)
+    return dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+                sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s",
+                single_thread=dict(value=6.0 * t1 * i * o / dt1 / 1e12, unit="TFLOP/s", cores=1,
+                                   sample=f"the first {t1} tokens of that sample, {dt1:.1f} s"))
 
 
 def quant_sweep(q, torch, synth):
@@ -316,6 +329,25 @@ def main():
     gemm_total_ms = sum(gemm_ms)
     achieved = gemm_flops_step * args.steps / (gemm_total_ms * 1e-3) / 1e12 if gemm_total_ms > 0 else 0.0
 
+    # per GEMM shape, from the same event pairs (launch order inside a step: forward, dX, dW of each layer): the rate,
+    # and the share of the HBM peak that the minimum traffic (operands once, result once) comes to -- products with a
+    # short inner dimension and an fp32 result are bound by the result's stores, not by the matrix cores
+    by_shape = {}
+    if len(gemm_ms) == 3 * len(layers) * args.steps:
+        for idx, m_s in enumerate(gemm_ms):
+            l, which = layers[(idx // 3) % len(layers)], idx % 3
+            mnk = ((l.t, l.o, l.i), (l.t, l.i, l.o), (l.o, l.i, l.t))[which]
+            by_shape.setdefault(mnk, []).append(m_s)
+    gemm_by_shape = []
+    for (m, n, k), v in sorted(by_shape.items()):
+        avg = sum(v) / len(v)
+        min_bytes = (m + n) * k * (0.5 + 1.0 / 32.0) + 4.0 * m * n
+        gemm_by_shape.append({"m": m, "n": n, "k": k, "launches": len(v), "avg_ms": round(avg, 4),
+                              "TFLOPs": round(2.0 * m * n * k / avg / 1e9, 1),
+                              "frac_mfma": round(2.0 * m * n * k / avg / 1e9 / PEAK_FP4_TFLOPS, 4),
+                              "min_GBps": round(min_bytes / avg / 1e6, 1),
+                              "frac_hbm": round(min_bytes / avg / 1e6 / PEAK_HBM_GBS, 4)})
+
     ms_per_step = dt * 1e3 / args.steps
     result = {
         "metric": "Quartet linear fwd+bwd TFLOP/s at 1 GPU",
@@ -336,6 +368,7 @@ def main():
                      "traffic": recorded(args.config, "gemm_config{config}_hbm_traffic.txt", "traffic_bytes_per_launch"),
                      "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms),
                      "compute_units": cus},
+        "gemm_by_shape": gemm_by_shape,
         "lower_bound_ms_per_step": round(lower_bound_ms(layers), 4),
         "kernel_time_share": {k: round(sum(v) / (dt_all * 1e3), 4) for k, v in sorted(per_kind_all.items())},
     }
