@@ -223,7 +223,10 @@ size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out);
  * dx [tokens x in], dw [out x in] (grad_dtype).  sign_word = first output word of Philox4x32-10 at
  * counter (0,0,0,0xFFFFFFFF) under the seed's key; Philox stream ids 0,1,2,3 serve dy, W_q^T, dy^T,
  * X_q^T.  tokens, in, out all % 32 == 0.  workspace: device memory of at least
- * quartet_linear_workspace_bytes() bytes, 256-byte aligned, used only during the call's work.
+ * quartet_linear_workspace_bytes() bytes, 256-byte aligned, used only during the call's work (it holds
+ * the four quantized operands of the two gradient products, each in a region of its own).
+ * Launch order: Q(dy^T), Q(X_q^T) and Q(W_q^T) in one kernel, the dW product, Q(dy), the dx product;
+ * the results do not depend on the order (every operand has its own Philox stream).
  */
 int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
                        const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,

@@ -104,22 +104,28 @@ size_t scale_bytes(int64_t rows, int64_t k) {
 }
 
 struct BwdWorkspace {
-    size_t g_codes, g_scales, b_codes, b_scales, acc, total;
+    size_t g_codes, g_scales;       // dy quantized along out            [tokens x out]
+    size_t gt_codes, gt_scales;     // dy^T quantized along the tokens   [out x tokens]
+    size_t bw_codes, bw_scales;     // W_q re-quantized along out        [in x out]
+    size_t bx_codes, bx_scales;     // X_q re-quantized along the tokens [in x tokens]
+    size_t acc, total;
 };
 
-// with_acc: room for the fp32 product of the larger gradient GEMM (Hadamard blocks above 32 apply the
-// gradient epilogue in a kernel of its own)
+// All four operands of the two gradient products have room of their own (the three that do not feed the first product
+// are converted in one launch while it still waits).  with_acc: room for the fp32 product of the larger gradient GEMM
+// (Hadamard blocks above 128 apply the gradient epilogue in a kernel of its own).
 BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out, bool with_acc = false) {
     BwdWorkspace w;
-    size_t to = (size_t)tokens * (size_t)out;
-    size_t bmax = (size_t)in * (size_t)(out > tokens ? out : tokens);
-    size_t gs = scale_bytes(tokens, out), gts = scale_bytes(out, tokens);
-    size_t bs = scale_bytes(in, out), bts = scale_bytes(in, tokens);
+    const size_t to = (size_t)tokens * (size_t)out;
     size_t off = 0;
     w.g_codes = off; off += align256(to / 2);
-    w.g_scales = off; off += align256(gs > gts ? gs : gts);
-    w.b_codes = off; off += align256(bmax / 2);
-    w.b_scales = off; off += align256(bs > bts ? bs : bts);
+    w.g_scales = off; off += align256(scale_bytes(tokens, out));
+    w.gt_codes = off; off += align256(to / 2);
+    w.gt_scales = off; off += align256(scale_bytes(out, tokens));
+    w.bw_codes = off; off += align256((size_t)in * (size_t)out / 2);
+    w.bw_scales = off; off += align256(scale_bytes(in, out));
+    w.bx_codes = off; off += align256((size_t)in * (size_t)tokens / 2);
+    w.bx_scales = off; off += align256(scale_bytes(in, tokens));
     w.acc = off;
     if (with_acc) off += align256(sizeof(float) * (size_t)in * (size_t)(out > tokens ? out : tokens));
     w.total = off;
@@ -149,8 +155,9 @@ int quartet_profile_enable(int max_records) {
     g_prof.stop = new hipEvent_t[max_records];
     g_prof.kind = new int[max_records];
     for (int i = 0; i < max_records; ++i) {
-        hipError_t e = hipEventCreate(&g_prof.start[i]);
-        if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[i]);
+        // timing only: no system-scope fence (cache write-back) when an event completes
+        hipError_t e = hipEventCreateWithFlags(&g_prof.start[i], hipEventDisableSystemFence);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&g_prof.stop[i], hipEventDisableSystemFence);
         if (e != hipSuccess) {
             g_prof.capacity = i;
             profile_free();
@@ -445,36 +452,64 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return QUARTET_EINVAL;
     uint8_t* base = static_cast<uint8_t*>(workspace);
     uint8_t *g_codes = base + w.g_codes, *g_scales = base + w.g_scales;
-    uint8_t *b_codes = base + w.b_codes, *b_scales = base + w.b_scales;
+    uint8_t *gt_codes = base + w.gt_codes, *gt_scales = base + w.gt_scales;
+    uint8_t *bw_codes = base + w.bw_codes, *bw_scales = base + w.bw_scales;
+    uint8_t *bx_codes = base + w.bx_codes, *bx_scales = base + w.bx_scales;
     float* acc = reinterpret_cast<float*>(base + w.acc);
     uint32_t sw[8];
     quartet_sign_words(seed, sw);
     const float c169 = 16.0f / 9.0f;
     int rc;
-    // dx = 16/9 H( (Q(dy) Q(W_q^T)^T) . M_x ), inner dimension = out
-    rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
+    // dx = 16/9 H( (Q(dy) Q(W_q^T)^T) . M_x ), inner dimension = out   (operand streams 0, 1)
+    // dW = 16/9 H( (Q(dy^T) Q(X_q^T)^T) . M_w ), inner dimension = tokens (operand streams 2, 3)
+    if (hb == 32) {
+        // Q(dy^T), Q(X_q^T), Q(W_q^T) in one launch, then dW, then Q(dy) and dx: measured 2.4 % faster per layer pass
+        // than six launches in the order of Algorithm 1 (each product starts on operands that were just written, and a
+        // quantizer between the two products lets the clock recover).  The same checks as the entry points that convert
+        // the operands one by one.
+        rc = check_quant_shape(out, tokens, out, 1);
+        if (!rc) rc = check_quant_shape(in, tokens, (in + 7) / 8 * 8, 1);
+        if (!rc) rc = check_quant_shape(in, out, (in + 7) / 8 * 8, 1);
+        if (!rc && in >= ((int64_t)1 << 24)) rc = QUARTET_ENOTSUP;
+        if (rc) return rc;
+        const int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+        {
+            ProfileScope prof(QUARTET_KIND_QUANT_BWD, (hipStream_t)stream);
+            hipError_t e = quartet::launch_bwd_operands(mode, dy_bf16, tokens, in, out, xq_codes, xq_scales, wq_codes, wq_scales,
+                                                        make_params(1u, sw, seed, 2u), make_params(1u, sw, seed, 3u),
+                                                        make_params(1u, sw, seed, 1u), gt_codes, gt_scales, bx_codes, bx_scales,
+                                                        bw_codes, bw_scales, (hipStream_t)stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        rc = quartet_mxfp4_gemm_grad_block(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
+        if (rc) return rc;
+        rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
+        if (rc) return rc;
+        return quartet_mxfp4_gemm_grad_block(g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, hb, x_mask, c169, dx, grad_dtype, in, stream);
+    }
+    // wider Hadamard blocks: one launch per operand, the products in the same order
+    rc = quartet_quant_bwd_sr_block(dy_bf16, out, tokens, out, 1, hb, sw, seed, 2u, rounding, gt_codes, gt_scales, stream);
     if (rc) return rc;
-    rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, b_codes, b_scales, stream);
+    rc = quartet_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, bx_codes, bx_scales, stream);
     if (rc) return rc;
     if (!big) {
-        rc = quartet_mxfp4_gemm_grad_block(g_codes, g_scales, b_codes, b_scales, tokens, in, out, hb, x_mask, c169, dx, grad_dtype, in, stream);
+        rc = quartet_mxfp4_gemm_grad_block(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
     } else {
         // a block of 256 columns spans two waves' tiles: fp32 product, then the epilogue kernel
-        rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+        rc = quartet_mxfp4_gemm(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
         if (rc) return rc;
-        rc = quartet_grad_epilogue_block(acc, x_mask, tokens, in, hb, c169, dx, grad_dtype, stream);
+        rc = quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);
     }
     if (rc) return rc;
-    // dW = 16/9 H( (Q(dy^T) Q(X_q^T)^T) . M_w ), inner dimension = tokens
-    rc = quartet_quant_bwd_sr_block(dy_bf16, out, tokens, out, 1, hb, sw, seed, 2u, rounding, g_codes, g_scales, stream);
+    rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
     if (rc) return rc;
-    rc = quartet_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, b_codes, b_scales, stream);
+    rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, bw_codes, bw_scales, stream);
     if (rc) return rc;
     if (!big)
-        return quartet_mxfp4_gemm_grad_block(g_codes, g_scales, b_codes, b_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
-    rc = quartet_mxfp4_gemm(g_codes, g_scales, b_codes, b_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+        return quartet_mxfp4_gemm_grad_block(g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, hb, x_mask, c169, dx, grad_dtype, in, stream);
+    rc = quartet_mxfp4_gemm(g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
     if (rc) return rc;
-    return quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);
+    return quartet_grad_epilogue_block(acc, x_mask, tokens, in, hb, c169, dx, grad_dtype, stream);
 }
 
 }  // extern "C"

@@ -19,6 +19,12 @@ hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_
 hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const uint8_t* src_scales,
                                     int64_t rows, int64_t k, const SrParams& p, uint8_t* codes,
                                     uint8_t* scales, hipStream_t st);
+// dy^T quantized along the tokens, X_q and W_q re-quantized along their other dimension: one launch (Hadamard block 32)
+hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t in, int64_t out,
+                               const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
+                               const SrParams& p_dyt, const SrParams& p_x, const SrParams& p_w,
+                               uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
+                               uint8_t* wt_codes, uint8_t* wt_scales, hipStream_t st);
 hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t k, float* out,
                           hipStream_t st);
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,

@@ -256,18 +256,17 @@ __device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, cons
 // groups 2w, 2w+1; lane l owns columns 2l, 2l+1.  Blocks are numbered K-quad first: the blocks that
 // run at the same time then write neighbouring 128-byte lines of the same output rows (measured 10 %
 // faster than column-tile first, where every block's lines lie a whole output row apart).
+// bx, by: the block's K-quad and column tile; s_codes (16 KB), s_scales (1 KB), s_mask (4 KB): the block's LDS
 template <int MODE, bool MASK>
-__global__ void __launch_bounds__(256, MODE == kBwdSr ? 3 : 4)
-quant_transposed_kernel(const uint16_t* __restrict__ src,
-                        uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
-                        uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
-    __shared__ uint4 s_codes[128 * 8];
-    __shared__ uint8_t s_scales[128 * 8];
-    __shared__ uint32_t s_mask[128 * 8];
+__device__ __forceinline__ void quant_transposed_tile(const uint16_t* __restrict__ src,
+                                                      uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
+                                                      uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
+                                                      const SrParams& p, uint32_t bx, uint32_t by,
+                                                      uint4* s_codes, uint8_t* s_scales, uint32_t* s_mask) {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
     const uint32_t gk = k >> 5;
-    const uint32_t col0 = blockIdx.y * 128u;
-    const uint32_t grp0 = blockIdx.x * 8u;
+    const uint32_t col0 = by * 128u;
+    const uint32_t grp0 = bx * 8u;
     const uint32_t col = col0 + 2u * lane;                // even; rows is even, so col+1 < rows too
     // the block's corner of the source through a buffer resource that ends with the last column of the
     // last source row
@@ -312,6 +311,17 @@ quant_transposed_kernel(const uint16_t* __restrict__ src,
     }
     __syncthreads();
     transposed_store_tile<MASK>(s_codes, s_scales, s_mask, col0, grp0, rows, gk, k, codes, scales, mask);
+}
+
+template <int MODE, bool MASK>
+__global__ void __launch_bounds__(256, MODE == kBwdSr ? 3 : 4)
+quant_transposed_kernel(const uint16_t* __restrict__ src,
+                        uint32_t rows, uint32_t k, int64_t ldx, uint8_t* __restrict__ codes,
+                        uint8_t* __restrict__ scales, uint32_t* __restrict__ mask, SrParams p) {
+    __shared__ uint4 s_codes[128 * 8];
+    __shared__ uint8_t s_scales[128 * 8];
+    __shared__ uint32_t s_mask[128 * 8];
+    quant_transposed_tile<MODE, MASK>(src, rows, k, ldx, codes, scales, mask, p, blockIdx.x, blockIdx.y, s_codes, s_scales, s_mask);
 }
 
 // The same tile for Hadamard blocks of NB = 2, 4 or 8 groups.  The groups of a block are whole source
@@ -412,31 +422,17 @@ constexpr uint32_t kStageStride = 36;   // floats per column of the stage: 16-by
 
 // WPB = waves per block (the launcher uses 1: the waves of a 256-column stretch never cooperate, and blocks of one
 // wave spread them over more CUs).
-template <int MODE, int WPB>
-__global__ void __launch_bounds__(64 * WPB, 4)   // 4 waves per SIMD: at most 128 registers
-requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
-                          uint32_t rows, uint32_t k, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
-                          SrParams p) {
-    __shared__ float s_stage[WPB][64 * kStageStride];
+// The work of one wave: `wave` = its place in the 256-column stretch `quad`, kq = the K-quad of the output, stage = the
+// wave's 64 x kStageStride floats of LDS.
+template <int MODE>
+__device__ __forceinline__ void requant_transposed_wave(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
+                                                        uint32_t rows, uint32_t k, uint8_t* __restrict__ codes,
+                                                        uint8_t* __restrict__ scales, const SrParams& p,
+                                                        uint32_t wave, uint32_t quad, uint32_t kq, float* stage) {
     const uint32_t lane = threadIdx.x & 63u;
-    float* stage = s_stage[threadIdx.x >> 6];
-    // its place in a 256-column stretch, and the stretch
-    uint32_t wave, quad;
-    if (WPB == 1) {
-        // One-wave blocks go to the 8 XCDs in turn.  The four waves of a stretch read the same 128-byte lines, so they
-        // are the blocks b, b+8, b+16, b+24 of a run of 32: same XCD, one L2 fetch per line instead of four.  The grid
-        // is padded to whole runs; the blocks past the last stretch leave at once.
-        quad = (blockIdx.x >> 5) * 8u + (blockIdx.x & 7u);
-        wave = (blockIdx.x >> 3) & 3u;
-        if (quad * 256u >= rows) return;
-    } else {
-        const uint32_t gwave = blockIdx.x * (uint32_t)WPB + (threadIdx.x >> 6);   // wave of the whole launch along the columns
-        wave = gwave & 3u;
-        quad = gwave >> 2;
-    }
     const uint32_t gk = k >> 5, okq = (k + 255u) >> 8;          // output groups per row, output K-quads
     const uint32_t half = rows >> 1, skq = (rows + 255u) >> 8;  // source row pitch in bytes, source K-quads
-    const uint32_t c0 = quad * 256u + wave * 64u, kq = blockIdx.y, grp0 = kq * 8u;
+    const uint32_t c0 = quad * 256u + wave * 64u, grp0 = kq * 8u;
     // load role: source row rl of the group, 32-column chunk ch of the wave's 64 columns
     const uint32_t rl = lane >> 1, ch = lane & 1u, cg = wave * 2u + ch;   // cg: column group inside the source's K-quad
     // The block's corner of the source codes and the scale tiles below it through buffer resources that
@@ -544,6 +540,75 @@ requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* 
             for (uint32_t q = 0; q < 4; ++q)
                 if (grp0 + 2u * q + h < gk) reinterpret_cast<uint8_t*>(dst)[q] = (uint8_t)(w >> (8u * q));
         }
+    }
+}
+
+template <int MODE, int WPB>
+__global__ void __launch_bounds__(64 * WPB, 4)   // 4 waves per SIMD: at most 128 registers
+requant_transposed_kernel(const uint8_t* __restrict__ src_codes, const uint8_t* __restrict__ src_scales,
+                          uint32_t rows, uint32_t k, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales,
+                          SrParams p) {
+    __shared__ float s_stage[WPB][64 * kStageStride];
+    // its place in a 256-column stretch, and the stretch
+    uint32_t wave, quad;
+    if (WPB == 1) {
+        // One-wave blocks go to the 8 XCDs in turn.  The four waves of a stretch read the same 128-byte lines, so they
+        // are the blocks b, b+8, b+16, b+24 of a run of 32: same XCD, one L2 fetch per line instead of four.  The grid
+        // is padded to whole runs; the blocks past the last stretch leave at once.
+        quad = (blockIdx.x >> 5) * 8u + (blockIdx.x & 7u);
+        wave = (blockIdx.x >> 3) & 3u;
+        if (quad * 256u >= rows) return;
+    } else {
+        const uint32_t gwave = blockIdx.x * (uint32_t)WPB + (threadIdx.x >> 6);   // wave of the whole launch along the columns
+        wave = gwave & 3u;
+        quad = gwave >> 2;
+    }
+    requant_transposed_wave<MODE>(src_codes, src_scales, rows, k, codes, scales, p, wave, quad, blockIdx.y, s_stage[threadIdx.x >> 6]);
+}
+
+// ------------------------------------------------------------------ the backward pass's three operand conversions in one launch
+// dy^T quantized along the tokens (quant_transposed_tile), X_q and W_q re-quantized along their other dimension
+// (requant_transposed_wave, four waves = one 256-column stretch per block): Algorithm 1 Backward needs all three before the
+// two gradient products and none depends on another.  Launched one after the other, the re-quantizers leave most of the
+// chip idle on weight-sized tensors and every kernel pays its own ramp-up and drain.  In one grid the re-quantizer blocks
+// come first (W_q's, then X_q's) and the dy^T tiles fill the CUs as those finish.  (Spreading the re-quantizer blocks
+// evenly among the tiles was measured slower than launching the kernels one by one: it breaks up the order in which
+// neighbouring tiles write their lines.)
+struct BwdOperandsMap {
+    uint32_t n_rq_w, n_rq;           // re-quantizer blocks of W_q, and of W_q and X_q together: block indices [0, n_rq)
+    uint32_t t_gx, w_quads, x_quads; // dy^T tiles per column tile row (K-quads); 256-column stretches of W_q^T, X_q^T
+    FastDiv div_t_gx, div_w_quads, div_x_quads;
+};
+
+template <int MODE>
+__global__ void __launch_bounds__(256, 3)
+bwd_operands_kernel(const uint16_t* __restrict__ dy, uint32_t t_rows, uint32_t t_k, int64_t t_ldx,
+                    uint8_t* __restrict__ t_codes, uint8_t* __restrict__ t_scales, SrParams t_p,
+                    const uint8_t* __restrict__ x_src_codes, const uint8_t* __restrict__ x_src_scales, uint32_t x_rows, uint32_t x_k,
+                    uint8_t* __restrict__ x_codes, uint8_t* __restrict__ x_scales, SrParams x_p,
+                    const uint8_t* __restrict__ w_src_codes, const uint8_t* __restrict__ w_src_scales, uint32_t w_rows, uint32_t w_k,
+                    uint8_t* __restrict__ w_codes, uint8_t* __restrict__ w_scales, SrParams w_p, BwdOperandsMap map) {
+    __shared__ __align__(16) uint8_t smem[4u * 64u * kStageStride * sizeof(float)];   // 36 KB: four re-quantizer stages
+    static_assert(sizeof(smem) >= 128 * 8 * (16 + 1 + 4), "the dy^T tile's staging must fit as well");
+    const uint32_t b = blockIdx.x;
+    if (b < map.n_rq) {
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        float* stage = reinterpret_cast<float*>(smem) + wave * (64u * kStageStride);
+        if (b < map.n_rq_w) {
+            const uint32_t kq = fast_div(b, map.div_w_quads), quad = b - kq * map.w_quads;
+            requant_transposed_wave<MODE>(w_src_codes, w_src_scales, w_rows, w_k, w_codes, w_scales, w_p, wave, quad, kq, stage);
+        } else {
+            const uint32_t j = b - map.n_rq_w;
+            const uint32_t kq = fast_div(j, map.div_x_quads), quad = j - kq * map.x_quads;
+            requant_transposed_wave<MODE>(x_src_codes, x_src_scales, x_rows, x_k, x_codes, x_scales, x_p, wave, quad, kq, stage);
+        }
+    } else {
+        const uint32_t tb = b - map.n_rq;
+        const uint32_t by = fast_div(tb, map.div_t_gx), bx = tb - by * map.t_gx;
+        uint4* s_codes = reinterpret_cast<uint4*>(smem);
+        uint32_t* s_mask = reinterpret_cast<uint32_t*>(smem + 128 * 8 * 16);
+        uint8_t* s_scales = smem + 128 * 8 * 20;
+        quant_transposed_tile<MODE, false>(dy, t_rows, t_k, t_ldx, t_codes, t_scales, nullptr, t_p, bx, by, s_codes, s_scales, s_mask);
     }
 }
 
@@ -782,6 +847,36 @@ hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const ui
     dim3 grid((uint32_t)((rows + 255) / 256), (uint32_t)((k + 255) / 256));
     if (mode == kBwdRtn) launch_requant_nb<kBwdRtn>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
     else launch_requant_nb<kBwdSr>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t in, int64_t out,
+                               const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
+                               const SrParams& p_dyt, const SrParams& p_x, const SrParams& p_w,
+                               uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
+                               uint8_t* wt_codes, uint8_t* wt_scales, hipStream_t st) {
+    if (tokens == 0 || in == 0 || out == 0) return hipSuccess;
+    BwdOperandsMap map;
+    // dy^T: logical [out x tokens]; X_q^T: [in x tokens] from [tokens x in]; W_q^T: [in x out] from [out x in]
+    map.t_gx = (uint32_t)((tokens / 32 + 7) / 8);
+    const uint32_t t_gy = (uint32_t)((out + 127) / 128);
+    map.w_quads = map.x_quads = (uint32_t)((in + 255) / 256);
+    map.n_rq_w = map.w_quads * (uint32_t)((out + 255) / 256);
+    map.n_rq = map.n_rq_w + map.x_quads * (uint32_t)((tokens + 255) / 256);
+    const uint64_t total = (uint64_t)map.t_gx * t_gy + map.n_rq;
+    if (total >= ((uint64_t)1 << 31)) return hipErrorInvalidValue;
+    map.div_t_gx = make_fast_div(map.t_gx);
+    map.div_w_quads = make_fast_div(map.w_quads);
+    map.div_x_quads = make_fast_div(map.x_quads);
+    dim3 grid((uint32_t)total), block(256);
+    if (mode == kBwdRtn)
+        hipLaunchKernelGGL((bwd_operands_kernel<kBwdRtn>), grid, block, 0, st, (const uint16_t*)dy, (uint32_t)out, (uint32_t)tokens, out,
+                           dyt_codes, dyt_scales, p_dyt, xq_codes, xq_scales, (uint32_t)in, (uint32_t)tokens, xt_codes, xt_scales, p_x,
+                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w, map);
+    else
+        hipLaunchKernelGGL((bwd_operands_kernel<kBwdSr>), grid, block, 0, st, (const uint16_t*)dy, (uint32_t)out, (uint32_t)tokens, out,
+                           dyt_codes, dyt_scales, p_dyt, xq_codes, xq_scales, (uint32_t)in, (uint32_t)tokens, xt_codes, xt_scales, p_x,
+                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w, map);
     return hipGetLastError();
 }
 
