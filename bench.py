@@ -329,14 +329,14 @@ def main():
     gemm_total_ms = sum(gemm_ms)
     achieved = gemm_flops_step * args.steps / (gemm_total_ms * 1e-3) / 1e12 if gemm_total_ms > 0 else 0.0
 
-    # per GEMM shape, from the same event pairs (launch order inside a step: forward, dX, dW of each layer): the rate,
+    # per GEMM shape, from the same event pairs (launch order inside a step: forward, dW, dX of each layer): the rate,
     # and the share of the HBM peak that the minimum traffic (operands once, result once) comes to -- products with a
     # short inner dimension and an fp32 result are bound by the result's stores, not by the matrix cores
     by_shape = {}
     if len(gemm_ms) == 3 * len(layers) * args.steps:
         for idx, m_s in enumerate(gemm_ms):
             l, which = layers[(idx // 3) % len(layers)], idx % 3
-            mnk = ((l.t, l.o, l.i), (l.t, l.i, l.o), (l.o, l.i, l.t))[which]
+            mnk = ((l.t, l.o, l.i), (l.o, l.i, l.t), (l.t, l.i, l.o))[which]
             by_shape.setdefault(mnk, []).append(m_s)
     gemm_by_shape = []
     for (m, n, k), v in sorted(by_shape.items()):
