@@ -141,6 +141,25 @@ int quartet_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_sc
                                  uint8_t *codes, uint8_t *scales, void *stream);
 
 /*
+ * The three operand conversions of Algorithm 1 Backward that do not depend on each other, in one
+ * launch (dy [tokens x out] bf16 row-major; X_q [tokens x in] and W_q [out x in] as
+ * quartet_quant_fwd wrote them; tokens, in, out all % 32 == 0):
+ *   dyt = quartet_quant_bwd_sr(dy, rows = out, k = tokens, ldx = out, transpose = 1, stream id 2)
+ *   xt  = quartet_requant_transpose_sr(X_q, rows = in, k = tokens, stream id 3)
+ *   wt  = quartet_requant_transpose_sr(W_q, rows = in, k = out,    stream id 1)
+ * with the same sign_word, seed and rounding; the six outputs are bit-identical to those of the
+ * three calls (dyt [out x tokens], xt [in x tokens], wt [in x out], codes and tiled scales).
+ * quartet_linear_bwd runs this, the dW product, quartet_quant_bwd_sr on dy (stream id 0), the dx
+ * product.  Errors as for the three calls.
+ */
+int quartet_bwd_operands(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                         const uint8_t *xq_codes, const uint8_t *xq_scales,
+                         const uint8_t *wq_codes, const uint8_t *wq_scales,
+                         uint32_t sign_word, uint64_t seed, int rounding,
+                         uint8_t *dyt_codes, uint8_t *dyt_scales, uint8_t *xt_codes, uint8_t *xt_scales,
+                         uint8_t *wt_codes, uint8_t *wt_scales, void *stream);
+
+/*
  * GEMM_LP (Section 4.4 "Stage 2": D = (A x SFA)(B x SFB), scales along K, one per 32):
  *   D[m x n] = alpha * sum_k dec(A)[m,k] * dec(B)[n,k]
  * A = (a_codes [m x k/2], a_scales tiled for [m x k]), B = (b_codes [n x k/2], b_scales tiled for

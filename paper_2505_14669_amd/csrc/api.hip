@@ -259,6 +259,35 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
                                               codes, scales, stream);
 }
 
+int quartet_bwd_operands(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                         const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
+                         uint32_t sign_word, uint64_t seed, int rounding,
+                         uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
+                         uint8_t* wt_codes, uint8_t* wt_scales, void* stream) {
+    if (!dy_bf16 || !xq_codes || !xq_scales || !wq_codes || !wq_scales) return QUARTET_EINVAL;
+    if (!dyt_codes || !dyt_scales || !xt_codes || !xt_scales || !wt_codes || !wt_scales) return QUARTET_EINVAL;
+    if (!aligned16(dy_bf16) || !aligned16(xq_codes) || !aligned16(wq_codes) || !aligned16(dyt_codes) || !aligned16(xt_codes) ||
+        !aligned16(wt_codes))
+        return QUARTET_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(dyt_scales) | reinterpret_cast<uintptr_t>(xt_scales) | reinterpret_cast<uintptr_t>(wt_scales)) & 3u)
+        return QUARTET_EINVAL;
+    if (rounding != QUARTET_ROUND_STOCHASTIC && rounding != QUARTET_ROUND_NEAREST) return QUARTET_EINVAL;
+    if (tokens < 0 || in < 0 || out < 0 || (tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return QUARTET_EINVAL;
+    // the checks of the three calls this launch stands for
+    int rc = check_quant_shape(out, tokens, out, 1);
+    if (!rc) rc = check_quant_shape(in, tokens, in, 1);
+    if (!rc) rc = check_quant_shape(in, out, in, 1);
+    if (!rc && in >= ((int64_t)1 << 24)) rc = QUARTET_ENOTSUP;
+    if (rc) return rc;
+    const int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
+    ProfileScope prof(QUARTET_KIND_QUANT_BWD, (hipStream_t)stream);
+    hipError_t e = quartet::launch_bwd_operands(mode, dy_bf16, tokens, in, out, xq_codes, xq_scales, wq_codes, wq_scales,
+                                                make_params(1u, &sign_word, seed, 2u), make_params(1u, &sign_word, seed, 3u),
+                                                make_params(1u, &sign_word, seed, 1u), dyt_codes, dyt_scales, xt_codes, xt_scales,
+                                                wt_codes, wt_scales, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
 int quartet_requant_transpose_sr_block(const uint8_t* src_codes, const uint8_t* src_scales,
                                        int64_t rows, int64_t k, int hadamard_block, const uint32_t* sign_words,
                                        uint64_t seed, uint32_t stream_id, int rounding,
@@ -465,22 +494,10 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
     if (hb == 32) {
         // Q(dy^T), Q(X_q^T), Q(W_q^T) in one launch, then dW, then Q(dy) and dx: measured 2.4 % faster per layer pass
         // than six launches in the order of Algorithm 1 (each product starts on operands that were just written, and a
-        // quantizer between the two products lets the clock recover).  The same checks as the entry points that convert
-        // the operands one by one.
-        rc = check_quant_shape(out, tokens, out, 1);
-        if (!rc) rc = check_quant_shape(in, tokens, (in + 7) / 8 * 8, 1);
-        if (!rc) rc = check_quant_shape(in, out, (in + 7) / 8 * 8, 1);
-        if (!rc && in >= ((int64_t)1 << 24)) rc = QUARTET_ENOTSUP;
+        // quantizer between the two products lets the clock recover).
+        rc = quartet_bwd_operands(dy_bf16, tokens, in, out, xq_codes, xq_scales, wq_codes, wq_scales, sw[0], seed, rounding,
+                                  gt_codes, gt_scales, bx_codes, bx_scales, bw_codes, bw_scales, stream);
         if (rc) return rc;
-        const int mode = rounding == QUARTET_ROUND_NEAREST ? quartet::kBwdRtn : quartet::kBwdSr;
-        {
-            ProfileScope prof(QUARTET_KIND_QUANT_BWD, (hipStream_t)stream);
-            hipError_t e = quartet::launch_bwd_operands(mode, dy_bf16, tokens, in, out, xq_codes, xq_scales, wq_codes, wq_scales,
-                                                        make_params(1u, sw, seed, 2u), make_params(1u, sw, seed, 3u),
-                                                        make_params(1u, sw, seed, 1u), gt_codes, gt_scales, bx_codes, bx_scales,
-                                                        bw_codes, bw_scales, (hipStream_t)stream);
-            if (e != hipSuccess) return hip_fail(e);
-        }
         rc = quartet_mxfp4_gemm_grad_block(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
         if (rc) return rc;
         rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);

@@ -855,19 +855,20 @@ hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t
                                const SrParams& p_dyt, const SrParams& p_x, const SrParams& p_w,
                                uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
                                uint8_t* wt_codes, uint8_t* wt_scales, hipStream_t st) {
-    if (tokens == 0 || in == 0 || out == 0) return hipSuccess;
     BwdOperandsMap map;
-    // dy^T: logical [out x tokens]; X_q^T: [in x tokens] from [tokens x in]; W_q^T: [in x out] from [out x in]
+    // dy^T: logical [out x tokens]; X_q^T: [in x tokens] from [tokens x in]; W_q^T: [in x out] from [out x in].
+    // An empty dimension empties the conversions it belongs to, not the others.
     map.t_gx = (uint32_t)((tokens / 32 + 7) / 8);
     const uint32_t t_gy = (uint32_t)((out + 127) / 128);
     map.w_quads = map.x_quads = (uint32_t)((in + 255) / 256);
     map.n_rq_w = map.w_quads * (uint32_t)((out + 255) / 256);
     map.n_rq = map.n_rq_w + map.x_quads * (uint32_t)((tokens + 255) / 256);
     const uint64_t total = (uint64_t)map.t_gx * t_gy + map.n_rq;
+    if (total == 0) return hipSuccess;
     if (total >= ((uint64_t)1 << 31)) return hipErrorInvalidValue;
-    map.div_t_gx = make_fast_div(map.t_gx);
-    map.div_w_quads = make_fast_div(map.w_quads);
-    map.div_x_quads = make_fast_div(map.x_quads);
+    map.div_t_gx = make_fast_div(map.t_gx ? map.t_gx : 1u);
+    map.div_w_quads = make_fast_div(map.w_quads ? map.w_quads : 1u);
+    map.div_x_quads = make_fast_div(map.x_quads ? map.x_quads : 1u);
     dim3 grid((uint32_t)total), block(256);
     if (mode == kBwdRtn)
         hipLaunchKernelGGL((bwd_operands_kernel<kBwdRtn>), grid, block, 0, st, (const uint16_t*)dy, (uint32_t)out, (uint32_t)tokens, out,

@@ -62,6 +62,21 @@ def requant_transpose_sr(src_codes, src_scales, sign_word, seed, stream_id, roun
     return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
 
 
+def bwd_operands(dy_u16, xq_codes, xq_scales, wq_codes, wq_scales, sign_word, seed, rounding=0):
+    """quartet_bwd_operands on host arrays (scales row-major); returns (codes, scales) of dy^T, X_q^T, W_q^T."""
+    t, o = dy_u16.shape
+    i = xq_codes.shape[1] * 2
+    outs = []
+    for r, c in ((o, t), (i, t), (i, o)):
+        outs += [dev_empty((r, c // 2), np.uint8, 0xEE), dev_empty((max(q.quartet_scale_bytes(r, c), 4),), np.uint8, 0xFF)]
+    q.check(q.quartet_bwd_operands(to_dev(dy_u16), t, i, o, to_dev(xq_codes), to_dev(scales_to_tiled(xq_scales)),
+                                   to_dev(wq_codes), to_dev(scales_to_tiled(wq_scales)), sign_word, seed, rounding, *outs))
+    res = []
+    for n, (r, c) in enumerate(((o, t), (i, t), (i, o))):
+        res.append((to_host(outs[2 * n], np.uint8), scales_from_tiled(to_host(outs[2 * n + 1], np.uint8), r, c)))
+    return res
+
+
 def dequant(codes, scales):
     rows, k = codes.shape[0], codes.shape[1] * 2
     out = dev_empty((rows, k), np.float32, float("nan"))

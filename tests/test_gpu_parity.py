@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from paper_2505_14669_amd import synth
-from indep import scale_tiled_bytes as q_scale_bytes, scales_from_tiled
+from indep import scale_tiled_bytes as q_scale_bytes, scales_from_tiled, scales_to_tiled
 
 pytestmark = pytest.mark.gpu
 
@@ -233,6 +233,42 @@ def test_grad_epilogue(G, shape):
     assert np.array_equal(got3.view(np.uint32), oracle.grad_epilogue(g, None, 1.0).view(np.uint32))
     got4 = G.grad_epilogue(g, mask, oracle.FL_16_9, bf16=True)
     assert np.array_equal(got4, synth.f32_to_bf16(want))
+
+
+@pytest.mark.parametrize("tio", [(32, 32, 32), (96, 160, 224), (288, 320, 352), (800, 544, 1056), (1024, 1280, 256)])
+@pytest.mark.parametrize("rounding", [0, 1])
+def test_bwd_operands_match_the_three_conversions(G, tio, rounding):
+    # Algorithm 1 Backward: Q(dy^T), Q(X_q^T), Q(W_q^T) from one launch, bit for bit the oracle's three quantizations.
+    # X_q and W_q come from the oracle's forward quantizer.
+    t, i, o = tio
+    dy = synth.small_matrix(300 + t, t, o, "normal", 1e-3)
+    xq_codes, xq_scales, _ = oracle.quant_fwd(synth.small_matrix(301 + i, t, i, "heavy"))
+    wq_codes, wq_scales, _ = oracle.quant_fwd(synth.small_matrix(302 + o, o, i, "normal", 0.02))
+    sw, seed = 0xC3A5F00F ^ t, 2 ** 36 + 3 * o + rounding
+    got = G.bwd_operands(dy, xq_codes, xq_scales, wq_codes, wq_scales, sw, seed, rounding)
+    want = (oracle.quant_bwd_sr(dy, sw, seed, 2, rounding, transpose=True),
+            oracle.requant_transpose_sr(xq_codes, xq_scales, sw, seed, 3, rounding),
+            oracle.requant_transpose_sr(wq_codes, wq_scales, sw, seed, 1, rounding))
+    for name, g, w in zip(("dy^T", "X_q^T", "W_q^T"), got, want):
+        same(g[0], w[0], f"{name} codes")
+        same(g[1], w[1], f"{name} scales")
+
+
+def test_bwd_operands_with_no_tokens_still_convert_the_weights(G):
+    # an empty dimension empties the conversions it belongs to, not the third one
+    i, o = 64, 96
+    wq_codes, wq_scales, _ = oracle.quant_fwd(synth.small_matrix(77, o, i, "normal", 0.02))
+    sw, seed = 0x12345678, 99
+    dummy = G.dev_empty((64,), np.uint8, 0)          # stands in for the pointers of the empty tensors (never read or written)
+    wt_codes = G.dev_empty((i, o // 2), np.uint8, 0xEE)
+    wt_scales = G.dev_empty((q_scale_bytes(i, o),), np.uint8, 0xFF)
+    from paper_2505_14669_amd import binding as q
+    q.check(q.quartet_bwd_operands(dummy, 0, i, o, dummy, dummy, G.to_dev(wq_codes), G.to_dev(scales_to_tiled(wq_scales)),
+                                   sw, seed, 0, dummy, dummy, dummy, dummy, wt_codes, wt_scales))
+    want = oracle.requant_transpose_sr(wq_codes, wq_scales, sw, seed, 1, 0)
+    same(G.to_host(wt_codes, np.uint8), want[0], "W_q^T codes")
+    same(scales_from_tiled(G.to_host(wt_scales, np.uint8), i, o), want[1], "W_q^T scales")
+    assert int(dummy.sum()) == 0
 
 
 def _check_linear(G, L, seed, roundings=(0, 1)):
