@@ -376,7 +376,11 @@ def main():
     if clock:   # the same fraction against what the chip can do at the clock it actually holds under this kernel
         peak_obs = cus * clock * 1e9 * 16384 / 1e12
         result["roofline"].update(observed_clock_ghz=clock, peak_at_observed_clock=round(peak_obs, 1),
-                                  frac_at_observed_clock=round(achieved / peak_obs, 4))
+                                  frac_at_observed_clock=round(achieved / peak_obs, 4),
+                                  note="the chip is power-limited under FP4 matrix work: a register-only loop of the same "
+                                       "matrix-core instruction on quantized Gaussian codes sustains 6.2 PFLOP/s "
+                                       "(profiles/gemm_config4_mfma_counters.txt); the vendor library's MXFP4 GEMM runs "
+                                       "these shapes at 2.1 PFLOP/s (profiles/vendor_mxfp4_gemm_config4.txt)")
     if args.breakdown:
         for k, v in sorted(per_kind_all.items()):
             print(f"  {k:10s} launches {len(v):4d} total {sum(v):9.3f} ms  ({sum(v) / (dt_all * 1e3) * 100:5.1f} % of one fully bracketed step)",
