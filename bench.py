@@ -83,22 +83,29 @@ class Layer:
                                      self.dx, self.dw, q.QUARTET_DTYPE_F32, ws, self.ws_bytes))
 
 
-def cpu_baseline(config):
+def cpu_baseline(config, layer=None, q=None):
     """The oracle, as it stands, on a bounded sample: the first layer of the workload with the token
-    count cut so that the run takes roughly 10-30 s of CPU work."""
+    count cut so that the run takes roughly 10-30 s of CPU work.  With `layer` (the benchmark's own first
+    layer) the sample is the first rows of the tensors the timed region ran on, and the HIP path's results
+    on that sample are compared with the oracle's (same bar as the parity tests)."""
     import numpy as np
     import oracle
     from paper_2505_14669_amd import synth
     name, t, i, o = synth.CONFIGS[config]["layers"][0]
     budget = 3.6e11                       # multiply-adds the plain fp64 loops get through in 10-15 s on the box's 16 cores
     ts = int(min(t, max(32, (budget / (3.0 * i * o)) // 32 * 32)))
-    rng = np.random.Generator(np.random.PCG64(4242))
-    x = synth.f32_to_bf16(rng.standard_t(3.0, size=(ts, i)).astype(np.float32))
-    w = synth.f32_to_bf16(rng.standard_normal((o, i), dtype=np.float32) * np.float32(0.02))
-    dy = synth.f32_to_bf16(rng.standard_normal((ts, o), dtype=np.float32) * np.float32(1e-3))
+    if layer is not None:
+        import torch
+        host = lambda tensor: tensor.view(torch.int16).cpu().numpy().view(np.uint16)
+        x, w, dy = host(layer.x[:ts]), host(layer.w), host(layer.dy[:ts])
+    else:
+        rng = np.random.Generator(np.random.PCG64(4242))
+        x = synth.f32_to_bf16(rng.standard_t(3.0, size=(ts, i)).astype(np.float32))
+        w = synth.f32_to_bf16(rng.standard_normal((o, i), dtype=np.float32) * np.float32(0.02))
+        dy = synth.f32_to_bf16(rng.standard_normal((ts, o), dtype=np.float32) * np.float32(1e-3))
     t0 = time.perf_counter()
-    _, ctx = oracle.linear_fwd(x, w)
-    oracle.linear_bwd(dy, ctx, 0, 0)
+    y_ref, ctx = oracle.linear_fwd(x, w)
+    dx_ref, dw_ref = oracle.linear_bwd(dy, ctx, 0, 0)
     dt = time.perf_counter() - t0
     cores = oracle.num_threads()
     # the same code on one thread, on the first tokens/cores rows of the same sample (about the same wall time)
@@ -111,10 +118,25 @@ def cpu_baseline(config):
         dt1 = time.perf_counter() - t0
     finally:
         oracle.set_num_threads(cores)
-    return dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
-                sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s",
-                single_thread=dict(value=6.0 * t1 * i * o / dt1 / 1e12, unit="TFLOP/s", cores=1,
-                                   sample=f"the first {t1} tokens of that sample, {dt1:.1f} s"))
+    out = dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+               sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s",
+               single_thread=dict(value=6.0 * t1 * i * o / dt1 / 1e12, unit="TFLOP/s", cores=1,
+                                  sample=f"the first {t1} tokens of that sample, {dt1:.1f} s"))
+    if layer is not None and q is not None:
+        # the HIP path on the same rows, stochastic rounding with the same seed: relative Frobenius errors
+        f32 = dict(dtype=torch.float32, device=layer.x.device)
+        y, dx, dw = torch.empty((ts, o), **f32), torch.empty((ts, i), **f32), torch.empty((o, i), **f32)
+        ws_bytes = q.quartet_linear_workspace_bytes(ts, i, o)
+        ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=layer.x.device)
+        q.check(q.quartet_linear_fwd(layer.x[:ts], layer.w, ts, i, o, y, q.QUARTET_DTYPE_F32, layer.xq_codes, layer.xq_scales,
+                                     layer.x_mask, layer.wq_codes, layer.wq_scales, layer.w_mask))
+        q.check(q.quartet_linear_bwd(layer.dy[:ts], ts, i, o, layer.xq_codes, layer.xq_scales, layer.x_mask, layer.wq_codes,
+                                     layer.wq_scales, layer.w_mask, 0, 0, dx, dw, q.QUARTET_DTYPE_F32, ws, ws_bytes))
+        torch.cuda.synchronize()
+        rel = lambda got, want: float(np.linalg.norm(got.cpu().numpy().astype(np.float64) - want) / np.linalg.norm(want))
+        out["parity_on_sample"] = dict(y=rel(y, y_ref), dx=rel(dx, dx_ref), dw=rel(dw, dw_ref), tolerance=1e-5,
+                                       what="relative Frobenius error of the HIP path against the oracle on that sample")
+    return out
 
 
 def quant_sweep(q, torch, synth):
@@ -401,7 +423,7 @@ def main():
         torch.cuda.empty_cache()
         result["quantizer_sweep"] = quant_sweep(q, torch, synth)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args.config)
+        result["cpu_baseline"] = cpu_baseline(args.config, layers[0] if args.hadamard_block == 32 else None, q)
     print(json.dumps(result))
 
 
