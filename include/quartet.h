@@ -141,6 +141,17 @@ int quartet_requant_transpose_sr(const uint8_t *src_codes, const uint8_t *src_sc
                                  uint8_t *codes, uint8_t *scales, void *stream);
 
 /*
+ * The two operand quantizations of Algorithm 1 Forward in one launch: X [tokens x in] and W [out x in]
+ * (bf16 row-major, leading dimension in), in % 32 == 0.  The outputs are bit-identical to
+ *   quartet_quant_fwd(x, tokens, in, in, 0, xq_codes, xq_scales, x_mask) and
+ *   quartet_quant_fwd(w, out,    in, in, 0, wq_codes, wq_scales, w_mask);
+ * both masks are required.  quartet_linear_fwd runs this and the product.  Errors as for the two calls.
+ */
+int quartet_fwd_operands(const void *x_bf16, const void *w_bf16, int64_t tokens, int64_t in, int64_t out,
+                         uint8_t *xq_codes, uint8_t *xq_scales, uint32_t *x_mask,
+                         uint8_t *wq_codes, uint8_t *wq_scales, uint32_t *w_mask, void *stream);
+
+/*
  * The three operand conversions of Algorithm 1 Backward that do not depend on each other, in one
  * launch (dy [tokens x out] bf16 row-major; X_q [tokens x in] and W_q [out x in] as
  * quartet_quant_fwd wrote them; tokens, in, out all % 32 == 0):

@@ -24,7 +24,7 @@ QUARTET_ROUND_NEAREST = 1
 EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
     "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
-    "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_bwd_operands",
+    "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_fwd_operands", "quartet_bwd_operands",
     "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
     "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
@@ -52,6 +52,7 @@ _lib.quartet_sign_word.argtypes = [_u64]
 _lib.quartet_quant_fwd.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p]
 _lib.quartet_quant_bwd_sr.argtypes = [_p, _i64, _i64, _i64, _int, _u32, _u64, _u32, _int, _p, _p, _p]
 _lib.quartet_requant_transpose_sr.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u32, _int, _p, _p, _p]
+_lib.quartet_fwd_operands.argtypes = [_p, _p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p]
 _lib.quartet_bwd_operands.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _u32, _u64, _int, _p, _p, _p, _p, _p, _p, _p]
 _lib.quartet_mxfp4_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
 _lib.quartet_mxfp4_gemm_grad.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _p, _f, _p, _int, _i64, _p]
@@ -161,6 +162,13 @@ def quartet_requant_transpose_sr(src_codes, src_scales, rows, k, sign_word, seed
                                  scales, stream=None):
     return _lib.quartet_requant_transpose_sr(_ptr(src_codes), _ptr(src_scales), rows, k, sign_word, seed,
                                              stream_id, rounding, _ptr(codes), _ptr(scales), _stream(stream))
+
+
+def quartet_fwd_operands(x_bf16, w_bf16, tokens, in_features, out_features, xq_codes, xq_scales, x_mask, wq_codes,
+                         wq_scales, w_mask, stream=None):
+    return _lib.quartet_fwd_operands(_ptr(x_bf16), _ptr(w_bf16), tokens, in_features, out_features, _ptr(xq_codes),
+                                     _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales), _ptr(w_mask),
+                                     _stream(stream))
 
 
 def quartet_bwd_operands(dy_bf16, tokens, in_features, out_features, xq_codes, xq_scales, wq_codes, wq_scales, sign_word,

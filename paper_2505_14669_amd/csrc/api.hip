@@ -259,6 +259,25 @@ int quartet_requant_transpose_sr(const uint8_t* src_codes, const uint8_t* src_sc
                                               codes, scales, stream);
 }
 
+int quartet_fwd_operands(const void* x_bf16, const void* w_bf16, int64_t tokens, int64_t in, int64_t out,
+                         uint8_t* xq_codes, uint8_t* xq_scales, uint32_t* x_mask,
+                         uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask, void* stream) {
+    if (!x_bf16 || !w_bf16 || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask) return QUARTET_EINVAL;
+    if (!aligned16(x_bf16) || !aligned16(w_bf16) || !aligned16(xq_codes) || !aligned16(wq_codes) || !aligned16(x_mask) ||
+        !aligned16(w_mask))
+        return QUARTET_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(xq_scales) | reinterpret_cast<uintptr_t>(wq_scales)) & 3u) return QUARTET_EINVAL;
+    if (in < 0 || (in % 32) != 0) return QUARTET_EINVAL;
+    int rc = check_quant_shape(tokens, in, in, 0);
+    if (!rc) rc = check_quant_shape(out, in, in, 0);
+    if (rc) return rc;
+    SrParams p = make_params(1u, nullptr, 0u, 0u);
+    ProfileScope prof(QUARTET_KIND_QUANT_FWD, (hipStream_t)stream);
+    hipError_t e = quartet::launch_fwd_operands(x_bf16, tokens, w_bf16, out, in, xq_codes, xq_scales, x_mask, wq_codes, wq_scales,
+                                                w_mask, p, (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
 int quartet_bwd_operands(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
                          const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
                          uint32_t sign_word, uint64_t seed, int rounding,
@@ -432,10 +451,16 @@ int quartet_linear_fwd_block(const void* x_bf16, const void* w_bf16, int64_t tok
         return QUARTET_EINVAL;
     if (block_groups(hadamard_block) == 0u) return QUARTET_EINVAL;
     if (tokens < 0 || in < 0 || out < 0 || (in % hadamard_block) != 0) return QUARTET_EINVAL;
-    int rc = quartet_quant_fwd_block(x_bf16, tokens, in, in, 0, hadamard_block, xq_codes, xq_scales, x_mask, stream);
-    if (rc) return rc;
-    rc = quartet_quant_fwd_block(w_bf16, out, in, in, 0, hadamard_block, wq_codes, wq_scales, w_mask, stream);
-    if (rc) return rc;
+    int rc;
+    if (hadamard_block == 32) {
+        rc = quartet_fwd_operands(x_bf16, w_bf16, tokens, in, out, xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask, stream);
+        if (rc) return rc;
+    } else {
+        rc = quartet_quant_fwd_block(x_bf16, tokens, in, in, 0, hadamard_block, xq_codes, xq_scales, x_mask, stream);
+        if (rc) return rc;
+        rc = quartet_quant_fwd_block(w_bf16, out, in, in, 0, hadamard_block, wq_codes, wq_scales, w_mask, stream);
+        if (rc) return rc;
+    }
     return quartet_mxfp4_gemm(xq_codes, xq_scales, wq_codes, wq_scales, tokens, out, in, 1.0f, y, y_dtype,
                               out, stream);
 }

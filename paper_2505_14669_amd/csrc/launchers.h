@@ -19,6 +19,10 @@ hipError_t launch_quant(int mode, const void* x, int64_t rows, int64_t k, int64_
 hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const uint8_t* src_scales,
                                     int64_t rows, int64_t k, const SrParams& p, uint8_t* codes,
                                     uint8_t* scales, hipStream_t st);
+// X [tokens x in] and W [out x in] quantized by the forward rule in one launch (Hadamard block 32, masks written)
+hipError_t launch_fwd_operands(const void* x, int64_t tokens, const void* w, int64_t out, int64_t in, uint8_t* xq_codes,
+                               uint8_t* xq_scales, uint32_t* x_mask, uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
+                               const SrParams& p, hipStream_t st);
 // dy^T quantized along the tokens, X_q and W_q re-quantized along their other dimension: one launch (Hadamard block 32)
 hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t in, int64_t out,
                                const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,

@@ -138,18 +138,17 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
 // leave as whole 32-byte runs of the scale tiles (8 rows x one dword), never as single bytes.
 // BIG: the Hadamard block spans p.nb = 2, 4 or 8 groups; they sit in consecutive lanes (a row's groups
 // start at a multiple of 8 in every block), so the group-combining stages are lane exchanges.
+// bid: the block's number in its matrix; stage (16 KB), s_scale (256 B): the block's LDS
 template <int MODE, bool MASK, bool BIG>
-__global__ void __launch_bounds__(256)
-quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
-                 uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
-                 SrParams p, uint32_t k_blocks, FastDiv div_k_blocks) {
-    __shared__ uint4 stage[4][256];
-    __shared__ uint32_t s_scale[64];
+__device__ __forceinline__ void quant_row_tile(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
+                                               uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
+                                               const SrParams& p, uint32_t k_blocks, FastDiv div_k_blocks, uint32_t bid,
+                                               uint4 (*stage)[256], uint32_t* s_scale) {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     // consecutive blocks walk along K inside the same 8 rows, so the blocks in flight cover one
     // contiguous stretch of the input
-    const uint32_t row_set = fast_div(blockIdx.x, div_k_blocks);
-    const uint32_t row0 = row_set * 8u, kq0 = (blockIdx.x - row_set * k_blocks) * 4u, kqs = (gk + 7u) >> 3;
+    const uint32_t row_set = fast_div(bid, div_k_blocks);
+    const uint32_t row0 = row_set * 8u, kq0 = (bid - row_set * k_blocks) * 4u, kqs = (gk + 7u) >> 3;
     // The block's rows through a buffer resource that ends with the last element of its last row:
     // rows past the matrix read as zeros without a predicate.  Groups past k inside a row read
     // whatever lies there (the row's padding or the next row); their results are never stored.
@@ -200,6 +199,39 @@ quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int
             }
         }
     }
+}
+
+template <int MODE, bool MASK, bool BIG>
+__global__ void __launch_bounds__(256)
+quant_row_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, int64_t ldx,
+                 uint4* __restrict__ codes, uint8_t* __restrict__ scales, uint32_t* __restrict__ mask,
+                 SrParams p, uint32_t k_blocks, FastDiv div_k_blocks) {
+    __shared__ uint4 stage[4][256];
+    __shared__ uint32_t s_scale[64];
+    quant_row_tile<MODE, MASK, BIG>(x, rows, gk, ldx, codes, scales, mask, p, k_blocks, div_k_blocks, blockIdx.x, stage, s_scale);
+}
+
+// Two matrices with the same inner dimension in one launch (Algorithm 1 Forward quantizes X and W, and neither depends
+// on the other): blocks [0, split) work on the first, the rest on the second.  A weight-sized matrix alone fills the chip
+// for a few microseconds only, most of it ramp-up and drain; behind the activations' blocks it costs its bytes.
+struct RowMatrix {
+    const uint16_t* x;
+    uint32_t rows;
+    int64_t ldx;
+    uint4* codes;
+    uint8_t* scales;
+    uint32_t* mask;
+};
+
+template <int MODE, bool MASK>
+__global__ void __launch_bounds__(256)
+quant_row_pair_kernel(RowMatrix a, RowMatrix b, uint32_t split, uint32_t gk, SrParams p, uint32_t k_blocks, FastDiv div_k_blocks) {
+    __shared__ uint4 stage[4][256];
+    __shared__ uint32_t s_scale[64];
+    const bool second = blockIdx.x >= split;
+    const RowMatrix& m = second ? b : a;
+    quant_row_tile<MODE, MASK, false>(m.x, m.rows, gk, m.ldx, m.codes, m.scales, m.mask, p, k_blocks, div_k_blocks,
+                                      second ? blockIdx.x - split : blockIdx.x, stage, s_scale);
 }
 
 // Store phase of the transposed kernels: the tile's codes, scale bytes and mask words gathered in LDS
@@ -847,6 +879,21 @@ hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const ui
     dim3 grid((uint32_t)((rows + 255) / 256), (uint32_t)((k + 255) / 256));
     if (mode == kBwdRtn) launch_requant_nb<kBwdRtn>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
     else launch_requant_nb<kBwdSr>(grid, st, src_codes, src_scales, rows, k, p, codes, scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_operands(const void* x, int64_t tokens, const void* w, int64_t out, int64_t in, uint8_t* xq_codes,
+                               uint8_t* xq_scales, uint32_t* x_mask, uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
+                               const SrParams& p, hipStream_t st) {
+    if (in == 0 || (tokens == 0 && out == 0)) return hipSuccess;
+    const uint32_t gk = (uint32_t)(in / 32);
+    const uint32_t k_blocks = (gk + 31) / 32;
+    const uint64_t na = (uint64_t)((tokens + 7) / 8) * k_blocks, nb = (uint64_t)((out + 7) / 8) * k_blocks;
+    if (na + nb >= ((uint64_t)1 << 31)) return hipErrorInvalidValue;
+    RowMatrix a = {(const uint16_t*)x, (uint32_t)tokens, in, (uint4*)xq_codes, xq_scales, x_mask};
+    RowMatrix b = {(const uint16_t*)w, (uint32_t)out, in, (uint4*)wq_codes, wq_scales, w_mask};
+    hipLaunchKernelGGL((quant_row_pair_kernel<kFwd, true>), dim3((uint32_t)(na + nb)), dim3(256), 0, st, a, b, (uint32_t)na, gk, p,
+                       k_blocks, make_fast_div(k_blocks));
     return hipGetLastError();
 }
 

@@ -62,6 +62,19 @@ def requant_transpose_sr(src_codes, src_scales, sign_word, seed, stream_id, roun
     return to_host(codes, np.uint8), scales_from_tiled(to_host(scales, np.uint8), rows, k)
 
 
+def fwd_operands(x_u16, w_u16):
+    """quartet_fwd_operands on host arrays; returns (codes, scales row-major, mask) of X and of W."""
+    t, i = x_u16.shape
+    o = w_u16.shape[0]
+    outs = []
+    for r in (t, o):
+        outs += [dev_empty((r, i // 2), np.uint8, 0xEE), dev_empty((max(q.quartet_scale_bytes(r, i), 4),), np.uint8, 0xFF),
+                 dev_empty((r, i // 32), np.uint32, 0x5A5A5A5A)]
+    q.check(q.quartet_fwd_operands(to_dev(x_u16), to_dev(w_u16), t, i, o, *outs))
+    return [(to_host(outs[3 * n], np.uint8), scales_from_tiled(to_host(outs[3 * n + 1], np.uint8), r, i),
+             to_host(outs[3 * n + 2], np.uint32)) for n, r in enumerate((t, o))]
+
+
 def bwd_operands(dy_u16, xq_codes, xq_scales, wq_codes, wq_scales, sign_word, seed, rounding=0):
     """quartet_bwd_operands on host arrays (scales row-major); returns (codes, scales) of dy^T, X_q^T, W_q^T."""
     t, o = dy_u16.shape

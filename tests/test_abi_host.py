@@ -59,6 +59,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert q.quartet_quant_bwd_sr(P, 4, 64, 64, 0, 0, 0, 0, 2, P, P, 0) == E  # rounding
     assert q.quartet_quant_bwd_sr(P, 4, 64, 64, 0, 0, 0, 0, 0, None, P, 0) == E
     assert q.quartet_requant_transpose_sr(P, P, 48, 64, 0, 0, 0, 0, P, P, 0) == E  # rows % 32
+    assert q.quartet_fwd_operands(P, P, 4, 48, 8, P, P, P, P, P, P, 0) == E                          # in % 32
+    assert q.quartet_fwd_operands(P, P, 4, 64, 8, P, P, None, P, P, P, 0) == E                        # both masks required
+    assert q.quartet_fwd_operands(P, P + 2, 4, 64, 8, P, P, P, P, P, P, 0) == E                       # alignment
+    assert q.quartet_fwd_operands(P, P, 2 ** 40, 2 ** 20, 8, P, P, P, P, P, P, 0) == q.QUARTET_ENOTSUP
     assert q.quartet_bwd_operands(P, 64, 64, 48, P, P, P, P, 0, 0, 0, P, P, P, P, P, P, 0) == E     # out % 32
     assert q.quartet_bwd_operands(P, 64, 64, 64, P, P, P, P, 0, 0, 2, P, P, P, P, P, P, 0) == E     # rounding
     assert q.quartet_bwd_operands(P, 64, 64, 64, P, P, P, None, 0, 0, 0, P, P, P, P, P, P, 0) == E
@@ -90,6 +94,7 @@ def test_empty_problems_are_accepted_without_a_gpu():
     assert q.quartet_quant_bwd_sr(P, 0, 64, 64, 0, 0, 0, 0, 0, P, P, 0) == 0
     assert q.quartet_mxfp4_gemm(P, P, P, P, 0, 8, 64, 1.0, P, 0, 8, 0) == 0
     assert q.quartet_bwd_operands(P, 0, 0, 0, P, P, P, P, 0, 0, 0, P, P, P, P, P, P, 0) == 0
+    assert q.quartet_fwd_operands(P, P, 0, 64, 0, P, P, P, P, P, P, 0) == 0
     assert q.quartet_grad_epilogue(P, None, 0, 64, 1.0, P, 0, 0) == 0
 
 

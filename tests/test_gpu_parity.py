@@ -235,6 +235,20 @@ def test_grad_epilogue(G, shape):
     assert np.array_equal(got4, synth.f32_to_bf16(want))
 
 
+@pytest.mark.parametrize("tio", [(1, 32, 1), (50, 160, 7), (13, 1056, 300), (264, 2080, 96), (8, 64, 1000)])
+def test_fwd_operands_match_the_two_quantizations(G, tio):
+    # Algorithm 1 Forward: QuEST(H X) and QuEST(H W) from one launch, bit for bit the oracle's forward quantizer on each
+    t, i, o = tio
+    x = synth.small_matrix(400 + t, t, i, "outliers")
+    w = synth.small_matrix(401 + o, o, i, "normal", 0.02)
+    got = G.fwd_operands(x, w)
+    for name, g, src in (("X", got[0], x), ("W", got[1], w)):
+        want = oracle.quant_fwd(src)
+        same(g[0], want[0], f"{name} codes")
+        same(g[1], want[1], f"{name} scales")
+        same(g[2], want[2], f"{name} mask")
+
+
 @pytest.mark.parametrize("tio", [(32, 32, 32), (96, 160, 224), (288, 320, 352), (800, 544, 1056), (1024, 1280, 256)])
 @pytest.mark.parametrize("rounding", [0, 1])
 def test_bwd_operands_match_the_three_conversions(G, tio, rounding):
