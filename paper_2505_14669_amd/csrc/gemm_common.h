@@ -27,7 +27,7 @@ constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here 
 // group, so with FUSED the gradient epilogue of Algorithm 1 Backward,
 // D = alpha * H_32_along_n(acc . M), is applied on the way: mask select, butterflies of stride 1
 // and 2 inside the lane and of stride 4, 8, 16 between the 8 lanes (the lower partner ends up with a + b,
-// the upper with a - b, bit-identical to the in-register transform: see QUARTET_BUTTERFLY4), the normalization,
+// the upper with a - b, bit-identical to the in-register transform: see QUARTET_BUTTERFLIES_ACROSS), the normalization,
 // then the scale.  Lane i of the 8 holds 4-column chunk i ^ (i & 4 ? 3 : 0), which makes the three
 // partners lane ^ 1, lane ^ 2 and 7 - lane: all reachable by DPP, none through LDS.
 // wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
@@ -39,18 +39,22 @@ constexpr uint32_t kEpiStride = 36;   // floats per LDS row (144 bytes: 16-byte 
 // stages in which it was the upper one); the partners of every stage have been upper equally often before it, so the signs
 // cancel inside each stage, and the normalization constant takes the final sign back (epilogue_norm).  Rounding is symmetric
 // in sign: the bits are those of a + b and a - b.
-// The instruction is written out (the compiler keeps a separate lane move in front of a fused multiply-add); a DPP operand
-// must not be read in the two issue slots after a vector instruction wrote it, hence the s_nop in front of the four.
-#define QUARTET_BUTTERFLY4(CTRL_TEXT, v0, v1, v2, v3, t)                                                          \
-    asm("s_nop 1\n\t"                                                                                              \
-        "v_fmac_f32_dpp %0, %0, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"                       \
-        "v_fmac_f32_dpp %1, %1, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"                       \
-        "v_fmac_f32_dpp %2, %2, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"                       \
-        "v_fmac_f32_dpp %3, %3, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1"                           \
-        : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3) : "v"(t))
-#define QUARTET_DPP_XOR1 "quad_perm:[1,0,3,2]"
-#define QUARTET_DPP_XOR2 "quad_perm:[2,3,0,1]"
-#define QUARTET_DPP_HALF_MIRROR "row_half_mirror"
+// The instruction is written out (the compiler keeps a separate lane move in front of a fused multiply-add).  A DPP
+// operand must not be read in the two issue slots after a vector instruction wrote it: hence the s_nop in front, and the
+// three stages of the four values in one block, where every value is read four instructions after it was written.
+#define QUARTET_DPP_TAIL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+#define QUARTET_BUTTERFLY_STAGE(CTRL_TEXT, T)                           \
+    "v_fmac_f32_dpp %0, %0, " T " " CTRL_TEXT QUARTET_DPP_TAIL            \
+    "v_fmac_f32_dpp %1, %1, " T " " CTRL_TEXT QUARTET_DPP_TAIL            \
+    "v_fmac_f32_dpp %2, %2, " T " " CTRL_TEXT QUARTET_DPP_TAIL            \
+    "v_fmac_f32_dpp %3, %3, " T " " CTRL_TEXT QUARTET_DPP_TAIL
+// strides 4, 8, 16 of a 32-column slice held as four values in each of eight lanes: partners lane ^ 1, lane ^ 2, 7 - lane
+#define QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, t4, t8, t16)                        \
+    asm("s_nop 1\n\t"                                                                   \
+        QUARTET_BUTTERFLY_STAGE("quad_perm:[1,0,3,2]", "%4")                            \
+        QUARTET_BUTTERFLY_STAGE("quad_perm:[2,3,0,1]", "%5")                            \
+        QUARTET_BUTTERFLY_STAGE("row_half_mirror", "%6")                                \
+        : "+v"(v0), "+v"(v1), "+v"(v2), "+v"(v3) : "v"(t4), "v"(t8), "v"(t16))
 // v * (+-norm) with the lane's sign taken back; the added +0 turns a zero of either sign into +0, which is what sums and
 // differences of the unsigned values give (x - x = +0, and no -0 enters: masked elements and empty sums are +0).
 __device__ __forceinline__ float epilogue_norm(float v, float signed_norm) { return __builtin_fmaf(v, signed_norm, 0.0f); }
@@ -63,7 +67,7 @@ __device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf
     constexpr uint32_t ITERS = TM * 4;   // 8 rows per pass
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
     const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
-    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLY4
+    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLIES_ACROSS
     const float snorm = ((c ^ (c >> 1) ^ (c >> 2)) & 1u) ? -kInvSqrt32 : kInvSqrt32;
     const bool wide = FULL || (ldd & 3u) == 0u;   // every 4-column chunk starts 16-byte (fp32) / 8-byte (bf16) aligned
     const uint32_t mask_ld = n >> 5;
@@ -101,9 +105,7 @@ __device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf
                 v3 = __uint_as_float(__float_as_uint(v3) & (uint32_t)((bits << 28) >> 31));
                 const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
                 v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
-                QUARTET_BUTTERFLY4(QUARTET_DPP_XOR1, v0, v1, v2, v3, up4);           // stride 4
-                QUARTET_BUTTERFLY4(QUARTET_DPP_XOR2, v0, v1, v2, v3, up8);           // stride 8
-                QUARTET_BUTTERFLY4(QUARTET_DPP_HALF_MIRROR, v0, v1, v2, v3, up16);   // stride 16
+                QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, up4, up8, up16);           // strides 4, 8, 16
                 v0 = epilogue_norm(v0, snorm); v1 = epilogue_norm(v1, snorm); v2 = epilogue_norm(v2, snorm); v3 = epilogue_norm(v3, snorm);
             }
             v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
@@ -150,7 +152,7 @@ __device__ __forceinline__ void store_tile_body_rows(v16f (&acc)[TM][TN], float*
     constexpr uint32_t STRIDE = TN * 32u + 4u;   // floats per LDS row: 16-byte aligned, rows shifted by 4 banks
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
     const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
-    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLY4
+    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLIES_ACROSS
     const bool wide = FULL || (ldd & 3u) == 0u;
     const uint32_t mask_ld = n >> 5;
 #pragma unroll
@@ -220,9 +222,7 @@ __device__ __forceinline__ void store_tile_body_rows(v16f (&acc)[TM][TN], float*
                 if (FUSED) {
                     const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
                     v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
-                    QUARTET_BUTTERFLY4(QUARTET_DPP_XOR1, v0, v1, v2, v3, up4);           // stride 4
-                    QUARTET_BUTTERFLY4(QUARTET_DPP_XOR2, v0, v1, v2, v3, up8);           // stride 8
-                    QUARTET_BUTTERFLY4(QUARTET_DPP_HALF_MIRROR, v0, v1, v2, v3, up16);   // stride 16
+                    QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, up4, up8, up16);           // strides 4, 8, 16
                     v0 = epilogue_norm(v0, norm); v1 = epilogue_norm(v1, norm); v2 = epilogue_norm(v2, norm); v3 = epilogue_norm(v3, norm);
                 }
                 v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
