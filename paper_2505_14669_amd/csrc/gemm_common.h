@@ -48,9 +48,11 @@ constexpr uint32_t kEpiStride = 36;   // floats per LDS row (144 bytes: 16-byte 
     "v_fmac_f32_dpp %1, %1, " T " " CTRL_TEXT QUARTET_DPP_TAIL            \
     "v_fmac_f32_dpp %2, %2, " T " " CTRL_TEXT QUARTET_DPP_TAIL            \
     "v_fmac_f32_dpp %3, %3, " T " " CTRL_TEXT QUARTET_DPP_TAIL
-// strides 4, 8, 16 of a 32-column slice held as four values in each of eight lanes: partners lane ^ 1, lane ^ 2, 7 - lane
+// strides 4, 8, 16 of a 32-column slice held as four values in each of eight lanes: partners lane ^ 1, lane ^ 2, 7 - lane.
+// volatile: the block reads other lanes, so it must stay where all lanes of a row group are active (not be moved into the
+// predicated store that uses its results).
 #define QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, t4, t8, t16)                        \
-    asm("s_nop 1\n\t"                                                                   \
+    asm volatile("s_nop 1\n\t"                                                              \
         QUARTET_BUTTERFLY_STAGE("quad_perm:[1,0,3,2]", "%4")                            \
         QUARTET_BUTTERFLY_STAGE("quad_perm:[2,3,0,1]", "%5")                            \
         QUARTET_BUTTERFLY_STAGE("row_half_mirror", "%6")                                \
