@@ -94,21 +94,45 @@ template <> __device__ __forceinline__ float lane_xor<4>(float x) {
     return u2f((uint32_t)__builtin_amdgcn_ds_swizzle((int)f2u(x), 0x101F /* bit mode: and 0x1F, or 0, xor 4 */));
 }
 
-// One group-combining stage when the groups of a block sit in consecutive lanes (group j of the block
-// in lane l with l % nb == j): the lower lane of a pair keeps a + b, the upper one a - b, a being the
-// lower lane's value.  Every lane of the wave must take part.
+// One group-combining stage when the groups of a block sit in consecutive lanes (group j of the block in lane l with
+// l % nb == j).  Both lanes of a pair form partner * t + own in one fused multiply-add, t = +1 in the lower lane (a + b),
+// t = -1 in the upper lane (-(a - b)): multiplying by +-1 is exact and rounding is symmetric in sign, so the bits are those
+// of a + b and a - b, and a lane's values carry the sign (-1)^(stages in which it was the upper one).  The partners of
+// every stage have been upper equally often before it; the transforms that follow are linear; block_norm_signed() takes
+// the sign back in the final normalization.  For partners inside a quad the lane exchange rides in the instruction
+// (written out: the compiler keeps a separate lane move; a DPP operand must not be read in the two issue slots after a
+// vector instruction wrote it, hence the s_nop in front of four independent ones).  Every lane of the wave must take part.
+#define QUARTET_STAGE4_DPP(CTRL_TEXT, a, b, c, d, t)                                                  \
+    asm volatile("s_nop 1\n\t"                                                                         \
+                 "v_fmac_f32_dpp %0, %0, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"  \
+                 "v_fmac_f32_dpp %1, %1, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"  \
+                 "v_fmac_f32_dpp %2, %2, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"  \
+                 "v_fmac_f32_dpp %3, %3, %4 " CTRL_TEXT " row_mask:0xf bank_mask:0xf bound_ctrl:1"       \
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "v"(t))
 template <int XOR> __device__ __forceinline__ void cross_lane_stage(float (&v)[32], uint32_t lane) {
-    const bool upper = (lane & (uint32_t)XOR) != 0u;
+    const float t = (lane & (uint32_t)XOR) ? -1.0f : 1.0f;
+    if (XOR == 4) {
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-        const float other = lane_xor<XOR>(v[i]);
-        v[i] = upper ? other - v[i] : v[i] + other;
+        for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(lane_xor<4>(v[i]), t, v[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; i += 4) {
+            if (XOR == 1) QUARTET_STAGE4_DPP("quad_perm:[1,0,3,2]", v[i], v[i + 1], v[i + 2], v[i + 3], t);
+            else QUARTET_STAGE4_DPP("quad_perm:[2,3,0,1]", v[i], v[i + 1], v[i + 2], v[i + 3], t);
+        }
     }
 }
 __device__ __forceinline__ void cross_lane_stages(float (&v)[32], uint32_t lane, uint32_t nb) {
     if (nb > 1u) cross_lane_stage<1>(v, lane);
     if (nb > 2u) cross_lane_stage<2>(v, lane);
     if (nb > 4u) cross_lane_stage<4>(v, lane);
+}
+// fl(1/sqrt(32 nb)) with the sign the lane's values carry after cross_lane_stages.  Use it as
+// fma(v, block_norm_signed, +0): the added +0 makes a zero of either sign +0, which is what the sums and differences of
+// the unsigned values give.
+__device__ __forceinline__ float block_norm_signed(uint32_t nb, uint32_t lane) {
+    const uint32_t j = lane & (nb - 1u);
+    return ((j ^ (j >> 1) ^ (j >> 2)) & 1u) ? -block_norm(nb) : block_norm(nb);
 }
 
 // Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> four 32-bit words.

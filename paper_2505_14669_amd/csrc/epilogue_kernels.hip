@@ -46,9 +46,9 @@ grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t
     if (BIG) {
         cross_lane_stages(v, lane, nb);
         fwht32_unscaled(v);
-        const float c = block_norm(nb);
+        const float c = block_norm_signed(nb, lane);
 #pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
+        for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);
     } else {
         fwht32(v);
     }

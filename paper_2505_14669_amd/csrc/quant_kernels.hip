@@ -62,9 +62,9 @@ __device__ __forceinline__ void quantize_group_lanes(float (&v)[32], const SrPar
     }
     cross_lane_stages(v, lane, p.nb);
     fwht32_unscaled(v);
-    const float c = block_norm(p.nb);
+    const float c = block_norm_signed(p.nb, lane);
 #pragma unroll
-    for (int i = 0; i < 32; ++i) v[i] = v[i] * c;
+    for (int i = 0; i < 32; ++i) v[i] = __builtin_fmaf(v[i], c, 0.0f);
     encode_group<MODE>(v, p, q_base, codes, scale_byte, mask_word);
 }
 
