@@ -613,7 +613,7 @@ struct BwdOperandsMap {
 };
 
 template <int MODE>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, 4)   // 128 registers: four blocks per CU (their LDS, 4 x 36 KB, fits too)
 bwd_operands_kernel(const uint16_t* __restrict__ dy, uint32_t t_rows, uint32_t t_k, int64_t t_ldx,
                     uint8_t* __restrict__ t_codes, uint8_t* __restrict__ t_scales, SrParams t_p,
                     const uint8_t* __restrict__ x_src_codes, const uint8_t* __restrict__ x_src_scales, uint32_t x_rows, uint32_t x_k,
