@@ -34,9 +34,6 @@ def parse():
     ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
     ap.add_argument("--fp8-compare", action="store_true",
                     help="also time the library's own MXFP8 GEMM and quantizer on the workload's shapes (the paper's comparison format)")
-    ap.add_argument("--vendor-compare", action="store_true",
-                    help="also time the vendor library's MXFP4 GEMM (hipBLASLt) next to quartet_mxfp4_gemm on the "
-                         "workload's GEMM shapes (child process; takes a few minutes, most of it the vendor library's start-up)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-kind time breakdown to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 1 GiB elementwise copy kernel (torch.mul by 1), the known-size "
@@ -177,31 +174,6 @@ def quant_sweep(q, torch, synth):
                             GBps_best=round(bpe * r * c / best / 1e6, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
         del xs, codes, scales, mask
     return out
-
-
-def vendor_compare(layers):
-    """Context, not a target: hipBLASLt's MXFP4 GEMM (E2M1 operands, E8M0 scale per 32 along K, fp32 result; the best of
-    the first algorithms its heuristic returns) and quartet_mxfp4_gemm on the same buffers with uniformly random codes,
-    for every distinct GEMM shape of the workload; totals weighted by how often a shape occurs in a step."""
-    import collections
-    import subprocess
-    from paper_2505_14669_amd import build as qbuild
-    if not os.path.exists(qbuild.VENDOR_TOOL):
-        raise RuntimeError("vendor_mxfp4_gemm is not built: run python -m paper_2505_14669_amd.build")
-    count = collections.Counter()
-    for l in layers:
-        for shape in ((l.t, l.o, l.i), (l.t, l.i, l.o), (l.o, l.i, l.t)):     # forward, dX, dW
-            count[shape] += 1
-    shapes = sorted(count)
-    cmd = [qbuild.VENDOR_TOOL, qbuild.LIB] + [str(v) for sh in shapes for v in sh]
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, text=True, check=True, timeout=900)
-    rows = [json.loads(line) for line in proc.stdout.splitlines() if line.startswith("{")]
-    flop = sum(2.0 * r["m"] * r["n"] * r["k"] * count[(r["m"], r["n"], r["k"])] for r in rows)
-    t_vendor = sum(r["vendor_ms"] * count[(r["m"], r["n"], r["k"])] for r in rows)
-    t_ours = sum(r["quartet_ms"] * count[(r["m"], r["n"], r["k"])] for r in rows)
-    return {"library": "hipBLASLt (ROCm of this image)", "data": "uniformly random codes, scale bytes 120..133",
-            "shapes": rows, "vendor_tflops": round(flop / t_vendor / 1e9, 1), "quartet_tflops": round(flop / t_ours / 1e9, 1),
-            "quartet_over_vendor": round(t_vendor / t_ours, 3)}
 
 
 def fp8_compare(q, torch, layers):
@@ -416,8 +388,6 @@ def main():
         del src, dst
     if args.fp8_compare:
         result["fp8_comparison"] = fp8_compare(q, torch, layers)
-    if args.vendor_compare:
-        result["vendor_comparison"] = vendor_compare(layers)
     if args.quant_sweep:
         del layers, ws
         torch.cuda.empty_cache()

@@ -25,7 +25,7 @@ EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
     "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_fwd_operands", "quartet_bwd_operands",
-    "quartet_mxfp4_gemm", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
+    "quartet_mxfp4_gemm", "quartet_debug_set_gemm_plan", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
     "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
     "quartet_requant_transpose_sr_block", "quartet_mxfp4_gemm_grad_block", "quartet_grad_epilogue_block", "quartet_linear_fwd_block",
@@ -55,6 +55,7 @@ _lib.quartet_requant_transpose_sr.argtypes = [_p, _p, _i64, _i64, _u32, _u64, _u
 _lib.quartet_fwd_operands.argtypes = [_p, _p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _p]
 _lib.quartet_bwd_operands.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _u32, _u64, _int, _p, _p, _p, _p, _p, _p, _p]
 _lib.quartet_mxfp4_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
+_lib.quartet_debug_set_gemm_plan.argtypes = [_int, _int]
 _lib.quartet_mxfp4_gemm_grad.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _p, _f, _p, _int, _i64, _p]
 _lib.quartet_mxfp8_quant.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p]
 _lib.quartet_mxfp8_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
@@ -182,6 +183,10 @@ def quartet_bwd_operands(dy_bf16, tokens, in_features, out_features, xq_codes, x
 def quartet_mxfp4_gemm(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, d_dtype, ldd, stream=None):
     return _lib.quartet_mxfp4_gemm(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
                                    alpha, _ptr(d), d_dtype, ldd, _stream(stream))
+
+
+def quartet_debug_set_gemm_plan(variant, band_height):
+    return _lib.quartet_debug_set_gemm_plan(variant, band_height)
 
 
 def quartet_mxfp4_gemm_grad(a_codes, a_scales, b_codes, b_scales, m, n, k, mask, scale, d, d_dtype, ldd, stream=None):

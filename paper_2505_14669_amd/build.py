@@ -7,7 +7,6 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquartet.so")
-VENDOR_TOOL = os.path.join(HERE, "vendor_mxfp4_gemm")
 OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "quant_kernels.hip", "gemm_kernels.hip", "epilogue_kernels.hip", "fp8_kernels.hip"]
 
@@ -38,9 +37,6 @@ def build(verbose=False):
                 print(out)
     objs = [o for o, _ in results]
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
-    # context tool of bench.py --vendor-compare: the vendor library's MXFP4 GEMM next to quartet_mxfp4_gemm
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", os.path.join(CSRC, "vendor_mxfp4_gemm.cpp"),
-                    "-o", VENDOR_TOOL, "-lhipblaslt", "-ldl"], check=True)
     return LIB
 
 

@@ -354,6 +354,12 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
+int quartet_debug_set_gemm_plan(int variant, int band_height) {
+    if (variant < -1 || variant > 2 || band_height < 0 || band_height > 64) return QUARTET_EINVAL;
+    quartet::set_gemm_plan(variant, band_height);
+    return QUARTET_OK;
+}
+
 int quartet_mxfp4_gemm_grad(const uint8_t* a_codes, const uint8_t* a_scales,
                             const uint8_t* b_codes, const uint8_t* b_scales,
                             int64_t m, int64_t n, int64_t k, const uint32_t* mask, float scale,

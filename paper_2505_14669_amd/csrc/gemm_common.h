@@ -287,10 +287,6 @@ __device__ __forceinline__ v4i_t make_rsrc_words(const void* base, uint32_t byte
 // 16 bytes per lane from the buffer resource at byte offset voff (past the end: zeros) to LDS byte
 // address lds_base + 16 * lane.  lds_base must be wave-uniform.  Completion is counted by vmcnt.
 __device__ __forceinline__ void lds_direct_load16(v4i_t rsrc, uint32_t voff, uint32_t lds_base) {
-#ifdef QUARTET_TIMING_WITHOUT_LOADS   // timing experiments only: results are meaningless
-    (void)rsrc; (void)voff; (void)lds_base;
-    return;
-#endif
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory");
 }

@@ -18,9 +18,16 @@
 #include "gemm_common.h"
 #include "launchers.h"
 
-#include <stdlib.h>
-
 namespace quartet {
+
+// Test / tuning override of the kernel choice (quartet_debug_set_gemm_plan): -1 / 0 = the size heuristics below.
+static int g_forced_variant = -1;
+static int g_forced_band = 0;
+
+void set_gemm_plan(int variant, int band_height) {
+    g_forced_variant = variant;
+    g_forced_band = band_height;
+}
 
 template <int S>
 __device__ __forceinline__ v16f mfma_fp4(const uint4& a, const uint4& b, v16f c, uint32_t sa, uint32_t sb) {
@@ -429,10 +436,8 @@ static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const
     // Height of the bands of tile rows an XCD walks (its 32 CUs then work on gm x 32/gm tiles at a time).  Measured on
     // the Llama shapes: 4 is never worse than 8 (+0-7 %); with 40 or more tile columns 2 is better still
     // (16384 x 11008 x 4096: 3.39 against 2.96 PFLOP/s with 8), unless the tile rows do not pair up.
-    // QUARTET_GEMM_BAND overrides (tuning aid).
-    const char* e = getenv("QUARTET_GEMM_BAND");
     uint32_t gm = (tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
-    if (e && *e && atoi(e) > 0) gm = (uint32_t)atoi(e);
+    if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
     hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
                        tiles_m, tiles_n, gm, nb);
@@ -452,15 +457,14 @@ static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, co
 // Variants: 0 = 256x256 block, ring of 4 LDS stages, two stages per trip with the scale byte picked by
 // op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too small to fill the chip with
 // big tiles); 2 = 256x256 block, two LDS buffers.
-// QUARTET_GEMM_VARIANT overrides the size heuristic (tuning aid).
+// set_gemm_plan overrides the size heuristic (tests reach every variant through it).
 // fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
 // be null = all ones), n % (32 nb) == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                        int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     if (m == 0 || n == 0) return hipSuccess;
-    const char* env = getenv("QUARTET_GEMM_VARIANT");
-    int variant = (env && *env) ? atoi(env) : -1;
+    int variant = g_forced_variant;
     if (variant < 0) {
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
         // measured crossover on an MI355X: 128 big tiles (4096 x 2048 x 2048) are 8 % faster as 128 x 128 tiles,

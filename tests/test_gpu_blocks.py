@@ -106,14 +106,12 @@ def test_grad_epilogue_block(G, block):
 
 
 @pytest.fixture(params=["auto", "0", "1", "2"])
-def gemm_variant(request, monkeypatch):
+def gemm_variant(request, G):
     # every tile shape of the GEMM kernel; a block of 128 columns does not fit the 64-column wave tile of variant 1,
     # the library switches to variant 2 by itself
-    if request.param == "auto":
-        monkeypatch.delenv("QUARTET_GEMM_VARIANT", raising=False)
-    else:
-        monkeypatch.setenv("QUARTET_GEMM_VARIANT", request.param)
-    return request.param
+    G.q.check(G.q.quartet_debug_set_gemm_plan(-1 if request.param == "auto" else int(request.param), 0))
+    yield request.param
+    G.q.check(G.q.quartet_debug_set_gemm_plan(-1, 0))
 
 
 @pytest.mark.parametrize("block", (64, 128))

@@ -167,13 +167,11 @@ def test_gemm_exhaustive_code_pairs_bit_exact(G):
 
 
 @pytest.fixture(params=["auto", "0", "1", "2"])
-def gemm_variant(request, monkeypatch):
+def gemm_variant(request, G):
     # every tile shape of the GEMM kernel is checked, not only the one the size heuristic picks
-    if request.param == "auto":
-        monkeypatch.delenv("QUARTET_GEMM_VARIANT", raising=False)
-    else:
-        monkeypatch.setenv("QUARTET_GEMM_VARIANT", request.param)
-    return request.param
+    G.q.check(G.q.quartet_debug_set_gemm_plan(-1 if request.param == "auto" else int(request.param), 0))
+    yield request.param
+    G.q.check(G.q.quartet_debug_set_gemm_plan(-1, 0))
 
 
 @pytest.mark.parametrize("mnk", [(1, 1, 32), (32, 32, 64), (128, 128, 128), (130, 70, 96), (257, 129, 160),
