@@ -275,6 +275,26 @@ int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t 
                        void *dx, void *dw, int grad_dtype,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * quartet_linear_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, results and launch
+ * order as quartet_linear_bwd (bit for bit), but the four quantized operands live in a device array that is part
+ * of the library's code object: QUARTET_STATIC_SCRATCH_BYTES (64 MiB) on every GPU the library is loaded on, held
+ * until the process ends.  The call allocates and frees nothing and clears nothing (every byte it reads from the
+ * array it has written before in the same call).  Shapes whose workspace (quartet_linear_workspace_bytes) exceeds
+ * the array return QUARTET_ENOTSUP with nothing enqueued; other errors as quartet_linear_bwd.  The first call on a
+ * device looks the array's address up (hipGetSymbolAddress), so make that call outside a graph capture.  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race; calls
+ * on one stream are ordered and safe.  quartet_static_scratch_bytes() returns the array's size.
+ */
+#define QUARTET_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+size_t quartet_static_scratch_bytes(void);
+int quartet_linear_bwd_static(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                              const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,
+                              const uint8_t *wq_codes, const uint8_t *wq_scales, const uint32_t *w_mask,
+                              uint64_t seed, int rounding,
+                              void *dx, void *dw, int grad_dtype, void *stream);
+
 /* sign word quartet_linear_bwd derives from a seed (host computation, no GPU work). */
 uint32_t quartet_sign_word(uint64_t seed);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_fwd_operands", "quartet_bwd_operands",
     "quartet_mxfp4_gemm", "quartet_debug_set_gemm_plan", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
+    "quartet_static_scratch_bytes", "quartet_linear_bwd_static",
     "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
     "quartet_requant_transpose_sr_block", "quartet_mxfp4_gemm_grad_block", "quartet_grad_epilogue_block", "quartet_linear_fwd_block",
     "quartet_linear_workspace_bytes_block", "quartet_linear_bwd_block",
@@ -66,6 +67,8 @@ _lib.quartet_linear_workspace_bytes.restype = ctypes.c_size_t
 _lib.quartet_linear_workspace_bytes.argtypes = [_i64, _i64, _i64]
 _lib.quartet_linear_bwd.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64, _int, _p, _p, _int,
                                     _p, ctypes.c_size_t, _p]
+_lib.quartet_static_scratch_bytes.restype = ctypes.c_size_t
+_lib.quartet_linear_bwd_static.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p, _u64, _int, _p, _p, _int, _p]
 _lib.quartet_sign_words.argtypes = [_u64, _p]
 _lib.quartet_quant_fwd_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p]
 _lib.quartet_quant_bwd_sr_block.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _u64, _u32, _int, _p, _p, _p]
@@ -229,6 +232,18 @@ def quartet_linear_bwd(dy_bf16, tokens, in_features, out_features, xq_codes, xq_
                                    _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales),
                                    _ptr(w_mask), seed, rounding, _ptr(dx), _ptr(dw), grad_dtype,
                                    _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def quartet_static_scratch_bytes():
+    return _lib.quartet_static_scratch_bytes()
+
+
+def quartet_linear_bwd_static(dy_bf16, tokens, in_features, out_features, xq_codes, xq_scales, x_mask, wq_codes,
+                              wq_scales, w_mask, seed, rounding, dx, dw, grad_dtype, stream=None):
+    return _lib.quartet_linear_bwd_static(_ptr(dy_bf16), tokens, in_features, out_features, _ptr(xq_codes),
+                                          _ptr(xq_scales), _ptr(x_mask), _ptr(wq_codes), _ptr(wq_scales),
+                                          _ptr(w_mask), seed, rounding, _ptr(dx), _ptr(dw), grad_dtype,
+                                          _stream(stream))
 
 
 # ---- Hadamard blocks of 32, 64, 128 or 256 elements (sign_words: sequence of host integers)

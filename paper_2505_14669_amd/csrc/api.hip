@@ -132,6 +132,31 @@ BwdWorkspace plan_bwd(int64_t tokens, int64_t in, int64_t out, bool with_acc = f
     return w;
 }
 
+// ---- workspace of quartet_linear_bwd_static: device memory that exists from the moment the library is loaded, one copy
+// per GPU.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+constexpr size_t kStaticScratchBytes = QUARTET_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (resolved once per device, with that device current).
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return QUARTET_ENOTSUP;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return QUARTET_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return QUARTET_OK;
+}
+
 }  // namespace
 
 using quartet::SrParams;
@@ -490,6 +515,30 @@ int quartet_linear_bwd(const void* dy_bf16, int64_t tokens, int64_t in, int64_t 
                        void* workspace, size_t workspace_bytes, void* stream) {
     return quartet_linear_bwd_block(dy_bf16, tokens, in, out, 32, xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask,
                                     seed, rounding, dx, dw, grad_dtype, workspace, workspace_bytes, stream);
+}
+
+size_t quartet_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int quartet_linear_bwd_static(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out,
+                              const uint8_t* xq_codes, const uint8_t* xq_scales, const uint32_t* x_mask,
+                              const uint8_t* wq_codes, const uint8_t* wq_scales, const uint32_t* w_mask,
+                              uint64_t seed, int rounding,
+                              void* dx, void* dw, int grad_dtype, void* stream) {
+    if (!dy_bf16 || !xq_codes || !xq_scales || !x_mask || !wq_codes || !wq_scales || !w_mask || !dx || !dw)
+        return QUARTET_EINVAL;
+    if (tokens < 0 || in < 0 || out < 0 || (tokens % 32) != 0 || (in % 32) != 0 || (out % 32) != 0) return QUARTET_EINVAL;
+    // size first (in floating point: the exact plan could overflow on absurd shapes), then the exact plan
+    const double rough = 1.0625 * (double)tokens * (double)out + 0.53125 * ((double)in * (double)out + (double)in * (double)tokens);
+    if (rough > (double)kStaticScratchBytes) return QUARTET_ENOTSUP;
+    const size_t need = plan_bwd(tokens, in, out, false).total;
+    if (need > kStaticScratchBytes) return QUARTET_ENOTSUP;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc) return rc;
+    // every byte of the workspace that a kernel reads as data was written by an earlier kernel of the same call, so
+    // nothing has to be cleared between calls
+    return quartet_linear_bwd_block(dy_bf16, tokens, in, out, 32, xq_codes, xq_scales, x_mask, wq_codes, wq_scales, w_mask,
+                                    seed, rounding, dx, dw, grad_dtype, ws, kStaticScratchBytes, stream);
 }
 
 int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, int64_t out, int hadamard_block,

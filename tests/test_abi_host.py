@@ -127,3 +127,17 @@ def test_block_entry_points_reject_bad_arguments_on_the_host():
     assert q.quartet_mxfp4_gemm_grad_block(P, P, P, P, 4, 96, 64, 64, None, 1.0, P, 0, 96, 0) == E      # n % block
     assert q.quartet_mxfp4_gemm_grad_block(P, P, P, P, 4, 128, 64, 48, None, 1.0, P, 0, 128, 0) == E    # unsupported block
     assert q.quartet_last_hip_error() == 0
+
+
+def test_static_scratch_backward_rejects_layers_beyond_its_array_on_the_host():
+    from paper_2505_14669_amd import binding as q
+    P = 0x10000
+    assert q.quartet_static_scratch_bytes() == 64 << 20
+    t, i, o = 16384, 4096, 4096
+    assert q.quartet_linear_workspace_bytes(t, i, o) > q.quartet_static_scratch_bytes()
+    args = lambda t, i, o: (P, t, i, o, P, P, P, P, P, P, 0, 0, P, P, q.QUARTET_DTYPE_F32, 0)
+    assert q.quartet_linear_bwd_static(*args(t, i, o)) == q.QUARTET_ENOTSUP
+    assert q.quartet_linear_bwd_static(*args(2 ** 40, 2 ** 30, 2 ** 30)) == q.QUARTET_ENOTSUP
+    assert q.quartet_linear_bwd_static(*args(48, 32, 32)) == q.QUARTET_EINVAL
+    assert q.quartet_linear_bwd_static(None, 32, 32, 32, P, P, P, P, P, P, 0, 0, P, P, 0, 0) == q.QUARTET_EINVAL
+    assert q.quartet_debug_set_gemm_plan(3, 0) == q.QUARTET_EINVAL and q.quartet_debug_set_gemm_plan(-1, 0) == q.QUARTET_OK
