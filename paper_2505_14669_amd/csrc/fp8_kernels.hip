@@ -123,6 +123,7 @@ gemm_mxfp8_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
     constexpr uint32_t KEEP = (D - 1) * LOADS;
     constexpr uint32_t WAIT_STAGE = 0x0F70u | (KEEP & 15u) | ((KEEP >> 4) << 14);
     __shared__ uint4 lds[kRing * STAGE];
+    static_assert(kRing * STAGE * 16 >= 4 * TM * 32 * kEpiStride * 4, "the epilogue's per-wave scratch must fit in the ring");
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);

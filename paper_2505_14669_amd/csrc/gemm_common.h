@@ -31,7 +31,7 @@ constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here 
 // then the scale.  Lane i of the 8 holds 4-column chunk i ^ (i & 4 ? 3 : 0), which makes the three
 // partners lane ^ 1, lane ^ 2 and 7 - lane: all reachable by DPP, none through LDS.
 // wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
-constexpr uint32_t kEpiStride = 36;   // floats per LDS row (144 bytes: 16-byte aligned, rows spread over banks)
+constexpr uint32_t kEpiStride = 40;   // floats per LDS row: 16-byte aligned, and the two half-waves of a write (4 rows apart) fall into different halves of the 64 banks (counters: one conflict cycle per write with 36)
 
 // One butterfly stage between a lane and its DPP partner for the four values of a chunk, one instruction per value: both
 // lanes form partner * t + own (t = +-1, so the fused multiply-add rounds exactly like the addition): t = +1 in the lower
@@ -151,7 +151,7 @@ __device__ __forceinline__ void store_tile_body_rows(v16f (&acc)[TM][TN], float*
                                                      const uint32_t* mask, float alpha, uint32_t row_base,
                                                      uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane,
                                                      uint32_t nb) {
-    constexpr uint32_t STRIDE = TN * 32u + 4u;   // floats per LDS row: 16-byte aligned, rows shifted by 4 banks
+    constexpr uint32_t STRIDE = TN * 32u + 8u;   // floats per LDS row: 16-byte aligned, rows 4 apart 32 banks apart
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
     const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
     const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLIES_ACROSS
@@ -272,6 +272,131 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, voi
     if (full) store_tile_body<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
     else store_tile_body<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
 }
+
+// Epilogue of the streaming kernel: the wave's 128 x 128 accumulator tile leaves in 16 passes of 8 rows x 128
+// columns through a 4 KB scratch of the wave's own (outside the ring, so the ring keeps streaming the next tile).
+// Row 4*lhalf + e of a pass comes from register 4*qd + e of the four accumulators of tile row i; a lane reads
+// back chunk c (4 columns) of all four 32-column slices of row `sub`, so Hadamard blocks of 32, 64 and 128 columns
+// are handled alike (group-combining stages inside the lane, then the 32-point stages of each slice).
+// LDS image: row r at r*128 floats, slice j of rows 4..7 stored at slice position j^1 (the two half-waves of a
+// write then hit different bank halves).
+template <int TM, bool OUT_BF16, bool FUSED, bool FULL>
+__device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][4], float* wbuf, void* d, uint32_t ldd,
+                                                 const uint32_t* mask, float alpha, uint32_t row_base,
+                                                 uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane, uint32_t nb) {
+    constexpr uint32_t TN = 4, PASSES = TM * 4, W = 128;
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
+    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;
+    const float norm = ((c ^ (c >> 1) ^ (c >> 2)) & 1u) ? -block_norm(nb) : block_norm(nb);
+    const bool wide = FULL || (ldd & 3u) == 0u;
+    const uint32_t mask_ld = n >> 5;
+    float* wr = wbuf + lhalf * 4u * W + lrow;          // + e*W + ((j ^ lhalf) * 32)
+    const float* rd = wbuf + sub * W + 4u * c;         // + ((j ^ (sub >> 2)) * 32)
+    const uint32_t rswz = sub >> 2;
+    uint32_t mw[PASSES][TN];
+    if (FUSED) {
+        const bool mvec = FULL && (mask_ld & 3u) == 0u && (reinterpret_cast<uintptr_t>(mask) & 15u) == 0u;   // wave-uniform
+#pragma unroll
+        for (uint32_t p = 0; p < PASSES; ++p) {
+            const uint32_t grow = row_base + p * 8u + sub;
+            if (mvec) {
+                const uint4 w4 = *reinterpret_cast<const uint4*>(&mask[(size_t)grow * mask_ld + (col_base >> 5)]);
+                mw[p][0] = w4.x; mw[p][1] = w4.y; mw[p][2] = w4.z; mw[p][3] = w4.w;
+            } else {
+#pragma unroll
+                for (uint32_t j = 0; j < TN; ++j) {
+                    const uint32_t gcol = col_base + j * 32u;
+                    if (FULL) mw[p][j] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
+                    else mw[p][j] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
+                }
+            }
+        }
+    }
+#define ROWS8_WRITE(P)                                                                                  \
+    _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                                 \
+        _Pragma("unroll") for (uint32_t e = 0; e < 4; ++e)                                              \
+            wr[e * W + ((j ^ lhalf) * 32u)] = acc[(P) >> 2][j][((P) & 3u) * 4u + e];
+    ROWS8_WRITE(0u)
+#pragma unroll
+    for (uint32_t p = 0; p < PASSES; ++p) {
+        float4 sl[TN];
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j) sl[j] = *reinterpret_cast<const float4*>(&rd[(j ^ rswz) * 32u]);
+        if (p + 1u < PASSES) { ROWS8_WRITE(p + 1u) }     // behind the reads in the wave's LDS queue: LDS operations of a wave run in order
+        const uint32_t grow = row_base + p * 8u + sub;
+        float vv[TN][4];
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j) {
+            vv[j][0] = sl[j].x; vv[j][1] = sl[j].y; vv[j][2] = sl[j].z; vv[j][3] = sl[j].w;
+            if (FUSED) {
+                const int32_t bits = (int32_t)(mw[p][j] >> (4u * c));
+#pragma unroll
+                for (uint32_t e = 0; e < 4; ++e)
+                    vv[j][e] = __uint_as_float(__float_as_uint(vv[j][e]) & (uint32_t)((bits << (31 - (int)e)) >> 31));
+            }
+        }
+        if (FUSED && nb >= 2u) {
+#pragma unroll
+            for (uint32_t j = 0; j + 1u < TN; j += 2)
+#pragma unroll
+                for (uint32_t e = 0; e < 4; ++e) {
+                    const float a = vv[j][e], b = vv[j + 1][e];
+                    vv[j][e] = a + b;
+                    vv[j + 1][e] = a - b;
+                }
+        }
+        if (FUSED && nb >= 4u) {
+#pragma unroll
+            for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+                for (uint32_t e = 0; e < 4; ++e) {
+                    const float a = vv[j][e], b = vv[j + 2u][e];
+                    vv[j][e] = a + b;
+                    vv[j + 2u][e] = a - b;
+                }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < TN; ++j) {
+            const uint32_t gcol = col_base + j * 32u;
+            float v0 = vv[j][0], v1 = vv[j][1], v2 = vv[j][2], v3 = vv[j][3];
+            if (FUSED) {
+                const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;
+                v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;
+                QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, up4, up8, up16);
+                v0 = epilogue_norm(v0, norm); v1 = epilogue_norm(v1, norm); v2 = epilogue_norm(v2, norm); v3 = epilogue_norm(v3, norm);
+            }
+            v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
+            if (!FULL && grow >= m) continue;
+            const uint32_t col = gcol + 4u * c;
+            const size_t at = (size_t)grow * ldd + col;
+            if (OUT_BF16) {
+                uint16_t* dst = static_cast<uint16_t*>(d) + at;
+                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                } else {
+                    if (col < n) dst[0] = (uint16_t)h0;
+                    if (col + 1u < n) dst[1] = (uint16_t)h1;
+                    if (col + 2u < n) dst[2] = (uint16_t)h2;
+                    if (col + 3u < n) dst[3] = (uint16_t)h3;
+                }
+            } else {
+                float* dst = static_cast<float*>(d) + at;
+                if (FULL || (wide && col + 4u <= n)) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                } else {
+                    if (col < n) dst[0] = v0;
+                    if (col + 1u < n) dst[1] = v1;
+                    if (col + 2u < n) dst[2] = v2;
+                    if (col + 3u < n) dst[3] = v3;
+                }
+            }
+        }
+    }
+#undef ROWS8_WRITE
+}
+
 
 // Depth of the LDS ring of the large-tile kernels.
 constexpr uint32_t kRing = 4;

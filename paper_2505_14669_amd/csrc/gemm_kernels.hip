@@ -13,8 +13,8 @@
 // so a wave's scale fragment is one coalesced 256-byte global load and the paper's separate
 // scale-rearrangement step does not exist here.
 //
-// Kernel shape: block tile BM x BN, K staged through LDS 256 elements (128 code bytes per row) at a
-// time, two LDS buffers, global loads for stage t+1 issued before the matrix-core work of stage t.
+// Two kernel shapes: gemm_mxfp4_kernel (one block per tile, two LDS buffers; small problems) and
+// gemm_mxfp4_stream_kernel (one block per compute unit streaming its tiles through a ring of LDS stages).
 #include "gemm_common.h"
 #include "launchers.h"
 
@@ -54,6 +54,8 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
     constexpr uint32_t LA = BM / 32, LB = BN / 32;      // 1 KB (64 lanes x 16 B) loads per wave per stage
     constexpr uint32_t STAGE = (BM + BN) * 8;           // 16-byte chunks per LDS buffer
     __shared__ uint4 lds[2 * STAGE];
+    static_assert(2 * STAGE * 16 >= 4 * TM * 32 * kEpiStride * 4 && 2 * STAGE * 16 >= 4 * 32 * (TN * 32 + 8) * 4,
+                  "the epilogue's per-wave scratch (either form) must fit in the stage buffers");
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lives in an SGPR
@@ -224,221 +226,248 @@ gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ring variant for large problems.  Same 256 x 256 block tile and 128 x 128 wave tile, but K is staged
-// 128 elements (64 code bytes per row) at a time through a ring of kRing LDS stages that is filled
-// kRing-1 stages ahead, so roughly 100 KB per CU are in flight and no wait ever falls on loads that
-// were just issued.  A stage is [A codes 16 KB][B codes 16 KB][16 scale tiles 4 KB], all written by
-// LDS-direct loads (8 per wave per stage, and one more for the scale tiles with every even stage).
-//
-// The LDS-direct loads are issued from inline assembly and the barrier is a bare s_barrier, with the
-// vector-memory counter managed by hand: the compiler cannot tell which LDS reads alias an
-// LDS-direct load in flight, so it would otherwise drain every outstanding load before each
-// fragment read (and before each barrier), which serializes the copy and the matrix-core work.
+// Streaming variant: one block per compute unit walks its tiles (virtual block ids b, b + G, ...), and the ring of LDS
+// stages never drains between them: the loads of the next tile's first stages are issued during the last stages
+// of the current one, so a tile's first matrix-core instruction follows the previous tile's result stores directly.
+// The epilogue uses a scratch of its own (16 KB beside the 144 KB ring).
 template <bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
-gemm_mxfp4_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
-                       const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
-                       uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                       const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
+gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+                         const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
+                         uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
+                         const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
     constexpr uint32_t D = kRing - 1;                    // prefetch distance in stages
-    __shared__ uint4 lds[kRing * STAGE];
+    constexpr uint32_t EPI = 4u * 256u;                  // 16-byte chunks of epilogue scratch (4 KB per wave)
+    __shared__ uint4 lds[kRing * STAGE + EPI];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-
-    uint32_t tile;
-    {
-        const uint32_t nb = gridDim.x, xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
-        const uint32_t per = nb >> 3, rem = nb & 7u;
-        tile = xcd * per + (xcd < rem ? xcd : rem) + q;
-    }
+    const uint32_t total_tiles = tiles_m * tiles_n, G = gridDim.x;
+    const uint32_t per = total_tiles >> 3, rem = total_tiles & 7u;
     const uint32_t GM = band_height;
-    const uint32_t band = tile / (GM * tiles_n);
-    const uint32_t band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
-    const uint32_t in_band = tile - band * GM * tiles_n;
-    const uint32_t m0 = (band * GM + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
     const uint32_t wm0 = (wave >> 1) * 128u, wn0 = (wave & 1u) * 128u;
-
     const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;
-    const uint32_t rows_a = (m - m0) < BM ? (m - m0) : BM, rows_b = (n - n0) < BN ? (n - n0) : BN;
-    const v4i_t res_a = make_rsrc_words(a_codes + (size_t)m0 * kb, rows_a * kb);
-    const v4i_t res_b = make_rsrc_words(b_codes + (size_t)n0 * kb, rows_b * kb);
-    // waves 0,1 fetch the A scale tiles, waves 2,3 the B scale tiles (4 tiles of 256 B per load)
     const bool scales_of_a = wave < 2u;
-    const uint32_t srow0 = scales_of_a ? m0 : n0, srows = scales_of_a ? rows_a : rows_b;
-    const v4i_t res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0 >> 5) * kq * 256u,
-                                        ((srows + 31u) >> 5) * kq * 256u);
 
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+// tile origin of virtual block id V (XCD-aware order, bands of GM tile rows); V >= total_tiles: M0 = m (no rows)
+#define STREAM_TILE(V, M0, N0)                                                                          \
+    {                                                                                                   \
+        const uint32_t v_ = (V);                                                                        \
+        if (v_ < total_tiles) {                                                                         \
+            const uint32_t xcd_ = v_ & 7u;                                                              \
+            const uint32_t tile_ = xcd_ * per + (xcd_ < rem ? xcd_ : rem) + (v_ >> 3);                  \
+            const uint32_t band_ = tile_ / (GM * tiles_n);                                              \
+            const uint32_t band_rows_ = (tiles_m - band_ * GM) < GM ? (tiles_m - band_ * GM) : GM;      \
+            const uint32_t in_band_ = tile_ - band_ * GM * tiles_n;                                     \
+            M0 = (band_ * GM + in_band_ % band_rows_) * BM;                                             \
+            N0 = (in_band_ / band_rows_) * BN;                                                          \
+        } else {                                                                                        \
+            M0 = m; N0 = n;                                                                             \
+        }                                                                                               \
+    }
+    // issue cursor: the tile and stage the next LDS-direct loads belong to
+    uint32_t iv = blockIdx.x, ist = 0u;
+    v4i_t res_a, res_b, res_s;
+#define STREAM_ISSUE_SETUP()                                                                            \
+    {                                                                                                   \
+        uint32_t m0_, n0_;                                                                              \
+        STREAM_TILE(iv, m0_, n0_)                                                                       \
+        const uint32_t rows_a_ = (m - m0_) < BM ? (m - m0_) : BM, rows_b_ = (n - n0_) < BN ? (n - n0_) : BN; \
+        res_a = make_rsrc_words(a_codes + (size_t)m0_ * kb, rows_a_ * kb);                              \
+        res_b = make_rsrc_words(b_codes + (size_t)n0_ * kb, rows_b_ * kb);                              \
+        const uint32_t srow0_ = scales_of_a ? m0_ : n0_, srows_ = scales_of_a ? rows_a_ : rows_b_;      \
+        res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0_ >> 5) * kq * 256u, \
+                                ((srows_ + 31u) >> 5) * kq * 256u);                                     \
+    }
+    STREAM_ISSUE_SETUP()
 
-    // codes: load j of a wave fills chunks [j*256 + wave*64, +64) = rows j*64 + wave*16 + lane/4 of the
-    // stage (4 chunks per row); chunk c of row r is stored at r*4 + (c ^ (r/4)%4), the XOR pattern that
-    // measured conflict-free for 16-byte reads of 64-byte rows (144 B/clk/CU against 114 for (r/2)%4).
     const uint32_t drow = wave * 16u + (lane >> 2);
     const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
     const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
     const uint32_t gstep = 64u * kb;
     const uint32_t soff = (((wave & 1u) * 4u + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
-    // fragment reads of K-step s (0,1): chunk (2s + lhalf) ^ (row/4)%4 of row w?0 + i*32 + lrow
     const uint32_t swz = (lrow >> 2) & 3u;
     const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
     const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
     const uint32_t sb_base = CODES * 4u + 8u * 64u + (wn0 >> 5) * 64u + lane;
 
     const uint32_t stages = (k + 127u) >> 7;
+    const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);   // stages per tile, even (extra stages are zero-filled)
     uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
     uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
-// load J (0..3: A rows, 4..7: B rows, 8: scale tiles) of stage ST; stages past the end give zeros
-#define RING_ISSUE(ST, J)                                                                               \
+// load J (0..3: A rows, 4..7: B rows, 8: scale tiles) of the issue cursor's stage into ring slot SLOT
+#define STREAM_ISSUE(SLOT, J)                                                                           \
     {                                                                                                   \
-        const uint32_t st_ = (ST);                                                                      \
-        const uint32_t slot_ = lds0 + ((st_ % kRing) * STAGE + wave * 64u) * 16u;                       \
+        const uint32_t slot_ = lds0 + ((SLOT) * STAGE + wave * 64u) * 16u;                              \
         if ((J) < 8u) {                                                                                 \
-            const uint32_t base_ = (st_ * 64u + dcol * 16u < kb) ? goff + st_ * 64u : kOutOfRange;      \
+            const uint32_t base_ = (ist * 64u + dcol * 16u < kb) ? goff + ist * 64u : kOutOfRange;      \
             lds_direct_load16((J) < 4u ? res_a : res_b, base_ + ((J) & 3u) * gstep, slot_ + (J) * 4096u); \
         } else {                                                                                        \
-            lds_direct_load16(res_s, (st_ < stages) ? soff + (st_ >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+            lds_direct_load16(res_s, (ist < stages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
         }                                                                                               \
     }
-#define RING_FRAG_A(ST, S, FA, I) FA[I] = lds[((ST) % kRing) * STAGE + fa_base + (I) * 128u + ((2u * (S) + lhalf) ^ swz)];
-#define RING_FRAG_B(ST, S, FB, J) FB[J] = lds[((ST) % kRing) * STAGE + fb_base + (J) * 128u + ((2u * (S) + lhalf) ^ swz)];
-// the raw scale dwords of a stage's K-quad
-#define RING_READ_SCALES_RAW(ST, RA, RB)                                                                \
+// the stage is issued: move the cursor on (to the next tile of this block after the tile's last stage)
+#define STREAM_ISSUE_ADVANCE()                                                                          \
     {                                                                                                   \
-        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[((ST) % kRing) * STAGE]);        \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) RA[i] = sbuf_[sa_base + i * 64u];           \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) RB[j] = sbuf_[sb_base + j * 64u];           \
+        ++ist;                                                                                          \
+        if (ist == S2) {                                                                                \
+            ist = 0u;                                                                                   \
+            iv += G;                                                                                    \
+            STREAM_ISSUE_SETUP()                                                                        \
+        }                                                                                               \
     }
-#define RING_FENCE() __builtin_amdgcn_sched_barrier(0);
+#define STREAM_FRAG_A(SLOT, S, FA, I) FA[I] = lds[(SLOT) * STAGE + fa_base + (I) * 128u + ((2u * (S) + lhalf) ^ swz)];
+#define STREAM_FRAG_B(SLOT, S, FB, J) FB[J] = lds[(SLOT) * STAGE + fb_base + (J) * 128u + ((2u * (S) + lhalf) ^ swz)];
+#define STREAM_FENCE() __builtin_amdgcn_sched_barrier(0);
 
-    {
-        // Two stages per trip.  A scale-tile dword holds the four K-steps of a K-quad, i.e. of an even stage
-        // and the odd stage after it: it is read once per pair and each matrix-core instruction picks its
-        // byte (op_sel), so there are no byte moves; the scale tiles travel with even stages only
-        // (17 loads per pair of stages instead of 18).  Otherwise the one-instruction-per-slot order.
-        constexpr uint32_t KEEP2 = 17u;                    // loads of one even and one odd stage stay in flight
-        constexpr uint32_t WAIT2 = 0x0F70u | (KEEP2 & 15u) | ((KEEP2 >> 4) << 14);
+    constexpr uint32_t KEEP2 = 17u;                    // loads of one even and one odd stage stay in flight
+    constexpr uint32_t WAIT2 = 0x0F70u | (KEEP2 & 15u) | ((KEEP2 >> 4) << 14);
 #pragma unroll
-        for (uint32_t s0 = 0; s0 < D; ++s0) {
+    for (uint32_t s0 = 0; s0 < D; ++s0) {
 #pragma unroll
-            for (uint32_t j = 0; j < 8u; ++j) RING_ISSUE(s0, j)
-            if ((s0 & 1u) == 0u) RING_ISSUE(s0, 8u)
-        }
-        __builtin_amdgcn_s_waitcnt(WAIT2);
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i) { RING_FRAG_A(0u, 0u, fa0, i) RING_FRAG_B(0u, 0u, fb0, i) }
-        const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
-// scale dwords of the K-quad that starts with (even) stage ST; bytes of groups past k/32 become 2^0
-#define RING2_SCALES(ST, XA, XB)                                                                        \
-        {                                                                                               \
-            uint32_t ra_[TM], rb_[TN];                                                                  \
-            RING_READ_SCALES_RAW(ST, ra_, rb_)                                                          \
-            uint32_t keep_ = 0xFFFFFFFFu;                                                               \
-            if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */         \
-                const uint32_t done_ = (ST) * 2u;                                                       \
-                const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
-                keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                            \
-            }                                                                                           \
-            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
-            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
-        }
-        RING2_SCALES(0u, sa, sb)
-#define RING_MF(S, FA, FB, I, J)                                                                        \
-        acc[I][J] = mfma_fp4<S>(FA[I], FB[J], acc[I][J], sa[I], sb[J]);                                 \
-        asm volatile("" : "+a"(acc[I][J]));                                                             \
-        RING_FENCE()
-#define RING2_BODY(PAR, ST)                                                                             \
-        {                                                                                               \
-            const uint32_t st_b = (ST);                                                                 \
-            RING_MF(2 * PAR, fa0, fb0, 0, 0) RING_FRAG_B(st_b, 1u, fb1, 0) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 0, 1) RING_FRAG_B(st_b, 1u, fb1, 1) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 0, 2) RING_FRAG_B(st_b, 1u, fb1, 2) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 0, 3) RING_FRAG_B(st_b, 1u, fb1, 3) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 1, 0) RING_FRAG_A(st_b, 1u, fa1, 0) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 1, 1) RING_FRAG_A(st_b, 1u, fa1, 1) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 1, 2) RING_FRAG_A(st_b, 1u, fa1, 2) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 1, 3) RING_FRAG_A(st_b, 1u, fa1, 3) RING_FENCE()                 \
-            RING_MF(2 * PAR, fa0, fb0, 2, 0) RING_ISSUE(st_b + D, 0u) RING_FENCE()                      \
-            RING_MF(2 * PAR, fa0, fb0, 2, 1)                                                            \
-            RING_MF(2 * PAR, fa0, fb0, 2, 2) RING_ISSUE(st_b + D, 1u) RING_FENCE()                      \
-            RING_MF(2 * PAR, fa0, fb0, 2, 3)                                                            \
-            RING_MF(2 * PAR, fa0, fb0, 3, 0) RING_ISSUE(st_b + D, 2u) RING_FENCE()                      \
-            RING_MF(2 * PAR, fa0, fb0, 3, 1)                                                            \
-            RING_MF(2 * PAR, fa0, fb0, 3, 2) RING_ISSUE(st_b + D, 3u) RING_FENCE()                      \
-            RING_MF(2 * PAR, fa0, fb0, 3, 3)                                                            \
-            RING_MF(2 * PAR + 1, fa1, fb1, 0, 0) RING_ISSUE(st_b + D, 4u) RING_FENCE()                  \
-            RING_MF(2 * PAR + 1, fa1, fb1, 0, 1)                                                        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 0, 2) RING_ISSUE(st_b + D, 5u) RING_FENCE()                  \
-            RING_MF(2 * PAR + 1, fa1, fb1, 0, 3)                                                        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 1, 0) RING_ISSUE(st_b + D, 6u) RING_FENCE()                  \
-            RING_MF(2 * PAR + 1, fa1, fb1, 1, 1)                                                        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 1, 2) RING_ISSUE(st_b + D, 7u) RING_FENCE()                  \
-            RING_MF(2 * PAR + 1, fa1, fb1, 1, 3)                                                        \
-            if (PAR == 1) { RING_ISSUE(st_b + D, 8u) RING_FENCE() }   /* st_b + D is even */            \
-            __builtin_amdgcn_s_waitcnt(WAIT2);                                                          \
-            __builtin_amdgcn_s_barrier();                                                               \
-            RING_FENCE()                                                                                \
-            RING_MF(2 * PAR + 1, fa1, fb1, 2, 0) RING_FRAG_A(st_b + 1u, 0u, fa0, 0) RING_FRAG_B(st_b + 1u, 0u, fb0, 0) RING_FENCE() \
-            RING_MF(2 * PAR + 1, fa1, fb1, 2, 1) RING_FRAG_B(st_b + 1u, 0u, fb0, 1) RING_FRAG_B(st_b + 1u, 0u, fb0, 2) RING_FENCE() \
-            RING_MF(2 * PAR + 1, fa1, fb1, 2, 2) RING_FRAG_B(st_b + 1u, 0u, fb0, 3) RING_FENCE()        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 2, 3) RING_FRAG_A(st_b + 1u, 0u, fa0, 1) RING_FENCE()        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 3, 0) RING_FRAG_A(st_b + 1u, 0u, fa0, 2) RING_FENCE()        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 3, 1) RING_FRAG_A(st_b + 1u, 0u, fa0, 3) RING_FENCE()        \
-            if (PAR == 1) { RING2_SCALES(st_b + 1u, sa_n, sb_n) RING_FENCE() }                          \
-            RING_MF(2 * PAR + 1, fa1, fb1, 3, 2)                                                        \
-            RING_MF(2 * PAR + 1, fa1, fb1, 3, 3)                                                        \
-            if (PAR == 1) {                                                                             \
-                _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                    \
-                _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                    \
-            }                                                                                           \
-        }
-        // an odd number of stages is rounded up: the extra stage is zero-filled (codes of +0) and adds nothing
-        for (uint32_t st = 0; st < stages; st += 2u) {
-            RING2_BODY(0, st)
-            RING2_BODY(1, st + 1u)
-        }
-#undef RING2_BODY
-#undef RING_MF
-#undef RING2_SCALES
+        for (uint32_t j = 0; j < 8u; ++j) STREAM_ISSUE(s0, j)
+        if ((s0 & 1u) == 0u) STREAM_ISSUE(s0, 8u)
+        STREAM_ISSUE_ADVANCE()
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the zero-filled stages issued past the end
-#undef RING_ISSUE
-#undef RING_FRAG_A
-#undef RING_FRAG_B
-#undef RING_READ_SCALES_RAW
-#undef RING_FENCE
-
-    // every wave is done reading the ring (and the zero-filled stages have landed): reuse it as the
-    // epilogue's scratch
+    __builtin_amdgcn_s_waitcnt(WAIT2);
     __builtin_amdgcn_s_barrier();
-    store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
-                                        alpha, m0 + wm0, n0 + wn0, m, n, lane, nb);
+#pragma unroll
+    for (uint32_t i = 0; i < TM; ++i) { STREAM_FRAG_A(0u, 0u, fa0, i) STREAM_FRAG_B(0u, 0u, fb0, i) }
+    const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
+// scale dwords of the K-quad that starts with (even) local stage ST, held in ring slot SLOT; bytes of groups past k/32 become 2^0
+#define STREAM_SCALES(SLOT, ST, XA, XB)                                                                 \
+    {                                                                                                   \
+        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(SLOT) * STAGE]);                \
+        uint32_t ra_[TM], rb_[TN];                                                                      \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_[i] = sbuf_[sa_base + i * 64u];          \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_[j] = sbuf_[sb_base + j * 64u];          \
+        uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
+        if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */             \
+            const uint32_t done_ = (ST) * 2u;                                                           \
+            const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
+            keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
+        }                                                                                               \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+    }
+    STREAM_SCALES(0u, 0u, sa, sb)
+#define STREAM_MF(S, FA, FB, I, J)                                                                      \
+    acc[I][J] = mfma_fp4<S>(FA[I], FB[J], acc[I][J], sa[I], sb[J]);                                     \
+    asm volatile("" : "+a"(acc[I][J]));                                                                 \
+    STREAM_FENCE()
+// one stage: PAR = its parity, ST = its local index, slots: SL = its own, SL1 = the next stage's, SLI = the one being filled
+#define STREAM_BODY(PAR, ST, SL, SL1, SLI, NEXT_ST)                                                     \
+    {                                                                                                   \
+        STREAM_MF(2 * PAR, fa0, fb0, 0, 0) STREAM_FRAG_B(SL, 1u, fb1, 0) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 0, 1) STREAM_FRAG_B(SL, 1u, fb1, 1) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 0, 2) STREAM_FRAG_B(SL, 1u, fb1, 2) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 0, 3) STREAM_FRAG_B(SL, 1u, fb1, 3) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 1, 0) STREAM_FRAG_A(SL, 1u, fa1, 0) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 1, 1) STREAM_FRAG_A(SL, 1u, fa1, 1) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 1, 2) STREAM_FRAG_A(SL, 1u, fa1, 2) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 1, 3) STREAM_FRAG_A(SL, 1u, fa1, 3) STREAM_FENCE()                 \
+        STREAM_MF(2 * PAR, fa0, fb0, 2, 0) STREAM_ISSUE(SLI, 0u) STREAM_FENCE()                         \
+        STREAM_MF(2 * PAR, fa0, fb0, 2, 1)                                                              \
+        STREAM_MF(2 * PAR, fa0, fb0, 2, 2) STREAM_ISSUE(SLI, 1u) STREAM_FENCE()                         \
+        STREAM_MF(2 * PAR, fa0, fb0, 2, 3)                                                              \
+        STREAM_MF(2 * PAR, fa0, fb0, 3, 0) STREAM_ISSUE(SLI, 2u) STREAM_FENCE()                         \
+        STREAM_MF(2 * PAR, fa0, fb0, 3, 1)                                                              \
+        STREAM_MF(2 * PAR, fa0, fb0, 3, 2) STREAM_ISSUE(SLI, 3u) STREAM_FENCE()                         \
+        STREAM_MF(2 * PAR, fa0, fb0, 3, 3)                                                              \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 0, 0) STREAM_ISSUE(SLI, 4u) STREAM_FENCE()                     \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 0, 1)                                                          \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 0, 2) STREAM_ISSUE(SLI, 5u) STREAM_FENCE()                     \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 0, 3)                                                          \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 1, 0) STREAM_ISSUE(SLI, 6u) STREAM_FENCE()                     \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 1, 1)                                                          \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 1, 2) STREAM_ISSUE(SLI, 7u) STREAM_FENCE()                     \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 1, 3)                                                          \
+        if (PAR == 1) { STREAM_ISSUE(SLI, 8u) STREAM_FENCE() }   /* the stage being filled is even */   \
+        STREAM_ISSUE_ADVANCE()                                                                          \
+        __builtin_amdgcn_s_waitcnt(WAIT2);                                                              \
+        __builtin_amdgcn_s_barrier();                                                                   \
+        STREAM_FENCE()                                                                                  \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 0) STREAM_FRAG_A(SL1, 0u, fa0, 0) STREAM_FRAG_B(SL1, 0u, fb0, 0) STREAM_FENCE() \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 1) STREAM_FRAG_B(SL1, 0u, fb0, 1) STREAM_FRAG_B(SL1, 0u, fb0, 2) STREAM_FENCE() \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 2) STREAM_FRAG_B(SL1, 0u, fb0, 3) STREAM_FENCE()            \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 3) STREAM_FRAG_A(SL1, 0u, fa0, 1) STREAM_FENCE()            \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 0) STREAM_FRAG_A(SL1, 0u, fa0, 2) STREAM_FENCE()            \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 1) STREAM_FRAG_A(SL1, 0u, fa0, 3) STREAM_FENCE()            \
+        if (PAR == 1) { STREAM_SCALES(SL1, NEXT_ST, sa_n, sb_n) STREAM_FENCE() }                        \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 2)                                                          \
+        STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 3)                                                          \
+        if (PAR == 1) {                                                                                 \
+            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                        \
+            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                        \
+        }                                                                                               \
+    }
+
+    v16f acc[TM][TN];
+    float* wbuf = reinterpret_cast<float*>(&lds[kRing * STAGE]) + wave * 1024u;
+    uint32_t g = 0u;                                       // stages done by this block (ring slot = g % kRing)
+    for (uint32_t cv = blockIdx.x; cv < total_tiles; cv += G) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (uint32_t st = 0u; st < S2; st += 2u, g += 2u) {
+            const uint32_t sl = g & 3u;                    // g is even: sl is 0 or 2
+            const uint32_t next_st = st + 2u < S2 ? st + 2u : 0u;   // after the tile's last pair: the next tile's stage 0
+            STREAM_BODY(0, st, sl, sl + 1u, sl ^ 3u, 0u)                        /* fills slot (g + 3) % 4 */
+            STREAM_BODY(1, st + 1u, sl + 1u, sl ^ 2u, sl, next_st)              /* fills slot (g + 4) % 4 */
+        }
+        // The ring already holds (or is receiving) the next tile's first stages, and fa0 / fb0 / sa / sb its first
+        // fragments and scales.  The result stores below are older than every load issued from here on and the
+        // vector-memory counter retires in order, so the next tile's first wait also waits for them.
+        uint32_t m0, n0;
+        STREAM_TILE(cv, m0, n0)
+        const uint32_t row_base = m0 + wm0, col_base = n0 + wn0;
+        const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n && (!FUSED || mask != nullptr);
+        if (full) store_tile_rows8<TM, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_rows8<TM, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
+#undef STREAM_TILE
+#undef STREAM_ISSUE_SETUP
+#undef STREAM_ISSUE
+#undef STREAM_ISSUE_ADVANCE
+#undef STREAM_FRAG_A
+#undef STREAM_FRAG_B
+#undef STREAM_FENCE
+#undef STREAM_SCALES
+#undef STREAM_MF
+#undef STREAM_BODY
+}
+
+static int stream_blocks() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n >= 8)
+            cus = n & ~7;
+        else
+            cus = 8;
+    }
+    return cus;
 }
 
 template <bool OUT_BF16, bool FUSED>
-static void launch_ring_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                          const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                          int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
+static void launch_stream_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                            const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
+                            int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
-    // Height of the bands of tile rows an XCD walks (its 32 CUs then work on gm x 32/gm tiles at a time).  Measured on
-    // the Llama shapes: 4 is never worse than 8 (+0-7 %); with 40 or more tile columns 2 is better still
-    // (16384 x 11008 x 4096: 3.39 against 2.96 PFLOP/s with 8), unless the tile rows do not pair up.
     uint32_t gm = (tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
     if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
-    hipLaunchKernelGGL((gemm_mxfp4_ring_kernel<OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
+    const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
+    hipLaunchKernelGGL((gemm_mxfp4_stream_kernel<OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
                        tiles_m, tiles_n, gm, nb);
 }
@@ -454,9 +483,9 @@ static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, co
                        tiles_m, tiles_n, nb);
 }
 
-// Variants: 0 = 256x256 block, ring of 4 LDS stages, two stages per trip with the scale byte picked by
-// op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too small to fill the chip with
-// big tiles); 2 = 256x256 block, two LDS buffers.
+// Variants: 0 = 256x256 tiles streamed by one block per compute unit through a ring of 4 LDS stages, two stages
+// per trip with the scale byte picked by op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too
+// small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.
 // set_gemm_plan overrides the size heuristic (tests reach every variant through it).
 // fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
 // be null = all ones), n % (32 nb) == 0.
@@ -479,7 +508,7 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st);      \
                else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); }         \
     } while (0)
-    if (variant == 0) QUARTET_DISPATCH(launch_ring_t, );
+    if (variant == 0) QUARTET_DISPATCH(launch_stream_t, );
     else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
     else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
 #undef QUARTET_DISPATCH
