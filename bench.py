@@ -31,7 +31,10 @@ def parse():
     ap.add_argument("--hadamard-block", type=int, default=32,
                     help="Hadamard block in elements (32 = the method; 64, 128, 256: the wider rotations)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--quant-sweep", action="store_true", help="also time the quantizer-only sweep (config 5)")
+    ap.add_argument("--quant-sweep", action="store_true", help="accepted for older command lines: the quantizer sweep (config 5) runs by default")
+    ap.add_argument("--no-quant-sweep", action="store_true", help="skip the quantizer-only sweep (config 5)")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the short whole-path timings of configurations 1-3")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the register-only matrix-core ceiling measurement")
     ap.add_argument("--fp8-compare", action="store_true",
                     help="also time the library's own MXFP8 GEMM and quantizer on the workload's shapes (the paper's comparison format)")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-kind time breakdown to stderr")
@@ -115,7 +118,16 @@ def cpu_baseline(config, layer=None, q=None):
         dt1 = time.perf_counter() - t0
     finally:
         oracle.set_num_threads(cores)
+    # the quantizer oracle alone, on the same sample: forward rule (codes, scales, mask) and backward rule with stochastic rounding
+    tq = time.perf_counter()
+    oracle.quant_fwd(x)
+    tq_fwd = time.perf_counter() - tq
+    tq = time.perf_counter()
+    oracle.quant_bwd_sr(x, 0x1234ABCD, 7, 0, 0)
+    tq_bwd = time.perf_counter() - tq
     out = dict(value=6.0 * ts * i * o / dt / 1e12, unit="TFLOP/s", cores=cores, kind="oracle",
+               quantizer=dict(fwd_rtn_GBps=round(2.65625 * ts * i / tq_fwd / 1e9, 3), bwd_sr_GBps=round(2.53125 * ts * i / tq_bwd / 1e9, 3),
+                              cores=cores, sample=f"the sample's activations [{ts} x {i}], algorithmic bytes / wall time"),
                sample=f"layer '{name}' of config {config} with tokens cut to {ts} (in={i}, out={o}), fwd+bwd, {dt:.1f} s",
                single_thread=dict(value=6.0 * t1 * i * o / dt1 / 1e12, unit="TFLOP/s", cores=1,
                                   sample=f"the first {t1} tokens of that sample, {dt1:.1f} s"))
@@ -156,6 +168,18 @@ def quant_sweep(q, torch, synth):
                  ("bwd_rtn_row", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], r, c, c, 0, 0x1234ABCD, 7, 0, 1, codes[j], scales[j])),
                  ("bwd_sr_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 0, codes[j], scales[j])),
                  ("bwd_rtn_transposed", 2.53125, lambda j: q.quartet_quant_bwd_sr(xs[j], c, r, c, 1, 0x1234ABCD, 7, 0, 1, codes[j], scales[j]))]
+        # a plain copy of the same matrix on the same box, timed the same way (torch's elementwise copy kernel; bytes read + written)
+        cp_dst = [torch.empty_like(x) for _ in range(2)]
+        for j in range(4):
+            cp_dst[j % 2].copy_(xs[j % sets])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for j in range(20):
+            cp_dst[j % 2].copy_(xs[j % sets])
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 4.0 * r * c * 20 / e0.elapsed_time(e1) / 1e6
+        del cp_dst
         for name, bpe, fn in cases:
             for j in range(warm):
                 q.check(fn(j % sets))
@@ -171,7 +195,8 @@ def quant_sweep(q, torch, synth):
             med, best = statistics.median(ms[:n]), min(ms[:n])
             gbs = bpe * r * c / med / 1e6
             out.append(dict(shape=[r, c], mode=name, ms_median=round(med, 4), ms_min=round(best, 4), GBps=round(gbs, 1),
-                            GBps_best=round(bpe * r * c / best / 1e6, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4)))
+                            GBps_best=round(bpe * r * c / best / 1e6, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4),
+                            copy_GBps=round(copy_gbs, 1)))
         del xs, codes, scales, mask
     return out
 
@@ -257,6 +282,53 @@ def lower_bound_ms(layers):
     return total * 1e3
 
 
+def mfma_ceiling(q, torch, layer, cus, wall_khz):
+    """What the bare matrix-core instruction sustains on this machine right now: the library's register-only loop of
+    v_mfma_scale_f32_32x32x64_f8f6f4 (one block of 4 waves per compute unit) on the first 32 KiB of the first layer's
+    quantized activations and 8 KiB of their scale bytes, timed by events on the current stream; the shader clock it
+    held comes from the kernel's own clock counters."""
+    codes = layer.xq_codes.reshape(-1)[:32768].contiguous()
+    scales = layer.xq_scales.reshape(-1)[:8192].contiguous()
+    sink = torch.empty((cus * 256,), dtype=torch.float32, device=codes.device)
+    ctr = torch.zeros((2,), dtype=torch.int64, device=codes.device)
+    warm, iters = 20000, 100000
+    q.check(q.quartet_probe_mfma_ceiling(codes, scales, warm, cus, sink))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    q.check(q.quartet_probe_mfma_ceiling(codes, scales, iters, cus, sink, ctr))
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    c = ctr.cpu().tolist()
+    flop = cus * 4.0 * iters * 16 * 2 * 32 * 32 * 64
+    return {"TFLOPs": round(flop / ms / 1e9, 1), "ms": round(ms, 2), "blocks": cus, "iterations": iters,
+            "clock_ghz": round(c[0] / c[1] * wall_khz / 1e6, 3) if c[1] > 0 and wall_khz > 0 else None,
+            "what": "register-only loop of the GEMM's matrix-core instruction on this run's quantized activations: "
+                    "no LDS, no memory traffic; the chip lowers its clock under it (power), so this, not 10.1 PFLOP/s, "
+                    "is what the instruction alone reaches on this box"}
+
+
+def time_config(q, torch, synth, config, steps, warmup, rounding):
+    """Whole-path rate of another configuration: K timed steps, no event pairs, wall clock around a synchronize."""
+    cfg = synth.CONFIGS[config]
+    layers = [Layer(q, torch, synth.device_layer(config, li)) for li in range(len(cfg["layers"]))]
+    ws_bytes = max(l.ws_bytes for l in layers)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda:0")
+    for s in range(warmup):
+        for l in layers:
+            l.step(q, ws, s, rounding)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for l in layers:
+            l.step(q, ws, 1000 + s, rounding)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flops = sum(l.flops for l in layers)
+    return {"config": config, "workload": cfg["name"], "layers": len(layers), "steps": steps,
+            "ms_per_step": round(dt * 1e3 / steps, 4), "value": round(flops * steps / dt / 1e12, 2), "unit": "TFLOP/s"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -271,6 +343,7 @@ def main():
 
     torch.cuda.set_device(0)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
+    wall_khz = q.quartet_wall_clock_khz()
     cfg = synth.CONFIGS[args.config]
     layers = [Layer(q, torch, synth.device_layer(args.config, li), args.hadamard_block) for li in range(len(cfg["layers"]))]
     ws_bytes = max(l.ws_bytes for l in layers)
@@ -298,7 +371,10 @@ def main():
             per.setdefault(q.KIND_NAMES[kk], []).append(m)
         return per
 
-    # timed region: only the dominant kernel (the GEMM) carries event pairs, each costs a few microseconds of stream time
+    # timed region: only the dominant kernel (the GEMM) carries event pairs, each costs a few microseconds of stream time;
+    # its blocks also add their shader-clock and constant-clock ticks to two device counters (two atomics per block)
+    clock_ctr = torch.zeros((2,), dtype=torch.int64, device="cuda:0")
+    q.check(q.quartet_profile_clock(clock_ctr))
     q.check(q.quartet_profile_kinds(1 << q.QUARTET_KIND_GEMM))
     q.check(q.quartet_profile_enable(launches_per_step * args.steps))
     torch.cuda.synchronize()
@@ -308,6 +384,8 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     per_kind = read_profile(launches_per_step * args.steps)
+    q.check(q.quartet_profile_clock(None))
+    clock_ticks = clock_ctr.cpu().tolist()
 
     # one more step, outside the timed region, with every launch bracketed: the per-kind time shares
     q.check(q.quartet_profile_kinds(0xFFFFFFFF))
@@ -343,8 +421,9 @@ def main():
                               "frac_hbm": round(min_bytes / avg / 1e6 / PEAK_HBM_GBS, 4)})
 
     ms_per_step = dt * 1e3 / args.steps
+    big_gemm = any(((l.t + 255) // 256) * ((l.o + 255) // 256) >= 160 for l in layers)
     result = {
-        "metric": "Quartet linear fwd+bwd TFLOP/s at 1 GPU",
+        "metric": "Quartet linear fwd+bwd TFLOP/s at 1 GPU; quantizer GB/s; % of MXFP4/HBM roofline",
         "value": round(flops_step / (ms_per_step * 1e-3) / 1e12, 3),
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -356,25 +435,30 @@ def main():
                                f"backward rounding {'stochastic' if args.rounding == 0 else 'nearest'}"
                                + ("" if args.hadamard_block == 32 else f", Hadamard block {args.hadamard_block}"),
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mxfp4_ring_kernel (all three GEMMs of every layer)",
+        "roofline": {"bound": "mfma",
+                     "kernel": ("gemm_mxfp4_stream_kernel" if big_gemm else "gemm_mxfp4_kernel") + " (all three GEMMs of every layer)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
                      "traffic": recorded(args.config, "gemm_config{config}_hbm_traffic.txt", "traffic_bytes_per_launch"),
+                     "traffic_source": "recorded, not measured in this run: rocprofv3 FETCH_SIZE / WRITE_SIZE per launch from "
+                                       f"profiles/gemm_config{args.config}_hbm_traffic.txt",
                      "avg_launch_ms": round(gemm_total_ms / max(len(gemm_ms), 1), 4), "launches": len(gemm_ms),
                      "compute_units": cus},
         "gemm_by_shape": gemm_by_shape,
         "lower_bound_ms_per_step": round(lower_bound_ms(layers), 4),
         "kernel_time_share": {k: round(sum(v) / (dt_all * 1e3), 4) for k, v in sorted(per_kind_all.items())},
     }
-    clock = recorded(args.config, "gemm_config{config}_mfma_counters.txt", "observed_clock_ghz")
-    if clock:   # the same fraction against what the chip can do at the clock it actually holds under this kernel
+    if clock_ticks[1] > 0 and wall_khz > 0:   # the shader clock the chip held under the GEMM kernel, measured by the kernel itself in the timed region
+        clock = clock_ticks[0] / clock_ticks[1] * wall_khz / 1e6
         peak_obs = cus * clock * 1e9 * 16384 / 1e12
-        result["roofline"].update(observed_clock_ghz=clock, peak_at_observed_clock=round(peak_obs, 1),
+        result["roofline"].update(observed_clock_ghz=round(clock, 3), peak_at_observed_clock=round(peak_obs, 1),
                                   frac_at_observed_clock=round(achieved / peak_obs, 4),
-                                  note="the chip is power-limited under FP4 matrix work: a register-only loop of the same "
-                                       "matrix-core instruction on quantized Gaussian codes sustains 6.2 PFLOP/s "
-                                       "(profiles/gemm_config4_mfma_counters.txt); the vendor library's MXFP4 GEMM runs "
-                                       "these shapes at 2.1 PFLOP/s (profiles/vendor_mxfp4_gemm_config4.txt)")
+                                  clock_source="measured in the timed region: shader-clock over constant-clock ticks summed "
+                                               "over the blocks of every large-tile GEMM launch")
+    if not args.no_ceiling and args.hadamard_block == 32:
+        ceil = mfma_ceiling(q, torch, layers[0], cus, wall_khz)
+        result["roofline"]["mfma_ceiling"] = ceil
+        result["roofline"]["frac_of_ceiling"] = round(achieved / ceil["TFLOPs"], 4) if ceil["TFLOPs"] > 0 else None
     if args.breakdown:
         for k, v in sorted(per_kind_all.items()):
             print(f"  {k:10s} launches {len(v):4d} total {sum(v):9.3f} ms  ({sum(v) / (dt_all * 1e3) * 100:5.1f} % of one fully bracketed step)",
@@ -388,12 +472,17 @@ def main():
         del src, dst
     if args.fp8_compare:
         result["fp8_comparison"] = fp8_compare(q, torch, layers)
-    if args.quant_sweep:
-        del layers, ws
-        torch.cuda.empty_cache()
+    first = layers[0] if args.hadamard_block == 32 else None     # the CPU baseline's sample comes from this layer's tensors
+    del layers, ws
+    torch.cuda.empty_cache()
+    if not args.no_quant_sweep:
         result["quantizer_sweep"] = quant_sweep(q, torch, synth)
+        torch.cuda.empty_cache()
+    if not args.no_other_configs:
+        result["other_configs"] = [time_config(q, torch, synth, c, 10, 3, args.rounding) for c in (1, 2, 3) if c != args.config]
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args.config, layers[0] if args.hadamard_block == 32 else None, q)
+        result["cpu_baseline"] = cpu_baseline(args.config, first, q)
     print(json.dumps(result))
 
 

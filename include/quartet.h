@@ -90,6 +90,29 @@ int quartet_profile_kinds(unsigned kind_mask);
 int quartet_profile_read(int *kinds, float *ms, int capacity);
 
 /*
+ * Clock and ceiling measurements (measurement support, as above; no step of the method).
+ *
+ * quartet_profile_clock(c): c is a DEVICE pointer to two uint64 the caller has zeroed, or NULL to switch the
+ * measurement off (the default).  While set, every block of the large-tile GEMM kernel launched through
+ * quartet_mxfp4_gemm / quartet_mxfp4_gemm_grad (and through the linear-layer calls) adds the shader-clock ticks
+ * it ran for to c[0] and the constant-clock ticks of the same interval to c[1] (two atomic additions per block);
+ * c[0] / c[1] * quartet_wall_clock_khz() is the shader clock in kHz the chip held under that kernel.  8-byte
+ * aligned; process-global, not thread-safe.
+ * quartet_wall_clock_khz(): rate of the device's constant clock in kHz (negative: error).
+ * quartet_probe_mfma_ceiling: launches `blocks` blocks of 4 waves that each run `iterations` rounds of the 16
+ * v_mfma_scale_f32_32x32x64_f8f6f4 instructions of one K-step of the GEMM's 128 x 128 wave tile on operands held in
+ * registers (no LDS or memory traffic inside the loop):
+ * blocks * 4 * iterations * 16 * 2 * 32 * 32 * 64 flop.  codes: 32768 device bytes (8 fragments x 256 lanes x 16 B,
+ * any E2M1 codes: the rate depends on the data, so pass quantized tensors of the workload), scales: 8192 device
+ * bytes (8 x 256 dwords of E8M0 bytes), sink: blocks * 256 floats the kernel writes once at its end,
+ * device_counters as for quartet_profile_clock or NULL.  The caller times the launch with events on `stream`.
+ */
+int quartet_profile_clock(uint64_t *device_counters);
+int quartet_wall_clock_khz(void);
+int quartet_probe_mfma_ceiling(const uint8_t *codes, const uint8_t *scales, int64_t iterations, int blocks,
+                               float *sink, uint64_t *device_counters, void *stream);
+
+/*
  * Forward quantizer (Algorithm 1 Forward, lines H_g then QuEST; Section 4.4 "Stage 1").
  * Logical input A[rows x k]:  transpose = 0: A = x, stored [rows x ldx];
  *                             transpose = 1: A = x^T, x stored [k x ldx] (ldx >= rows).

@@ -24,6 +24,7 @@ QUARTET_ROUND_NEAREST = 1
 EXPORTS = [
     "quartet_last_hip_error", "quartet_sr_bits", "quartet_sign_word",
     "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
+    "quartet_profile_clock", "quartet_wall_clock_khz", "quartet_probe_mfma_ceiling",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_fwd_operands", "quartet_bwd_operands",
     "quartet_mxfp4_gemm", "quartet_debug_set_gemm_plan", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
@@ -46,6 +47,9 @@ _lib.quartet_sr_bits.restype = _int
 _lib.quartet_profile_enable.argtypes = [_int]
 _lib.quartet_profile_kinds.argtypes = [ctypes.c_uint]
 _lib.quartet_profile_read.argtypes = [_p, _p, _int]
+_lib.quartet_profile_clock.argtypes = [_p]
+_lib.quartet_wall_clock_khz.restype = _int
+_lib.quartet_probe_mfma_ceiling.argtypes = [_p, _p, _i64, _int, _p, _p, _p]
 _lib.quartet_scale_bytes.restype = ctypes.c_size_t
 _lib.quartet_scale_bytes.argtypes = [_i64, _i64]
 _lib.quartet_sign_word.restype = _u32
@@ -141,6 +145,20 @@ def quartet_profile_kinds(kind_mask):
 def quartet_profile_read(kinds, ms, capacity):
     """kinds: ctypes int array, ms: ctypes float array, both of length >= capacity."""
     return _lib.quartet_profile_read(ctypes.cast(kinds, _p), ctypes.cast(ms, _p), capacity)
+
+
+def quartet_profile_clock(device_counters):
+    """device_counters: a CUDA int64 tensor of two zeros, or None to switch the measurement off."""
+    return _lib.quartet_profile_clock(_ptr(device_counters))
+
+
+def quartet_wall_clock_khz():
+    return _lib.quartet_wall_clock_khz()
+
+
+def quartet_probe_mfma_ceiling(codes, scales, iterations, blocks, sink, device_counters=None, stream=None):
+    return _lib.quartet_probe_mfma_ceiling(_ptr(codes), _ptr(scales), iterations, blocks, _ptr(sink), _ptr(device_counters),
+                                           _stream(stream))
 
 
 def quartet_scale_bytes(rows, k):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquartet.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quant_kernels.hip", "gemm_kernels.hip", "epilogue_kernels.hip", "fp8_kernels.hip"]
+SOURCES = ["api.hip", "quant_kernels.hip", "gemm_kernels.hip", "epilogue_kernels.hip", "fp8_kernels.hip", "probe_kernels.hip"]
 
 # -ffp-contract=off: the Hadamard butterflies and scale arithmetic must not be fused into FMAs;
 # packed-fp32 VALU ops are disabled (they have given wrong results on these machines).

@@ -212,6 +212,31 @@ int quartet_profile_read(int* kinds, float* ms, int capacity) {
     return n;
 }
 
+int quartet_profile_clock(uint64_t* device_counters) {
+    if (reinterpret_cast<uintptr_t>(device_counters) & 7u) return QUARTET_EINVAL;
+    quartet::set_clock_counters(device_counters);
+    return QUARTET_OK;
+}
+
+int quartet_wall_clock_khz(void) {
+    int dev = 0, khz = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+    if (e != hipSuccess) return hip_fail(e);
+    return khz;
+}
+
+int quartet_probe_mfma_ceiling(const uint8_t* codes, const uint8_t* scales, int64_t iterations, int blocks, float* sink,
+                               uint64_t* device_counters, void* stream) {
+    if (!codes || !scales || !sink) return QUARTET_EINVAL;
+    if (!aligned16(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return QUARTET_EINVAL;
+    if (reinterpret_cast<uintptr_t>(device_counters) & 7u) return QUARTET_EINVAL;
+    if (iterations < 0 || iterations > 0x7FFFFFFF || blocks < 0 || blocks > (1 << 20)) return QUARTET_EINVAL;
+    hipError_t e = quartet::launch_mfma_ceiling(codes, scales, (uint32_t)iterations, (uint32_t)blocks, sink, device_counters,
+                                                (hipStream_t)stream);
+    return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
 uint32_t quartet_sign_word(uint64_t seed) {
     const uint32_t ctr[4] = {0u, 0u, 0u, 0xFFFFFFFFu};
     const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
@@ -380,7 +405,7 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 }
 
 int quartet_debug_set_gemm_plan(int variant, int band_height) {
-    if (variant < -1 || variant > 3 || band_height < 0 || band_height > 64) return QUARTET_EINVAL;
+    if (variant < -1 || variant > 2 || band_height < 0 || band_height > 64) return QUARTET_EINVAL;
     quartet::set_gemm_plan(variant, band_height);
     return QUARTET_OK;
 }

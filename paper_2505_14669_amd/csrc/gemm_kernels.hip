@@ -24,6 +24,11 @@ namespace quartet {
 static int g_forced_variant = -1;
 static int g_forced_band = 0;
 
+// quartet_profile_clock: device counters the streaming kernel adds each block's run time to (null: off)
+static uint64_t* g_clock_counters = nullptr;
+
+void set_clock_counters(uint64_t* device_counters) { g_clock_counters = device_counters; }
+
 void set_gemm_plan(int variant, int band_height) {
     g_forced_variant = variant;
     g_forced_band = band_height;
@@ -235,13 +240,21 @@ __global__ void __launch_bounds__(256)
 gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                          const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                          uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                         const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
+                         const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb,
+                         uint64_t* __restrict__ clock_counters) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
     constexpr uint32_t D = kRing - 1;                    // prefetch distance in stages
     constexpr uint32_t EPI = 4u * 256u;                  // 16-byte chunks of epilogue scratch (4 KB per wave)
     __shared__ uint4 lds[kRing * STAGE + EPI];
+
+    // measurement support: shader-clock and constant-clock ticks of this block's run (wave-uniform branch)
+    uint64_t clk_t0 = 0, clk_w0 = 0;
+    if (clock_counters) {
+        clk_t0 = __builtin_readcyclecounter();
+        clk_w0 = __builtin_amdgcn_s_memrealtime();
+    }
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -435,6 +448,11 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         else store_tile_rows8<TM, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
+    if (clock_counters && tid == 0) {
+        const uint64_t t1 = __builtin_readcyclecounter(), w1 = __builtin_amdgcn_s_memrealtime();
+        atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters), (unsigned long long)(t1 - clk_t0));
+        atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters) + 1, (unsigned long long)(w1 - clk_w0));
+    }
 #undef STREAM_TILE
 #undef STREAM_ISSUE_SETUP
 #undef STREAM_ISSUE
@@ -469,7 +487,7 @@ static void launch_stream_t(const uint8_t* a_codes, const uint8_t* a_scales, con
     const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
     hipLaunchKernelGGL((gemm_mxfp4_stream_kernel<OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st, a_codes,
                        a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, gm, nb);
+                       tiles_m, tiles_n, gm, nb, g_clock_counters);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>

@@ -39,6 +39,12 @@ void set_gemm_plan(int variant, int band_height);
 hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, uint32_t nb, float scale,
                                 void* out, int out_bf16, hipStream_t st);
 
+// measurement support: register-only loop of the FP4 matrix-core instruction (probe_kernels.hip); device counters
+// {shader-clock ticks, constant-clock ticks} that the streaming GEMM kernel and the probe add their blocks' run time to
+hipError_t launch_mfma_ceiling(const uint8_t* codes, const uint8_t* scales, uint32_t iterations, uint32_t blocks, float* sink,
+                               uint64_t* counters, hipStream_t st);
+void set_clock_counters(uint64_t* device_counters);
+
 // MXFP8 comparison path (E4M3 elements, E8M0 scale per 32)
 hipError_t launch_mxfp8_quant(const void* x, int64_t rows, int64_t k, int64_t ldx, uint8_t* codes, uint8_t* scales,
                               hipStream_t st);
