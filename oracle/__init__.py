@@ -21,7 +21,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # QUARTET_REF_LIB: another build of quartet_ref.c (the sanitizer leg of the tests loads an instrumented one)
+        path = os.environ.get("QUARTET_REF_LIB") or _build.build(force=False)
         _lib = ctypes.CDLL(path)
         _declare(_lib)
     return _lib
@@ -47,6 +48,7 @@ def _declare(L):
     L.quartet_ref_philox4x32_10.argtypes = [_p, _p, _p]
     L.quartet_ref_sr_draw.restype = _u32
     L.quartet_ref_sr_draw.argtypes = [_u64, _u32, _u64]
+    L.quartet_ref_sr_draws.argtypes = [_u64, _u32, _u64, _i64, _p]
     L.quartet_ref_sign_word.restype = _u32
     L.quartet_ref_sign_word.argtypes = [_u64]
     L.quartet_ref_hadamard32.argtypes = [_p, _u32]
@@ -136,6 +138,13 @@ def philox4x32_10(ctr, key):
 
 def sr_draw(seed, stream_id, L):
     return lib().quartet_ref_sr_draw(int(seed), int(stream_id), int(L))
+
+
+def sr_draws(seed, stream_id, L0, count):
+    """The 22-bit draws of positions L0 .. L0 + count - 1 (uint32 array)."""
+    out = np.zeros(int(count), dtype=np.uint32)
+    lib().quartet_ref_sr_draws(int(seed), int(stream_id), int(L0), int(count), _ptr(out))
+    return out
 
 
 def sign_word(seed):

@@ -15,6 +15,16 @@ FLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
          "-fno-fast-math", "-Wall", "-Wextra"]
 
 
+SANITIZE = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+
+
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (CPU only), for the tests' sanitizer leg."""
+    flags = [f for f in FLAGS if f != "-O2"] + SANITIZE
+    subprocess.run(["gcc"] + flags + [SRC, "-o", out_path, "-lm"], check=True)
+    return out_path
+
+
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB

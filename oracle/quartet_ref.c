@@ -174,6 +174,13 @@ uint32_t quartet_ref_sr_draw(uint64_t seed, uint32_t stream_id, uint64_t L) {
     return R >> 10;
 }
 
+/* The draws of `count` consecutive positions L0, L0 + 1, ...: quartet_ref_sr_draw in a loop (for the statistical pins). */
+void quartet_ref_sr_draws(uint64_t seed, uint32_t stream_id, uint64_t L0, int64_t count, uint32_t* out) {
+    int64_t i;
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < count; ++i) out[i] = quartet_ref_sr_draw(seed, stream_id, L0 + (uint64_t)i);
+}
+
 /* Sign word of the randomized Hadamard used by one backward pass with seed xi:
  * first output word of Philox at counter (0,0,0,0xFFFFFFFF) under the same key. */
 uint32_t quartet_ref_sign_word(uint64_t seed) {

@@ -8,7 +8,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def _redirect_binding_to_hostcheck_build():
+    """QUARTET_HOSTCHECK_DIR (set by tests/test_sanitizers.py for its child run only): a directory holding a copy of the
+    binding next to a host-only, sanitizer-instrumented build of the C ABI; tests that import the binding then drive that
+    build instead of the HIP library."""
+    d = os.environ.get("QUARTET_HOSTCHECK_DIR")
+    if not d:
+        return
+    import importlib.util
+    import paper_2505_14669_amd
+    spec = importlib.util.spec_from_file_location("paper_2505_14669_amd.binding", os.path.join(d, "binding.py"))
+    mod = importlib.util.module_from_spec(spec)
+    sys.modules["paper_2505_14669_amd.binding"] = mod
+    spec.loader.exec_module(mod)
+    paper_2505_14669_amd.binding = mod
+
+
 def pytest_configure(config):
+    _redirect_binding_to_hostcheck_build()
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 

@@ -89,3 +89,38 @@ def scales_to_tiled(scales_row_major, fill=0xFF):
 
 def scales_from_tiled(tiled, rows, k):
     return np.asarray(tiled, dtype=np.uint8)[scale_tile_index(rows, k)] if rows * k else np.zeros((rows, k // 32), np.uint8)
+
+
+# ---- per-element error bounds for products accumulated in fp32 (used next to the Frobenius bar)
+
+def gemm_abs_products(a_codes, a_scales, b_codes, b_scales):
+    """sum_k |dec(A)[m,k]| |dec(B)[n,k]| in fp64: what a rounding error of the accumulation is relative to."""
+    return np.abs(decode(a_codes, a_scales)) @ np.abs(decode(b_codes, b_scales)).T
+
+
+def gemm_elem_bound(abs_products, k, alpha=1.0):
+    """Bound on |fp32-accumulated product - exact product| per element.  The products of E2M1 values and powers
+    of two are exact; the matrix cores add 64 of them to the fp32 accumulator per instruction, K/64 instructions in
+    a row, and each addition rounds (or truncates) the running sum once: at most 2^-23 of its magnitude, which never
+    exceeds sum |a||b|.  Three more roundings of the same size cover the multiply by alpha, the result's own rounding
+    and the conversion of the oracle's fp64 value.  c = K/64 + 3 ulps of 2^-23: a worst-case bound, not a fit."""
+    return abs(alpha) * (k // 64 + 3) * 2.0 ** -23 * abs_products
+
+
+def grad_elem_bound(product_bound, abs_exact_product, scale, block=32):
+    """The same bound carried through the gradient epilogue scale * H_block(g . mask) along the last axis: a transformed
+    element is a signed sum of its block's inputs over sqrt(block), so the input bounds add up; the log2(block)
+    butterfly stages and the two multiplies round log2(block) + 2 more times, each at most 2^-24 of a magnitude that
+    the block's sum of |inputs| over sqrt(block) bounds (12 x 2^-24 taken, enough up to block = 256)."""
+    m, n = product_bound.shape
+    per_block = (product_bound + 12 * 2.0 ** -24 * abs_exact_product).reshape(m, n // block, block).sum(-1, keepdims=True)
+    return np.broadcast_to(abs(scale) / np.sqrt(float(block)) * per_block, (m, n // block, block)).reshape(m, n)
+
+
+def worst_excess(got, want, bound):
+    """max over elements of |got - want| / bound (elements with a zero bound must agree exactly)."""
+    err = np.abs(np.asarray(got, dtype=np.float64) - np.asarray(want, dtype=np.float64))
+    zero = bound == 0
+    if np.any(err[zero] != 0):
+        return np.inf
+    return float(np.max(err[~zero] / bound[~zero])) if np.any(~zero) else 0.0

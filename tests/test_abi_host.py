@@ -44,10 +44,19 @@ def test_sign_word_is_philox_of_the_seed():
         assert binding.quartet_sign_word(seed) == oracle.sign_word(seed)
 
 
+def launches(q):
+    """kernel launches so far, if the library is the host-only build with counting stand-ins for the launchers; else None"""
+    try:
+        return q._lib.quartet_hostcheck_launches()
+    except AttributeError:
+        return None
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     from paper_2505_14669_amd import binding as q
     P = 0x10000  # fake, aligned, never dereferenced: validation fails first
     E = q.QUARTET_EINVAL
+    before = launches(q)
     assert q.quartet_quant_fwd(None, 4, 32, 32, 0, P, P, P, 0) == E
     assert q.quartet_quant_fwd(P, 4, 48, 48, 0, P, P, P, 0) == E          # k % 32
     assert q.quartet_quant_fwd(P, 4, 64, 32, 0, P, P, P, 0) == E          # ldx < k
@@ -85,6 +94,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert q.quartet_linear_bwd(P, 64, 64, 96, P, P, P, P, P, P, 0, 0, P, P, 0, None, need, 0) == E
     assert q.quartet_linear_bwd(P, 64, 60, 96, P, P, P, P, P, P, 0, 0, P, P, 0, 0x10000, need, 0) == E
     assert q.quartet_last_hip_error() == 0
+    assert launches(q) == before          # (host-only build) nothing was launched by a rejected call
 
 
 def test_empty_problems_are_accepted_without_a_gpu():
@@ -141,3 +151,16 @@ def test_static_scratch_backward_rejects_layers_beyond_its_array_on_the_host():
     assert q.quartet_linear_bwd_static(*args(48, 32, 32)) == q.QUARTET_EINVAL
     assert q.quartet_linear_bwd_static(None, 32, 32, 32, P, P, P, P, P, P, 0, 0, P, P, 0, 0) == q.QUARTET_EINVAL
     assert q.quartet_debug_set_gemm_plan(3, 0) == q.QUARTET_EINVAL and q.quartet_debug_set_gemm_plan(-1, 0) == q.QUARTET_OK
+
+
+def test_profile_record_can_be_set_up_and_dropped_without_a_gpu():
+    # with no GPU the events cannot be created: the call must fail cleanly and free what it made (last in this file: it
+    # leaves a HIP error in the thread's last-error slot, which the tests above expect to be clear)
+    from paper_2505_14669_amd import binding as q
+    assert q.quartet_profile_enable(-1) == q.QUARTET_EINVAL
+    rc = q.quartet_profile_enable(3)
+    assert rc in (q.QUARTET_OK, q.QUARTET_EHIP)
+    assert q.quartet_profile_enable(0) == q.QUARTET_OK
+    assert q.quartet_profile_read(None, None, 0) == 0
+    assert q.quartet_profile_clock(None) == q.QUARTET_OK and q.quartet_profile_clock(0x10004) == q.QUARTET_EINVAL
+    assert q.quartet_probe_mfma_ceiling(None, 0x10000, 1, 1, 0x10000, None, 0) == q.QUARTET_EINVAL

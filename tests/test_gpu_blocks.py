@@ -4,6 +4,7 @@ bytes and mask words bit-exact, GEMM-derived outputs within a relative Frobenius
 import numpy as np
 import pytest
 
+import indep
 import oracle
 from paper_2505_14669_amd import synth
 
@@ -130,6 +131,10 @@ def test_gemm_grad_block_fused(G, mnk, block, gemm_variant):
     want = oracle.grad_epilogue_block(acc, mask, block)
     got = G.gemm_grad_block(ac, asc, bc, bsc, block, mask, oracle.FL_16_9)
     assert rel_fro(got, want) < FRO_TOL
+    # element by element: (K/64 + 3) 2^-23 sum |a||b| per product element, carried through the block's Hadamard transform
+    absp = indep.gemm_abs_products(ac, asc, bc, bsc)
+    bound = indep.grad_elem_bound(indep.gemm_elem_bound(absp, k), absp, oracle.FL_16_9, block)
+    assert indep.worst_excess(got, want, bound) <= 1.0
     plain = G.gemm(ac, asc, bc, bsc)
     two_steps = G.grad_epilogue_block(plain, mask, block, oracle.FL_16_9)
     assert np.array_equal(got.view(np.uint32), two_steps.view(np.uint32))
@@ -137,6 +142,8 @@ def test_gemm_grad_block_fused(G, mnk, block, gemm_variant):
     assert np.array_equal(got_bf, synth.f32_to_bf16(got))
     got_nomask = G.gemm_grad_block(ac, asc, bc, bsc, block, None, 1.0)
     assert rel_fro(got_nomask, oracle.grad_epilogue_block(acc, None, block, 1.0)) < FRO_TOL
+    bound = indep.grad_elem_bound(indep.gemm_elem_bound(absp, k), absp, 1.0, block)
+    assert indep.worst_excess(got_nomask, oracle.grad_epilogue_block(acc, None, block, 1.0), bound) <= 1.0
 
 
 @pytest.mark.parametrize("block", BLOCKS)
@@ -151,12 +158,28 @@ def test_linear_block(G, block):
     for key in ctx_ref:
         same(ctx[key], ctx_ref[key], f"ctx {key}")
     assert rel_fro(G.to_host(lin.y, np.float32), y_ref) < FRO_TOL
+    xq, wq = (ctx_ref["xq_codes"], ctx_ref["xq_scales"]), (ctx_ref["wq_codes"], ctx_ref["wq_scales"])
+    assert indep.worst_excess(G.to_host(lin.y, np.float32), y_ref,
+                              indep.gemm_elem_bound(indep.gemm_abs_products(*xq, *wq), i)) <= 1.0
     dy = G.to_dev(L["dy"])
+    seed = 2 ** 40 + 5
+    sws = oracle.sign_words(seed)
     for rounding in (0, 1):
-        lin.bwd(dy, 2 ** 40 + 5, rounding)
-        dx_ref, dw_ref = oracle.linear_bwd_block(L["dy"], ctx_ref, block, 2 ** 40 + 5, rounding)
+        lin.bwd(dy, seed, rounding)
+        dx_ref, dw_ref = oracle.linear_bwd_block(L["dy"], ctx_ref, block, seed, rounding)
         assert rel_fro(G.to_host(lin.dx, np.float32), dx_ref) < FRO_TOL
         assert rel_fro(G.to_host(lin.dw, np.float32), dw_ref) < FRO_TOL
+        # element by element, with the sums of magnitudes of the two products from the oracle's quantized operands
+        gq = oracle.quant_bwd_sr_block(L["dy"], block, sws, seed, 0, rounding)
+        wt = oracle.requant_transpose_sr_block(*wq, block, sws, seed, 1, rounding)
+        absp = indep.gemm_abs_products(*gq, *wt)
+        assert indep.worst_excess(G.to_host(lin.dx, np.float32), dx_ref,
+                                  indep.grad_elem_bound(indep.gemm_elem_bound(absp, o), absp, oracle.FL_16_9, block)) <= 1.0
+        gt = oracle.quant_bwd_sr_block(L["dy"], block, sws, seed, 2, rounding, transpose=True)
+        xt = oracle.requant_transpose_sr_block(*xq, block, sws, seed, 3, rounding)
+        absp = indep.gemm_abs_products(*gt, *xt)
+        assert indep.worst_excess(G.to_host(lin.dw, np.float32), dw_ref,
+                                  indep.grad_elem_bound(indep.gemm_elem_bound(absp, t), absp, oracle.FL_16_9, block)) <= 1.0
 
 
 def test_block_32_entry_points_are_the_plain_ones(G):

@@ -10,6 +10,7 @@ import pytest
 
 import oracle
 from paper_2505_14669_amd import synth
+import indep
 from indep import scales_from_tiled, scales_to_tiled
 
 pytestmark = pytest.mark.gpu
@@ -27,6 +28,10 @@ def slabs(rows, width=64, n=4, seed=0):
     rng = np.random.default_rng(seed)
     starts = [0, rows - width] + [int(s) for s in rng.integers(1, rows - width - 1, size=n - 2)]
     return [(s, s + width) for s in starts]
+
+
+# The per-element bar next to the Frobenius one: |got - want| <= (K/64 + 3) 2^-23 sum_k |a||b| (indep.gemm_elem_bound: one
+# rounding of the fp32 accumulator per matrix-core instruction), carried through the Hadamard epilogue for the gradients.
 
 
 def rel_fro(a, b):
@@ -55,10 +60,21 @@ def test_quantizer_sweep_largest_matrix(G):
             assert np.array_equal(got[0][r0:r1], want[0]) and np.array_equal(got[1][r0:r1], want[1])
 
 
+def blocked_products(a, b, block=2048):
+    """a @ b.T in fp64, by row blocks (keeps the temporaries small)"""
+    out = np.empty((a.shape[0], b.shape[0]), dtype=np.float64)
+    bt = np.ascontiguousarray(b.T)
+    for r0 in range(0, a.shape[0], block):
+        out[r0:r0 + block] = a[r0:r0 + block] @ bt
+    return out
+
+
+# all six product shapes of configuration 4: forward, dx and dW of the 4096 -> 4096, 4096 -> 11008 and 11008 -> 4096 layers
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("mnk", [(16384, 4096, 4096), (16384, 11008, 4096), (16384, 4096, 11008),
-                                 (4096, 4096, 16384), (11008, 4096, 16384)])
+                                 (4096, 4096, 16384), (11008, 4096, 16384), (4096, 11008, 16384)])
 def test_gemm_config4_shapes(G, mnk):
-    # operands are seeded random codes and scales (not produced by the HIP path)
+    # operands are seeded random codes and scales (not produced by the HIP path); the result buffer starts as NaN
     m, n, k = mnk
     rng = np.random.default_rng(m + n + k)
     ac = rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8)
@@ -66,11 +82,21 @@ def test_gemm_config4_shapes(G, mnk):
     asc = rng.integers(115, 135, size=(m, k // 32), dtype=np.uint8)
     bsc = rng.integers(115, 135, size=(n, k // 32), dtype=np.uint8)
     got = G.gemm(ac, asc, bc, bsc)
-    for r0, r1 in slabs(m, width=16, n=3, seed=k):
-        want = oracle.mxfp4_gemm(ac, asc, bc, bsc, rows=(r0, r1))[r0:r1]
-        assert rel_fro(got[r0:r1], want) < FRO_TOL
+    assert np.isfinite(got).all()                           # no tile was skipped
+    # 256 random full rows against the oracle's fp64 product
+    rows = np.sort(rng.choice(m, size=256, replace=False))
+    want_rows = oracle.mxfp4_gemm(ac[rows], asc[rows], bc, bsc)
+    assert rel_fro(got[rows], want_rows) < FRO_TOL
+    # the whole matrix against numpy's fp64 product of independently decoded operands, and element by element
+    a, b = indep.decode(ac, asc), indep.decode(bc, bsc)
+    want = blocked_products(a, b)
+    assert rel_fro(want[rows], want_rows) < 1e-12           # the two references (different summation orders) agree
+    assert rel_fro(got, want) < FRO_TOL
+    bound = indep.gemm_elem_bound(blocked_products(np.abs(a), np.abs(b)), k)
+    assert indep.worst_excess(got, want, bound) <= 1.0
 
 
+@pytest.mark.timeout(1200)
 @pytest.mark.parametrize("config,layer", [(2, 0), (3, 2), (4, 4)])
 def test_linear_layers_full_size(G, config, layer):
     # config 2 q-projection, config 3 down-projection, config 4 gate-projection (the largest layer)
@@ -81,32 +107,56 @@ def test_linear_layers_full_size(G, config, layer):
     lin = G.Linear(L["x"], L["w"])
     lin.fwd()
     ctx = lin.ctx_host()
-    # forward context on slabs
-    for r0, r1 in slabs(t, n=3, seed=1):
-        c, s, m = oracle.quant_fwd(L["x"], rows_range=(r0, r1))
-        assert np.array_equal(ctx["xq_codes"][r0:r1], c) and np.array_equal(ctx["xq_scales"][r0:r1], s)
-        assert np.array_equal(ctx["x_mask"][r0:r1], m)
-    wc, ws, wm = oracle.quant_fwd(L["w"])                      # weights: whole matrix
+    # forward context: whole matrices
+    wc, ws, wm = oracle.quant_fwd(L["w"])
     assert np.array_equal(ctx["wq_codes"], wc) and np.array_equal(ctx["wq_scales"], ws)
     assert np.array_equal(ctx["w_mask"], wm)
-    xc, xs, xm = oracle.quant_fwd(L["x"])                      # needed whole for the dW chain
+    xc, xs, xm = oracle.quant_fwd(L["x"])
     assert np.array_equal(ctx["xq_codes"], xc) and np.array_equal(ctx["xq_scales"], xs)
+    assert np.array_equal(ctx["x_mask"], xm)
+    # y: 16 slabs of 16 rows (256 rows) against the oracle's product; the whole matrix, element by element, against numpy's
+    # fp64 product of independently decoded operands
     y = G.to_host(lin.y, np.float32)
-    for r0, r1 in slabs(t, width=16, n=3, seed=2):
+    assert np.isfinite(y).all()
+    for r0, r1 in slabs(t, width=16, n=16, seed=2):
         want = oracle.mxfp4_gemm(xc, xs, wc, ws, rows=(r0, r1))[r0:r1]
         assert rel_fro(y[r0:r1], want) < FRO_TOL
+    xd, wd = indep.decode(xc, xs), indep.decode(wc, ws)
+    y_np = blocked_products(xd, wd)
+    assert rel_fro(y, y_np) < FRO_TOL
+    assert indep.worst_excess(y, y_np, indep.gemm_elem_bound(blocked_products(np.abs(xd), np.abs(wd)), i)) <= 1.0
+    del xd, wd, y_np
     # backward
     lin.bwd(G.to_dev(L["dy"]), seed, rounding)
     dx, dw = G.to_host(lin.dx, np.float32), G.to_host(lin.dw, np.float32)
+    assert np.isfinite(dx).all() and np.isfinite(dw).all()
+    c169 = float(np.float32(16.0 / 9.0))
+
+    def numpy_gradient(a_q, b_q, mask, k):
+        """c169 * H_32((dec(A) dec(B)^T) . mask) in fp64 from independently decoded operands, and its element bound"""
+        ad, bd = indep.decode(*a_q), indep.decode(*b_q)
+        prod = blocked_products(ad, bd)
+        absp = blocked_products(np.abs(ad), np.abs(bd))
+        bits = ((mask[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(prod.shape).astype(bool)
+        want = c169 * indep.dense_hadamard_rows(np.where(bits, prod, 0.0))
+        return want, indep.grad_elem_bound(indep.gemm_elem_bound(absp, k), absp, c169)
+
     wt = oracle.requant_transpose_sr(wc, ws, sw, seed, 1, rounding)                 # [in, out]
-    for r0, r1 in slabs(t, width=16, n=3, seed=3):
+    for r0, r1 in slabs(t, width=16, n=16, seed=3):
         gq = oracle.quant_bwd_sr(L["dy"], sw, seed, 0, rounding, rows_range=(r0, r1))
         dxq = oracle.mxfp4_gemm(gq[0], gq[1], wt[0], wt[1]).astype(np.float32)
         want = oracle.grad_epilogue(dxq, xm[r0:r1])
         assert rel_fro(dx[r0:r1], want) < FRO_TOL
+    gq = oracle.quant_bwd_sr(L["dy"], sw, seed, 0, rounding)
+    want, bound = numpy_gradient(gq, wt, xm, o)
+    assert rel_fro(dx, want) < FRO_TOL and indep.worst_excess(dx, want, bound) <= 1.0
+    del gq, wt, want, bound
     xt = oracle.requant_transpose_sr(xc, xs, sw, seed, 3, rounding)                 # [in, tokens]
-    for r0, r1 in slabs(o, width=16, n=3, seed=4):
+    for r0, r1 in slabs(o, width=16, n=16, seed=4):
         gt = oracle.quant_bwd_sr(L["dy"], sw, seed, 2, rounding, transpose=True, rows_range=(r0, r1))
         dwq = oracle.mxfp4_gemm(gt[0], gt[1], xt[0], xt[1]).astype(np.float32)
         want = oracle.grad_epilogue(dwq, wm[r0:r1])
         assert rel_fro(dw[r0:r1], want) < FRO_TOL
+    gt = oracle.quant_bwd_sr(L["dy"], sw, seed, 2, rounding, transpose=True)
+    want, bound = numpy_gradient(gt, xt, wm, t)
+    assert rel_fro(dw, want) < FRO_TOL and indep.worst_excess(dw, want, bound) <= 1.0

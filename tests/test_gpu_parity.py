@@ -8,6 +8,7 @@ import pytest
 
 import oracle
 from paper_2505_14669_amd import synth
+import indep
 from indep import scale_tiled_bytes as q_scale_bytes, scales_from_tiled, scales_to_tiled
 
 pytestmark = pytest.mark.gpu
@@ -20,6 +21,15 @@ def rel_fro(a, b):
     b = np.asarray(b, dtype=np.float64)
     den = np.linalg.norm(b)
     return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a)
+
+
+def within_elem_bound(got, want, abs_products, k, alpha=1.0, grad_scale=None, block=32):
+    """the per-element bar next to the Frobenius one: (K/64 + 3) 2^-23 sum |a||b| per product element
+    (indep.gemm_elem_bound), carried through the Hadamard epilogue when grad_scale is given"""
+    bound = indep.gemm_elem_bound(abs_products, k, alpha)
+    if grad_scale is not None:
+        bound = indep.grad_elem_bound(bound, abs_products, grad_scale, block)
+    return indep.worst_excess(got, want, bound) <= 1.0
 
 
 def same(a, b, what):
@@ -186,6 +196,7 @@ def test_gemm_random(G, mnk, gemm_variant):
     want = oracle.mxfp4_gemm(ac, asc, bc, bsc, alpha=0.75)
     got = G.gemm(ac, asc, bc, bsc, alpha=0.75)
     assert rel_fro(got, want) < FRO_TOL
+    assert within_elem_bound(got, want, indep.gemm_abs_products(ac, asc, bc, bsc), k, alpha=0.75)
     got_ld = G.gemm(ac, asc, bc, bsc, alpha=0.75, ldd=n + 5)
     assert np.array_equal(got_ld[:, :n], got) and np.all(np.isnan(got_ld[:, n:]))
     got_bf = synth.bf16_to_f32(G.gemm(ac, asc, bc, bsc, alpha=0.75, bf16=True))
@@ -206,6 +217,8 @@ def test_gemm_grad_fused(G, mnk, gemm_variant):
     want = oracle.grad_epilogue(acc, mask)
     got = G.gemm_grad(ac, asc, bc, bsc, mask, oracle.FL_16_9)
     assert rel_fro(got, want) < FRO_TOL
+    absp = indep.gemm_abs_products(ac, asc, bc, bsc)
+    assert within_elem_bound(got, want, absp, k, grad_scale=oracle.FL_16_9)
     # the header promises the same bits as the library's own two separate steps
     two_step = G.grad_epilogue(G.gemm(ac, asc, bc, bsc), mask, oracle.FL_16_9)
     assert np.array_equal(got.view(np.uint32), two_step.view(np.uint32))
@@ -215,6 +228,7 @@ def test_gemm_grad_fused(G, mnk, gemm_variant):
     assert np.array_equal(got_bf, synth.f32_to_bf16(got))
     got_nomask = G.gemm_grad(ac, asc, bc, bsc, None, 1.0)
     assert rel_fro(got_nomask, oracle.grad_epilogue(acc, None, 1.0)) < FRO_TOL
+    assert within_elem_bound(got_nomask, oracle.grad_epilogue(acc, None, 1.0), absp, k, grad_scale=1.0)
 
 
 @pytest.mark.parametrize("shape", [(1, 32), (6, 96), (77, 160), (256, 512)])
@@ -291,12 +305,25 @@ def _check_linear(G, L, seed, roundings=(0, 1)):
     for key in ctx_ref:
         same(ctx[key], ctx_ref[key], f"ctx {key}")
     assert rel_fro(G.to_host(lin.y, np.float32), y_ref) < FRO_TOL
+    xq, wq = (ctx_ref["xq_codes"], ctx_ref["xq_scales"]), (ctx_ref["wq_codes"], ctx_ref["wq_scales"])
+    t, i, o = L["x"].shape[0], L["x"].shape[1], L["w"].shape[0]
+    assert within_elem_bound(G.to_host(lin.y, np.float32), y_ref, indep.gemm_abs_products(*xq, *wq), i)
     dy = G.to_dev(L["dy"])
+    sw = oracle.sign_word(seed)
     for rounding in roundings:
         lin.bwd(dy, seed, rounding)
         dx_ref, dw_ref = oracle.linear_bwd(L["dy"], ctx_ref, seed, rounding)
         assert rel_fro(G.to_host(lin.dx, np.float32), dx_ref) < FRO_TOL
         assert rel_fro(G.to_host(lin.dw, np.float32), dw_ref) < FRO_TOL
+        # element by element: the bound needs the two products' sums of magnitudes, from the oracle's quantized operands
+        gq = oracle.quant_bwd_sr(L["dy"], sw, seed, 0, rounding)
+        wt = oracle.requant_transpose_sr(*wq, sw, seed, 1, rounding)
+        assert within_elem_bound(G.to_host(lin.dx, np.float32), dx_ref, indep.gemm_abs_products(*gq, *wt), o,
+                                 grad_scale=oracle.FL_16_9)
+        gt = oracle.quant_bwd_sr(L["dy"], sw, seed, 2, rounding, transpose=True)
+        xt = oracle.requant_transpose_sr(*xq, sw, seed, 3, rounding)
+        assert within_elem_bound(G.to_host(lin.dw, np.float32), dw_ref, indep.gemm_abs_products(*gt, *xt), t,
+                                 grad_scale=oracle.FL_16_9)
 
 
 def test_linear_config1_full(G):

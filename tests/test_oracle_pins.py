@@ -138,6 +138,58 @@ def test_sr_draws_look_uniform():
     assert np.all(np.abs(c - np.eye(4)) < 5 / np.sqrt(d.shape[0]))
 
 
+def test_sr_neighbour_decisions_depend_at_the_2_to_minus_8_level_and_no_more():
+    # The four elements served by one Philox word own one byte each as the leading 8 bits of their draw; the 14 bits below
+    # are the neighbours' bytes.  Three pins on 4 x 10^7 draws (10^7 words):
+    # (1) the structure itself, exactly: bits 13..6 of element t's draw are element t-1's leading byte and bits 5..0 are
+    #     the top six bits of element t-2's (so the dependence is there, and only below the 8th bit);
+    # (2) the leading bytes of a word's four elements are jointly uniform (chi-square on every pair's 256 x 256 table), so
+    #     decisions are independent as far as their leading 8 bits decide them;
+    # (3) the consequence: for any two thresholds |P(A and B) - P(A) P(B)| <= 2^-8 / 4 (a neighbour's byte moves a
+    #     decision's probability by at most one leading-byte value, 2^-8, and P(A)(1 - P(A)) <= 1/4), reached by the
+    #     adversarial pair: A = "t-1 rounds up at f = 1/2" (the top bit of its byte), B = "t rounds up" with the threshold
+    #     in the middle of t's second byte -- there B equals A whenever t's leading byte sits on the threshold.
+    # Sampling noise of a covariance of two events over n pairs is at most 0.5 / sqrt(n); 6 of those are allowed.
+    words = 10 ** 7
+    d = oracle.sr_draws(0xC0FFEE1234, 2, 0, 4 * words).reshape(words, 4).astype(np.int64)
+    assert np.array_equal(d[:5].ravel(), [oracle.sr_draw(0xC0FFEE1234, 2, L) for L in range(20)])   # the bulk entry is the single one
+    assert d.min() >= 0 and d.max() < 2 ** 22
+    lead = d >> 14
+    for t in range(4):                                                          # (1)
+        assert np.array_equal((d[:, t] >> 6) & 0xFF, lead[:, (t - 1) % 4])
+        assert np.array_equal(d[:, t] & 0x3F, lead[:, (t - 2) % 4] >> 2)
+    from scipy.stats import chi2                                                # (2)
+    for t in range(4):
+        for u in range(t + 1, 4):
+            table = np.bincount(lead[:, t] * 256 + lead[:, u], minlength=65536)
+            stat = float(((table - words / 65536.0) ** 2).sum() / (words / 65536.0))
+            assert chi2.cdf(stat, 65535) < 1 - 1e-6, (t, u, stat)
+    noise = 6 * 0.5 / np.sqrt(words)                                            # (3)
+
+    def cov(up_a, up_b):
+        return float(np.mean(up_a & up_b) - np.mean(up_a) * np.mean(up_b))
+
+    up = lambda r, F: r >= (2 ** 22 - F)      # the decision of an element with fraction f, F = floor(f 2^22)
+    for t in range(4):
+        prev = (t - 1) % 4
+        a = up(d[:, prev], 2 ** 21)
+        for j in (3, 100, 250):
+            b = up(d[:, t], 2 ** 22 - (j * 2 ** 14 + 2 ** 13))
+            on = lead[:, t] == j
+            assert on.sum() > words / 512 and np.array_equal(b[on], a[on])       # on the threshold byte: B is A
+            assert np.array_equal(b[~on], lead[~on, t] > j)                      # elsewhere: the leading byte alone
+            assert abs(cov(a, b) - 2.0 ** -10) < noise
+    rng = np.random.default_rng(5)
+    for _ in range(12):
+        t, u = rng.choice(4, size=2, replace=False)
+        Fa, Fb = (int(v) for v in rng.integers(1, 2 ** 22, size=2))
+        assert abs(cov(up(d[:, t], Fa), up(d[:, u], Fb))) <= 2.0 ** -10 + noise
+    # different words (neighbouring words of one call, and words of different calls): independent
+    for (t, u, shift) in ((3, 0, 1), (0, 0, 1), (2, 1, 4), (1, 3, 7)):
+        a, b = up(d[:-shift, t], 2 ** 21), up(d[shift:, u], 2 ** 22 - (77 * 2 ** 14 + 2 ** 13))
+        assert abs(cov(a, b)) < noise
+
+
 # ------------------------------------------------------- stochastic rounding
 
 @pytest.mark.parametrize("v", [0.1, 0.26, 0.49, 0.5001, 0.9, 1.2, 1.74, 2.1, 2.9, 3.01, 4.5, 5.99, 1e-6])
