@@ -280,11 +280,12 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, voi
 // are handled alike (group-combining stages inside the lane, then the 32-point stages of each slice).
 // LDS image: row r at r*128 floats, slice j of rows 4..7 stored at slice position j^1 (the two half-waves of a
 // write then hit different bank halves).
-template <int TM, bool OUT_BF16, bool FUSED, bool FULL>
-__device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][4], float* wbuf, void* d, uint32_t ldd,
+template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
+__device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
                                                  const uint32_t* mask, float alpha, uint32_t row_base,
                                                  uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane, uint32_t nb) {
-    constexpr uint32_t TN = 4, PASSES = TM * 4, W = 128;
+    static_assert(TN == 2 || TN == 4, "the slice swap of rows 4..7 pairs the slices up");
+    constexpr uint32_t PASSES = TM * 4, W = TN * 32;
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
     const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
     const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;
@@ -296,7 +297,7 @@ __device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][4], float* wbuf
     const uint32_t rswz = sub >> 2;
     uint32_t mw[PASSES][TN];
     if (FUSED) {
-        const bool mvec = FULL && (mask_ld & 3u) == 0u && (reinterpret_cast<uintptr_t>(mask) & 15u) == 0u;   // wave-uniform
+        const bool mvec = FULL && TN == 4 && (mask_ld & 3u) == 0u && (reinterpret_cast<uintptr_t>(mask) & 15u) == 0u;   // wave-uniform
 #pragma unroll
         for (uint32_t p = 0; p < PASSES; ++p) {
             const uint32_t grow = row_base + p * 8u + sub;
@@ -346,14 +347,14 @@ __device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][4], float* wbuf
                     vv[j + 1][e] = a - b;
                 }
         }
-        if (FUSED && nb >= 4u) {
+        if (FUSED && nb >= 4u && TN >= 4) {
 #pragma unroll
             for (uint32_t j = 0; j < 2; ++j)
 #pragma unroll
                 for (uint32_t e = 0; e < 4; ++e) {
-                    const float a = vv[j][e], b = vv[j + 2u][e];
+                    const float a = vv[j][e], b = vv[(j + 2u) % TN][e];
                     vv[j][e] = a + b;
-                    vv[j + 2u][e] = a - b;
+                    vv[(j + 2u) % TN][e] = a - b;
                 }
         }
 #pragma unroll

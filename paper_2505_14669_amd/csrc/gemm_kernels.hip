@@ -444,8 +444,8 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         STREAM_TILE(cv, m0, n0)
         const uint32_t row_base = m0 + wm0, col_base = n0 + wn0;
         const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n && (!FUSED || mask != nullptr);
-        if (full) store_tile_rows8<TM, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
-        else store_tile_rows8<TM, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
     if (clock_counters && tid == 0) {
@@ -463,6 +463,228 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
 #undef STREAM_SCALES
 #undef STREAM_MF
 #undef STREAM_BODY
+}
+
+// ---------------------------------------------------------------------------------------------
+// The streaming design for other tile shapes: wave tile (TM*32) x (TN*32), block tile (64 TM) x (64 TN), for problems
+// whose 256 x 256 tiles would leave compute units idle.  Same ring, same issue cursor, same epilogue; the stage's
+// instruction order is generated from the tile shape instead of written out: after matrix-core instruction number idx of
+// a stage come, in this order, the fragment reads of the stage's second K-step (RPS per slot from slot 0), the stage's
+// LDS-direct loads (spread over the slots up to the barrier), the wait and the barrier POST instructions before the
+// stage's end, and behind the barrier the next stage's first fragments (and, on odd stages, the next K-quad's scales).
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
+__global__ void __launch_bounds__(256)
+gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
+                              const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
+                              uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
+                              const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
+    constexpr uint32_t BM = 64 * TM, BN = 64 * TN;
+    static_assert(BM % 128 == 0 && BN % 128 == 0, "a wave's four scale tiles must belong to one operand");
+    constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
+    constexpr uint32_t STAGE = CODES + 256;              // + room for 16 scale tiles of 256 B (one KB per wave)
+    constexpr uint32_t D = kRing - 1;
+    constexpr uint32_t EPI = 4u * TN * 64u;              // 16-byte chunks of epilogue scratch: 8 rows x TN*32 floats per wave
+    constexpr uint32_t LA = BM / 64, LB = BN / 64, NL = LA + LB;   // LDS-direct loads of codes per wave per stage
+    constexpr uint32_t NT = (BM + BN) / 32;              // scale tiles per K-quad: A's, then B's
+    constexpr int NM = TM * TN, R = TM + TN;             // matrix-core instructions and fragment reads per K-step
+    constexpr int POST = NM >= 16 ? 8 : (NM >= 8 ? 6 : 3);   // matrix-core instructions behind the barrier
+    constexpr int P = 2 * NM - POST;                     // slots in front of the barrier
+    constexpr int RPS = (2 * R > NM) ? 2 : 1;            // second-K-step fragment reads per slot
+    constexpr int RS_END = (R + RPS - 1) / RPS;          // first slot without such a read
+    static_assert(RS_END <= NM && RS_END < P, "the fragments of the second K-step must be read during the first");
+    __shared__ uint4 lds[kRing * STAGE + EPI];
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t total_tiles = tiles_m * tiles_n, G = gridDim.x;
+    const uint32_t per = total_tiles >> 3, rem = total_tiles & 7u;
+    const uint32_t GM = band_height;
+    const uint32_t wm0 = (wave >> 1) * (TM * 32u), wn0 = (wave & 1u) * (TN * 32u);
+    const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;
+    // scale tiles 4 wave .. 4 wave + 3 of [A's | B's] are this wave's to fetch (waves past the last tile fetch nothing real:
+    // their load is out of range and delivers zeros, which keeps every wave's count of loads the same)
+    const bool has_scales = 4u * wave < NT, scales_of_a = 4u * wave < BM / 32u;
+    const uint32_t stile0 = scales_of_a ? 4u * wave : 4u * wave - BM / 32u;
+
+#define TILE_ORIGIN(V, M0, N0)                                                                          \
+    {                                                                                                   \
+        const uint32_t v_ = (V);                                                                        \
+        if (v_ < total_tiles) {                                                                         \
+            const uint32_t xcd_ = v_ & 7u;                                                              \
+            const uint32_t tile_ = xcd_ * per + (xcd_ < rem ? xcd_ : rem) + (v_ >> 3);                  \
+            const uint32_t band_ = tile_ / (GM * tiles_n);                                              \
+            const uint32_t band_rows_ = (tiles_m - band_ * GM) < GM ? (tiles_m - band_ * GM) : GM;      \
+            const uint32_t in_band_ = tile_ - band_ * GM * tiles_n;                                     \
+            M0 = (band_ * GM + in_band_ % band_rows_) * BM;                                             \
+            N0 = (in_band_ / band_rows_) * BN;                                                          \
+        } else {                                                                                        \
+            M0 = m; N0 = n;                                                                             \
+        }                                                                                               \
+    }
+    uint32_t iv = blockIdx.x, ist = 0u;                  // issue cursor: the tile and stage the next loads belong to
+    v4i_t res_a, res_b, res_s;
+#define ISSUE_SETUP()                                                                                   \
+    {                                                                                                   \
+        uint32_t m0_, n0_;                                                                              \
+        TILE_ORIGIN(iv, m0_, n0_)                                                                       \
+        const uint32_t rows_a_ = (m - m0_) < BM ? (m - m0_) : BM, rows_b_ = (n - n0_) < BN ? (n - n0_) : BN; \
+        res_a = make_rsrc_words(a_codes + (size_t)m0_ * kb, rows_a_ * kb);                              \
+        res_b = make_rsrc_words(b_codes + (size_t)n0_ * kb, rows_b_ * kb);                              \
+        const uint32_t srow0_ = scales_of_a ? m0_ : n0_, srows_ = scales_of_a ? rows_a_ : rows_b_;      \
+        res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0_ >> 5) * kq * 256u, \
+                                has_scales ? ((srows_ + 31u) >> 5) * kq * 256u : 0u);                   \
+    }
+    ISSUE_SETUP()
+
+    const uint32_t drow = wave * 16u + (lane >> 2);
+    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
+    const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
+    const uint32_t gstep = 64u * kb;
+    const uint32_t soff = ((stile0 + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
+    const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
+    const uint32_t swz = (lrow >> 2) & 3u;
+    const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
+    const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
+    const uint32_t sb_base = CODES * 4u + (BM / 32u) * 64u + (wn0 >> 5) * 64u + lane;
+
+    const uint32_t stages = (k + 127u) >> 7;
+    const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);
+    uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
+    uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+
+// code load J (0 .. LA-1: A rows, LA .. NL-1: B rows) or the scale tiles (J == NL) of the cursor's stage into ring slot SLOT
+#define ISSUE(SLOT, J)                                                                                  \
+    {                                                                                                   \
+        const uint32_t slot_ = lds0 + ((SLOT) * STAGE + wave * 64u) * 16u;                              \
+        if ((uint32_t)(J) < NL) {                                                                       \
+            const uint32_t base_ = (ist * 64u + dcol * 16u < kb) ? goff + ist * 64u : kOutOfRange;      \
+            const uint32_t jj_ = (uint32_t)(J) < LA ? (uint32_t)(J) : (uint32_t)(J) - LA;               \
+            lds_direct_load16((uint32_t)(J) < LA ? res_a : res_b, base_ + jj_ * gstep, slot_ + (uint32_t)(J) * 4096u); \
+        } else {                                                                                        \
+            lds_direct_load16(res_s, (ist < stages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+        }                                                                                               \
+    }
+#define ISSUE_ADVANCE()                                                                                 \
+    {                                                                                                   \
+        ++ist;                                                                                          \
+        if (ist == S2) {                                                                                \
+            ist = 0u;                                                                                   \
+            iv += G;                                                                                    \
+            ISSUE_SETUP()                                                                               \
+        }                                                                                               \
+    }
+// fragment number RR of K-step S in first-needed order: A0, B0 .. B(TN-1), A1 .. A(TM-1)
+#define READ_FRAG(SLOT, S, FA, FB, RR)                                                                  \
+    {                                                                                                   \
+        const int rr_ = (RR);                                                                           \
+        if (rr_ == 0) FA[0] = lds[(SLOT) * STAGE + fa_base + ((2u * (S) + lhalf) ^ swz)];               \
+        else if (rr_ <= TN) FB[rr_ - 1] = lds[(SLOT) * STAGE + fb_base + (rr_ - 1) * 128u + ((2u * (S) + lhalf) ^ swz)]; \
+        else if (rr_ < R) FA[rr_ - TN] = lds[(SLOT) * STAGE + fa_base + (rr_ - TN) * 128u + ((2u * (S) + lhalf) ^ swz)]; \
+    }
+#define FENCE() __builtin_amdgcn_sched_barrier(0);
+#define READ_SCALES(SLOT, ST, XA, XB)                                                                   \
+    {                                                                                                   \
+        const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(SLOT) * STAGE]);                \
+        uint32_t ra_[TM], rb_[TN];                                                                      \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_[i] = sbuf_[sa_base + i * 64u];          \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_[j] = sbuf_[sb_base + j * 64u];          \
+        uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
+        if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */             \
+            const uint32_t done_ = (ST) * 2u;                                                           \
+            const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
+            keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
+        }                                                                                               \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+    }
+
+    constexpr uint32_t KEEP2 = 2u * NL + 1u;           // loads of one even and one odd stage stay in flight
+    constexpr uint32_t WAIT2 = 0x0F70u | (KEEP2 & 15u) | ((KEEP2 >> 4) << 14);
+#pragma unroll
+    for (uint32_t s0 = 0; s0 < D; ++s0) {
+#pragma unroll
+        for (uint32_t j = 0; j < NL; ++j) ISSUE(s0, j)
+        if ((s0 & 1u) == 0u) ISSUE(s0, NL)
+        ISSUE_ADVANCE()
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT2);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int r = 0; r < R; ++r) READ_FRAG(0u, 0u, fa0, fb0, r)
+    const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
+    READ_SCALES(0u, 0u, sa, sb)
+
+// one stage: PAR = its parity, slots SL = its own, SL1 = the next stage's, SLI = the one being filled; NEXT_ST: the
+// local index of the stage after the next (odd stages read its K-quad's scales)
+#define STAGE_BODY(PAR, SL, SL1, SLI, NEXT_ST)                                                          \
+    {                                                                                                   \
+        _Pragma("unroll") for (int idx = 0; idx < 2 * NM; ++idx) {                                      \
+            const int ij_ = idx % NM, I_ = ij_ / TN, J_ = ij_ % TN;                                     \
+            if (idx < NM) acc[I_][J_] = mfma_fp4<2 * PAR>(fa0[I_], fb0[J_], acc[I_][J_], sa[I_], sb[J_]); \
+            else acc[I_][J_] = mfma_fp4<2 * PAR + 1>(fa1[I_], fb1[J_], acc[I_][J_], sa[I_], sb[J_]);    \
+            asm volatile("" : "+a"(acc[I_][J_]));                                                       \
+            FENCE()                                                                                     \
+            if (idx < RS_END) {                                                                         \
+                _Pragma("unroll") for (int q_ = 0; q_ < RPS; ++q_) READ_FRAG(SL, 1u, fa1, fb1, idx * RPS + q_) \
+                FENCE()                                                                                 \
+            }                                                                                           \
+            if (idx >= RS_END && idx < P) {                                                             \
+                _Pragma("unroll") for (int l_ = 0; l_ < (int)NL; ++l_)                                  \
+                    if (RS_END + (l_ * (P - RS_END)) / (int)NL == idx) { ISSUE(SLI, l_) FENCE() }       \
+            }                                                                                           \
+            if (idx == P - 1) {                                                                         \
+                if (PAR == 1) { ISSUE(SLI, NL) FENCE() }   /* the stage being filled is even */         \
+                ISSUE_ADVANCE()                                                                         \
+                __builtin_amdgcn_s_waitcnt(WAIT2);                                                      \
+                __builtin_amdgcn_s_barrier();                                                           \
+                FENCE()                                                                                 \
+            }                                                                                           \
+            if (idx >= P) {                                                                             \
+                _Pragma("unroll") for (int r_ = 0; r_ < R; ++r_)                                        \
+                    if (P + (r_ * (POST > 2 ? POST - 2 : 1)) / R == idx) READ_FRAG(SL1, 0u, fa0, fb0, r_) \
+                FENCE()                                                                                 \
+            }                                                                                           \
+            if (PAR == 1 && idx == 2 * NM - (POST > 2 ? 3 : 1)) { READ_SCALES(SL1, NEXT_ST, sa_n, sb_n) FENCE() } \
+        }                                                                                               \
+        if (PAR == 1) {                                                                                 \
+            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                        \
+            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                        \
+        }                                                                                               \
+    }
+
+    v16f acc[TM][TN];
+    float* wbuf = reinterpret_cast<float*>(&lds[kRing * STAGE]) + wave * (TN * 256u);
+    uint32_t g = 0u;                                       // stages done by this block (ring slot = g % kRing)
+    for (uint32_t cv = blockIdx.x; cv < total_tiles; cv += G) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (uint32_t st = 0u; st < S2; st += 2u, g += 2u) {
+            const uint32_t sl = g & 3u;                    // g is even: sl is 0 or 2
+            const uint32_t next_st = st + 2u < S2 ? st + 2u : 0u;
+            STAGE_BODY(0, sl, sl + 1u, sl ^ 3u, 0u)
+            STAGE_BODY(1, sl + 1u, sl ^ 2u, sl, next_st)
+        }
+        uint32_t m0, n0;
+        TILE_ORIGIN(cv, m0, n0)
+        const uint32_t row_base = m0 + wm0, col_base = n0 + wn0;
+        const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n && (!FUSED || mask != nullptr);
+        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
+#undef TILE_ORIGIN
+#undef ISSUE_SETUP
+#undef ISSUE
+#undef ISSUE_ADVANCE
+#undef READ_FRAG
+#undef FENCE
+#undef READ_SCALES
+#undef STAGE_BODY
 }
 
 static int stream_blocks() {
@@ -491,6 +713,20 @@ static void launch_stream_t(const uint8_t* a_codes, const uint8_t* a_scales, con
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
+static void launch_stream_tile_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                                 const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
+                                 int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
+    uint32_t gm = 4u;
+    if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
+    const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
+    hipLaunchKernelGGL((gemm_mxfp4_stream_tile_kernel<TM, TN, OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st,
+                       a_codes, a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
+                       tiles_m, tiles_n, gm, nb);
+}
+
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
 static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                              const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                              int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
@@ -502,8 +738,9 @@ static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, co
 }
 
 // Variants: 0 = 256x256 tiles streamed by one block per compute unit through a ring of 4 LDS stages, two stages
-// per trip with the scale byte picked by op_sel (large problems); 1 = 128x128 block, two LDS buffers (problems too
-// small to fill the chip with big tiles); 2 = 256x256 block, two LDS buffers.
+// per trip with the scale byte picked by op_sel (large problems); 3, 4 = the same design with 128x256 and 128x128
+// tiles (3: problems too small to fill the chip with big tiles); 1 = 128x128 block, 2 = 256x256 block, one block per
+// tile with two LDS buffers (the earlier design, kept as an independent cross-check in the tests).
 // set_gemm_plan overrides the size heuristic (tests reach every variant through it).
 // fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
 // be null = all ones), n % (32 nb) == 0.
@@ -514,11 +751,13 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     int variant = g_forced_variant;
     if (variant < 0) {
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-        // measured crossover on an MI355X: 128 big tiles (4096 x 2048 x 2048) are 8 % faster as 128 x 128 tiles,
-        // 176 (5632 x 2048 x 8192) are 1.75 x faster as 256 x 256 tiles even though they leave 80 CUs idle
-        variant = big_tiles >= 160 ? 0 : 1;
+        // measured on an MI355X: 176 big tiles (5632 x 2048 x 8192) run 1.25 x faster as 256 x 256 tiles than as 128 x 256
+        // ones although they leave 80 compute units idle; 128 big tiles (4096 x 2048 x 2048) run 1.2 x faster as 128 x 256
+        // tiles, one per compute unit (and 1.17 x faster than the two-buffer kernel with 128 x 128 tiles)
+        variant = big_tiles >= 160 ? 0 : 3;
     }
     if (fused && nb >= 4u && variant == 1) variant = 2;   // a block of 128 columns needs the 128-column wave tile
+    if (fused && nb >= 4u && variant == 4) variant = 3;
 #define QUARTET_DISPATCH(FN, ...)                                                                     \
     do {                                                                                              \
         if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); \
@@ -526,7 +765,9 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st);      \
                else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); }         \
     } while (0)
-    if (variant == 0) QUARTET_DISPATCH(launch_stream_t, );
+    if (variant == 3) QUARTET_DISPATCH(launch_stream_tile_t, 2, 4, );
+    else if (variant == 4) QUARTET_DISPATCH(launch_stream_tile_t, 2, 2, );
+    else if (variant == 0) QUARTET_DISPATCH(launch_stream_t, );
     else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
     else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
 #undef QUARTET_DISPATCH
