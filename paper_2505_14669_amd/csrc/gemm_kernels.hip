@@ -477,7 +477,8 @@ __global__ void __launch_bounds__(256)
 gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
                               const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
                               uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                              const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb) {
+                              const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb,
+                              uint64_t* __restrict__ clock_counters) {
     constexpr uint32_t BM = 64 * TM, BN = 64 * TN;
     static_assert(BM % 128 == 0 && BN % 128 == 0, "a wave's four scale tiles must belong to one operand");
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
@@ -491,8 +492,16 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
     constexpr int P = 2 * NM - POST;                     // slots in front of the barrier
     constexpr int RPS = (2 * R > NM) ? 2 : 1;            // second-K-step fragment reads per slot
     constexpr int RS_END = (R + RPS - 1) / RPS;          // first slot without such a read
+    constexpr int XR = R - (POST > 2 ? POST - 2 : 1);    // reads of the next stage's first fragments that must double up
     static_assert(RS_END <= NM && RS_END < P, "the fragments of the second K-step must be read during the first");
     __shared__ uint4 lds[kRing * STAGE + EPI];
+
+    // measurement support: shader-clock and constant-clock ticks of this block's run (wave-uniform branch)
+    uint64_t clk_t0 = 0, clk_w0 = 0;
+    if (clock_counters) {
+        clk_t0 = __builtin_readcyclecounter();
+        clk_w0 = __builtin_amdgcn_s_memrealtime();
+    }
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -574,13 +583,18 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
             ISSUE_SETUP()                                                                               \
         }                                                                                               \
     }
-// fragment number RR of K-step S in first-needed order: A0, B0 .. B(TN-1), A1 .. A(TM-1)
+// fragment number RR of K-step S: B0 .. B(TN-1), then A0 .. A(TM-1)
 #define READ_FRAG(SLOT, S, FA, FB, RR)                                                                  \
     {                                                                                                   \
         const int rr_ = (RR);                                                                           \
-        if (rr_ == 0) FA[0] = lds[(SLOT) * STAGE + fa_base + ((2u * (S) + lhalf) ^ swz)];               \
-        else if (rr_ <= TN) FB[rr_ - 1] = lds[(SLOT) * STAGE + fb_base + (rr_ - 1) * 128u + ((2u * (S) + lhalf) ^ swz)]; \
+        if (rr_ < TN) FB[rr_] = lds[(SLOT) * STAGE + fb_base + rr_ * 128u + ((2u * (S) + lhalf) ^ swz)]; \
         else if (rr_ < R) FA[rr_ - TN] = lds[(SLOT) * STAGE + fa_base + (rr_ - TN) * 128u + ((2u * (S) + lhalf) ^ swz)]; \
+    }
+// the next stage's first fragments in the order the first instructions need them: A0, B0 .. B(TN-1), A1 .. A(TM-1)
+#define READ_FRAG_NEXT(SLOT, FA, FB, RR)                                                                \
+    {                                                                                                   \
+        const int rn_ = (RR);                                                                           \
+        READ_FRAG(SLOT, 0u, FA, FB, rn_ == 0 ? TN : (rn_ <= TN ? rn_ - 1 : rn_))                        \
     }
 #define FENCE() __builtin_amdgcn_sched_barrier(0);
 #define READ_SCALES(SLOT, ST, XA, XB)                                                                   \
@@ -612,6 +626,7 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int r = 0; r < R; ++r) READ_FRAG(0u, 0u, fa0, fb0, r)
+    static_assert(XR >= 0 && XR <= R / 2 + 1, "the next stage's fragment reads must fit behind the barrier");
     const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
     READ_SCALES(0u, 0u, sa, sb)
 
@@ -640,9 +655,9 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
                 __builtin_amdgcn_s_barrier();                                                           \
                 FENCE()                                                                                 \
             }                                                                                           \
-            if (idx >= P) {                                                                             \
+            if (idx >= P) {         /* two reads per slot while more reads than slots are left, then one */ \
                 _Pragma("unroll") for (int r_ = 0; r_ < R; ++r_)                                        \
-                    if (P + (r_ * (POST > 2 ? POST - 2 : 1)) / R == idx) READ_FRAG(SL1, 0u, fa0, fb0, r_) \
+                    if (P + (r_ < 2 * XR ? r_ / 2 : r_ - XR) == idx) READ_FRAG_NEXT(SL1, fa0, fb0, r_)  \
                 FENCE()                                                                                 \
             }                                                                                           \
             if (PAR == 1 && idx == 2 * NM - (POST > 2 ? 3 : 1)) { READ_SCALES(SL1, NEXT_ST, sa_n, sb_n) FENCE() } \
@@ -677,11 +692,17 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
         else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
+    if (clock_counters && tid == 0) {
+        const uint64_t t1 = __builtin_readcyclecounter(), w1 = __builtin_amdgcn_s_memrealtime();
+        atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters), (unsigned long long)(t1 - clk_t0));
+        atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters) + 1, (unsigned long long)(w1 - clk_w0));
+    }
 #undef TILE_ORIGIN
 #undef ISSUE_SETUP
 #undef ISSUE
 #undef ISSUE_ADVANCE
 #undef READ_FRAG
+#undef READ_FRAG_NEXT
 #undef FENCE
 #undef READ_SCALES
 #undef STAGE_BODY
@@ -718,12 +739,12 @@ static void launch_stream_tile_t(const uint8_t* a_codes, const uint8_t* a_scales
                                  int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
-    uint32_t gm = 4u;
+    uint32_t gm = (BM == 256 && BN == 256 && tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
     if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
     const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
     hipLaunchKernelGGL((gemm_mxfp4_stream_tile_kernel<TM, TN, OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st,
                        a_codes, a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, gm, nb);
+                       tiles_m, tiles_n, gm, nb, g_clock_counters);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
