@@ -207,10 +207,10 @@ int quartet_mxfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales,
 
 /*
  * Test and tuning aid (no part of the method): which of the library's GEMM kernels quartet_mxfp4_gemm and
- * quartet_mxfp4_gemm_grad launch from now on.  variant -1 = choose by problem size (the default); 0, 3, 4 = one
- * block per compute unit streaming 256 x 256, 128 x 256 or 128 x 128 tiles through a ring of four LDS stages;
- * 1, 2 = one block per 128 x 128 or 256 x 256 tile with two LDS buffers.  band_height 0 = choose by shape (the
- * default), 1..64 = tile rows each XCD walks at a time in the streaming variants.  Every combination gives the same results up to fp32 summation order; the parity tests use this to
+ * quartet_mxfp4_gemm_grad launch from now on.  variant -1 = choose by problem size (the default); 0, 1, 2 = tiles
+ * of 256 x 256, 128 x 256 or 128 x 128 (all three: one block per compute unit streams its tiles through a ring of
+ * four LDS stages).  band_height 0 = choose by shape (the default), 1..64 = tile rows each XCD walks at a time.
+ * Every combination gives the same results up to fp32 summation order; the parity tests use this to
  * reach each kernel.  Process-global, not thread-safe.  QUARTET_EINVAL outside those ranges.
  */
 int quartet_debug_set_gemm_plan(int variant, int band_height);

@@ -405,7 +405,7 @@ int quartet_mxfp4_gemm(const uint8_t* a_codes, const uint8_t* a_scales,
 }
 
 int quartet_debug_set_gemm_plan(int variant, int band_height) {
-    if (variant < -1 || variant > 4 || band_height < 0 || band_height > 64) return QUARTET_EINVAL;
+    if (variant < -1 || variant > 2 || band_height < 0 || band_height > 64) return QUARTET_EINVAL;
     quartet::set_gemm_plan(variant, band_height);
     return QUARTET_OK;
 }

@@ -267,8 +267,8 @@ gemm_mxfp8_ring_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __res
 #undef F8_STAGE
 
     __builtin_amdgcn_s_barrier();
-    store_tile<TM, TN, OUT_BF16, false>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, nullptr,
-                                        alpha, m0 + wm0, n0 + wn0, m, n, lane);
+    store_tile<TM, TN, OUT_BF16>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, alpha,
+                                 m0 + wm0, n0 + wn0, m, n, lane);
 }
 
 // ------------------------------------------------------------------ host-side launchers

@@ -21,17 +21,62 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here reaches
 
-// Epilogue of both kernels.  The wave's accumulator tile goes through LDS one 32-column slice at a
-// time and comes back with 8 consecutive lanes holding the 32 columns of one row (4 each): a
-// store instruction then writes 8 whole 128-byte lines.  The slice is exactly one Hadamard
-// group, so with FUSED the gradient epilogue of Algorithm 1 Backward,
-// D = alpha * H_32_along_n(acc . M), is applied on the way: mask select, butterflies of stride 1
-// and 2 inside the lane and of stride 4, 8, 16 between the 8 lanes (the lower partner ends up with a + b,
-// the upper with a - b, bit-identical to the in-register transform: see QUARTET_BUTTERFLIES_ACROSS), the normalization,
-// then the scale.  Lane i of the 8 holds 4-column chunk i ^ (i & 4 ? 3 : 0), which makes the three
-// partners lane ^ 1, lane ^ 2 and 7 - lane: all reachable by DPP, none through LDS.
-// wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
-constexpr uint32_t kEpiStride = 40;   // floats per LDS row: 16-byte aligned, and the two half-waves of a write (4 rows apart) fall into different halves of the 64 banks (counters: one conflict cycle per write with 36)
+// Plain epilogue of a kernel whose ring is free when it ends (the MXFP8 twin): the wave's accumulator tile goes through
+// LDS one 32-column slice at a time and comes back with 8 consecutive lanes holding the 32 columns of one row (4 each):
+// a store instruction then writes 8 whole 128-byte lines.  wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
+constexpr uint32_t kEpiStride = 40;   // floats per LDS row: 16-byte aligned, and the two half-waves of a write (4 rows apart) fall into different halves of the 64 banks
+
+template <int TM, int TN, bool OUT_BF16>
+__device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd, float alpha,
+                                           uint32_t row_base, uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
+    constexpr uint32_t ITERS = TM * 4;   // 8 rows per pass
+    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
+    const uint32_t sub = lane >> 3, c = lane & 7u;
+    const bool wide = (ldd & 3u) == 0u;   // every 4-column chunk starts 16-byte (fp32) / 8-byte (bf16) aligned
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t gcol = col_base + j * 32u;
+#pragma unroll
+        for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+            for (uint32_t r = 0; r < 16; ++r)
+                wbuf[(i * 32u + (r >> 2) * 8u + lhalf * 4u + (r & 3u)) * kEpiStride + lrow] = acc[i][j][r];
+        float4 slice[ITERS];   // all reads in flight before the first use: one wave per SIMD hides no LDS latency
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it)
+            slice[it] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * kEpiStride + 4u * c]);
+#pragma unroll
+        for (uint32_t it = 0; it < ITERS; ++it) {
+            const uint32_t grow = row_base + it * 8u + sub;
+            const float v0 = slice[it].x * alpha, v1 = slice[it].y * alpha, v2 = slice[it].z * alpha, v3 = slice[it].w * alpha;
+            if (grow >= m) continue;
+            const uint32_t col = gcol + 4u * c;
+            const size_t at = (size_t)grow * ldd + col;
+            if (OUT_BF16) {
+                uint16_t* dst = static_cast<uint16_t*>(d) + at;
+                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
+                if (wide && col + 4u <= n) {
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                } else {
+                    if (col < n) dst[0] = (uint16_t)h0;
+                    if (col + 1u < n) dst[1] = (uint16_t)h1;
+                    if (col + 2u < n) dst[2] = (uint16_t)h2;
+                    if (col + 3u < n) dst[3] = (uint16_t)h3;
+                }
+            } else {
+                float* dst = static_cast<float*>(d) + at;
+                if (wide && col + 4u <= n) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
+                } else {
+                    if (col < n) dst[0] = v0;
+                    if (col + 1u < n) dst[1] = v1;
+                    if (col + 2u < n) dst[2] = v2;
+                    if (col + 3u < n) dst[3] = v3;
+                }
+            }
+        }
+    }
+}
 
 // One butterfly stage between a lane and its DPP partner for the four values of a chunk, one instruction per value: both
 // lanes form partner * t + own (t = +-1, so the fused multiply-add rounds exactly like the addition): t = +1 in the lower
@@ -61,220 +106,13 @@ constexpr uint32_t kEpiStride = 40;   // floats per LDS row: 16-byte aligned, an
 // differences of the unsigned values give (x - x = +0, and no -0 enters: masked elements and empty sums are +0).
 __device__ __forceinline__ float epilogue_norm(float v, float signed_norm) { return __builtin_fmaf(v, signed_norm, 0.0f); }
 
-// FULL: the whole wave tile lies inside D and rows are 16-byte aligned, so nothing is predicated.
-template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
-__device__ __forceinline__ void store_tile_body(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
-                                                const uint32_t* mask, float alpha, uint32_t row_base,
-                                                uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane) {
-    constexpr uint32_t ITERS = TM * 4;   // 8 rows per pass
-    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
-    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLIES_ACROSS
-    const float snorm = ((c ^ (c >> 1) ^ (c >> 2)) & 1u) ? -kInvSqrt32 : kInvSqrt32;
-    const bool wide = FULL || (ldd & 3u) == 0u;   // every 4-column chunk starts 16-byte (fp32) / 8-byte (bf16) aligned
-    const uint32_t mask_ld = n >> 5;
-#pragma unroll
-    for (uint32_t j = 0; j < TN; ++j) {
-        const uint32_t gcol = col_base + j * 32u;
-        uint32_t mw[ITERS];
-        if (FUSED) {
-#pragma unroll
-            for (uint32_t it = 0; it < ITERS; ++it) {
-                const uint32_t grow = row_base + it * 8u + sub;
-                if (FULL) mw[it] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
-                else mw[it] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
-            }
-        }
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i)
-#pragma unroll
-            for (uint32_t r = 0; r < 16; ++r)
-                wbuf[(i * 32u + (r >> 2) * 8u + lhalf * 4u + (r & 3u)) * kEpiStride + lrow] = acc[i][j][r];
-        float4 slice[ITERS];   // all reads in flight before the first use: one wave per SIMD hides no LDS latency
-#pragma unroll
-        for (uint32_t it = 0; it < ITERS; ++it)
-            slice[it] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * kEpiStride + 4u * c]);
-#pragma unroll
-        for (uint32_t it = 0; it < ITERS; ++it) {
-            const uint32_t rr = it * 8u + sub, grow = row_base + rr;
-            float v0 = slice[it].x, v1 = slice[it].y, v2 = slice[it].z, v3 = slice[it].w;
-            if (FUSED) {
-                // bit clear -> +0: and with the bit spread over the word
-                const int32_t bits = (int32_t)(mw[it] >> (4u * c));
-                v0 = __uint_as_float(__float_as_uint(v0) & (uint32_t)((bits << 31) >> 31));
-                v1 = __uint_as_float(__float_as_uint(v1) & (uint32_t)((bits << 30) >> 31));
-                v2 = __uint_as_float(__float_as_uint(v2) & (uint32_t)((bits << 29) >> 31));
-                v3 = __uint_as_float(__float_as_uint(v3) & (uint32_t)((bits << 28) >> 31));
-                const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
-                v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
-                QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, up4, up8, up16);           // strides 4, 8, 16
-                v0 = epilogue_norm(v0, snorm); v1 = epilogue_norm(v1, snorm); v2 = epilogue_norm(v2, snorm); v3 = epilogue_norm(v3, snorm);
-            }
-            v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
-            if (!FULL && grow >= m) continue;
-            const uint32_t col = gcol + 4u * c;
-            const size_t at = (size_t)grow * ldd + col;
-            if (OUT_BF16) {
-                uint16_t* dst = static_cast<uint16_t*>(d) + at;
-                const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
-                if (FULL || (wide && col + 4u <= n)) {
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                } else {
-                    if (col < n) dst[0] = (uint16_t)h0;
-                    if (col + 1u < n) dst[1] = (uint16_t)h1;
-                    if (col + 2u < n) dst[2] = (uint16_t)h2;
-                    if (col + 3u < n) dst[3] = (uint16_t)h3;
-                }
-            } else {
-                float* dst = static_cast<float*>(d) + at;
-                if (FULL || (wide && col + 4u <= n)) {
-                    *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
-                } else {
-                    if (col < n) dst[0] = v0;
-                    if (col + 1u < n) dst[1] = v1;
-                    if (col + 2u < n) dst[2] = v2;
-                    if (col + 3u < n) dst[3] = v3;
-                }
-            }
-        }
-    }
-}
-
-// The same epilogue walking the tile by blocks of 32 rows instead of slices of 32 columns: a pass takes one row
-// block of all TN accumulators through LDS (32 rows x TN*32 columns), so a lane holds the same 4-column chunk of
-// all TN slices of a row at once.  That is what Hadamard blocks of nb = 2 or 4 groups (64 or 128 columns) need: the
-// stages that combine whole groups (stride 32, 64) are then additions inside the lane, done first, before the
-// 32-point stages of each slice, and the normalization is fl(1/sqrt(32 nb)).  nb = 1 gives the same bits as
-// store_tile_body (measured equally fast; the column-slice form stays the default).
-template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
-__device__ __forceinline__ void store_tile_body_rows(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
-                                                     const uint32_t* mask, float alpha, uint32_t row_base,
-                                                     uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane,
-                                                     uint32_t nb) {
-    constexpr uint32_t STRIDE = TN * 32u + 8u;   // floats per LDS row: 16-byte aligned, rows 4 apart 32 banks apart
-    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-    const uint32_t sub = lane >> 3, c = (lane & 7u) ^ ((lane & 4u) ? 3u : 0u);
-    const float up4 = (c & 1u) ? -1.0f : 1.0f, up8 = (c & 2u) ? -1.0f : 1.0f, up16 = (c & 4u) ? -1.0f : 1.0f;   // t of QUARTET_BUTTERFLIES_ACROSS
-    const bool wide = FULL || (ldd & 3u) == 0u;
-    const uint32_t mask_ld = n >> 5;
-#pragma unroll
-    for (uint32_t i = 0; i < TM; ++i) {
-        uint32_t mw[4][TN];
-        if (FUSED) {
-#pragma unroll
-            for (uint32_t it = 0; it < 4; ++it)
-#pragma unroll
-                for (uint32_t j = 0; j < TN; ++j) {
-                    const uint32_t grow = row_base + i * 32u + it * 8u + sub, gcol = col_base + j * 32u;
-                    if (FULL) mw[it][j] = mask[(size_t)grow * mask_ld + (gcol >> 5)];
-                    else mw[it][j] = (mask && grow < m && gcol < n) ? mask[(size_t)grow * mask_ld + (gcol >> 5)] : 0xFFFFFFFFu;
-                }
-        }
-#pragma unroll
-        for (uint32_t j = 0; j < TN; ++j)
-#pragma unroll
-            for (uint32_t r = 0; r < 16; ++r)
-                wbuf[((r >> 2) * 8u + lhalf * 4u + (r & 3u)) * STRIDE + j * 32u + lrow] = acc[i][j][r];
-        float4 sl[4][TN];
-#pragma unroll
-        for (uint32_t it = 0; it < 4; ++it)
-#pragma unroll
-            for (uint32_t j = 0; j < TN; ++j)
-                sl[it][j] = *reinterpret_cast<const float4*>(&wbuf[(it * 8u + sub) * STRIDE + j * 32u + 4u * c]);
-        const float norm = ((c ^ (c >> 1) ^ (c >> 2)) & 1u) ? -block_norm(nb) : block_norm(nb);   // with the lane's sign
-#pragma unroll
-        for (uint32_t it = 0; it < 4; ++it) {
-            const uint32_t grow = row_base + i * 32u + it * 8u + sub;
-            float vv[TN][4];
-#pragma unroll
-            for (uint32_t j = 0; j < TN; ++j) {
-                vv[j][0] = sl[it][j].x; vv[j][1] = sl[it][j].y; vv[j][2] = sl[it][j].z; vv[j][3] = sl[it][j].w;
-                if (FUSED) {
-                    // bit clear -> +0: and with the bit spread over the word
-                    const int32_t bits = (int32_t)(mw[it][j] >> (4u * c));
-#pragma unroll
-                    for (uint32_t e = 0; e < 4; ++e)
-                        vv[j][e] = __uint_as_float(__float_as_uint(vv[j][e]) & (uint32_t)((bits << (31 - (int)e)) >> 31));
-                }
-            }
-            if (FUSED && nb >= 2u) {          // stride 32: slices (0,1), (2,3)
-#pragma unroll
-                for (uint32_t j = 0; j + 1u < TN; j += 2)
-#pragma unroll
-                    for (uint32_t e = 0; e < 4; ++e) {
-                        const float a = vv[j][e], b = vv[j + 1][e];
-                        vv[j][e] = a + b;
-                        vv[j + 1][e] = a - b;
-                    }
-            }
-            if (FUSED && nb >= 4u && TN >= 4) {   // stride 64: slices (0,2), (1,3)
-#pragma unroll
-                for (uint32_t j = 0; j < 2; ++j)
-#pragma unroll
-                    for (uint32_t e = 0; e < 4; ++e) {
-                        const float a = vv[j][e], b = vv[(j + 2u) % TN][e];
-                        vv[j][e] = a + b;
-                        vv[(j + 2u) % TN][e] = a - b;
-                    }
-            }
-#pragma unroll
-            for (uint32_t j = 0; j < TN; ++j) {
-                const uint32_t gcol = col_base + j * 32u;
-                float v0 = vv[j][0], v1 = vv[j][1], v2 = vv[j][2], v3 = vv[j][3];
-                if (FUSED) {
-                    const float a0 = v0 + v1, a1 = v0 - v1, a2 = v2 + v3, a3 = v2 - v3;   // stride 1
-                    v0 = a0 + a2; v2 = a0 - a2; v1 = a1 + a3; v3 = a1 - a3;                // stride 2
-                    QUARTET_BUTTERFLIES_ACROSS(v0, v1, v2, v3, up4, up8, up16);           // strides 4, 8, 16
-                    v0 = epilogue_norm(v0, norm); v1 = epilogue_norm(v1, norm); v2 = epilogue_norm(v2, norm); v3 = epilogue_norm(v3, norm);
-                }
-                v0 = v0 * alpha; v1 = v1 * alpha; v2 = v2 * alpha; v3 = v3 * alpha;
-                if (!FULL && grow >= m) continue;
-                const uint32_t col = gcol + 4u * c;
-                const size_t at = (size_t)grow * ldd + col;
-                if (OUT_BF16) {
-                    uint16_t* dst = static_cast<uint16_t*>(d) + at;
-                    const uint32_t h0 = f32_to_bf16_rne(v0), h1 = f32_to_bf16_rne(v1), h2 = f32_to_bf16_rne(v2), h3 = f32_to_bf16_rne(v3);
-                    if (FULL || (wide && col + 4u <= n)) {
-                        *reinterpret_cast<uint2*>(dst) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                    } else {
-                        if (col < n) dst[0] = (uint16_t)h0;
-                        if (col + 1u < n) dst[1] = (uint16_t)h1;
-                        if (col + 2u < n) dst[2] = (uint16_t)h2;
-                        if (col + 3u < n) dst[3] = (uint16_t)h3;
-                    }
-                } else {
-                    float* dst = static_cast<float*>(d) + at;
-                    if (FULL || (wide && col + 4u <= n)) {
-                        *reinterpret_cast<float4*>(dst) = make_float4(v0, v1, v2, v3);
-                    } else {
-                        if (col < n) dst[0] = v0;
-                        if (col + 1u < n) dst[1] = v1;
-                        if (col + 2u < n) dst[2] = v2;
-                        if (col + 3u < n) dst[3] = v3;
-                    }
-                }
-            }
-        }
-    }
-}
-
-template <int TM, int TN, bool OUT_BF16, bool FUSED>
-__device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
-                                           const uint32_t* mask, float alpha, uint32_t row_base,
-                                           uint32_t col_base, uint32_t m, uint32_t n, uint32_t lane, uint32_t nb = 1u) {
-    const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n &&
-                      (!FUSED || mask != nullptr);   // wave-uniform
-    if (FUSED && nb > 1u) {     // Hadamard blocks of 64 or 128 columns: the row-block form
-        if (full) store_tile_body_rows<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
-        else store_tile_body_rows<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
-        return;
-    }
-    if (full) store_tile_body<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
-    else store_tile_body<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane);
-}
-
-// Epilogue of the streaming kernel: the wave's 128 x 128 accumulator tile leaves in 16 passes of 8 rows x 128
-// columns through a 4 KB scratch of the wave's own (outside the ring, so the ring keeps streaming the next tile).
+// Epilogue of the streaming kernels: the wave's accumulator tile leaves in passes of 8 rows x TN*32 columns through a
+// scratch of the wave's own (outside the ring, so the ring keeps streaming the next tile); every store instruction writes
+// 8 whole 128-byte lines.  With FUSED the gradient epilogue of Algorithm 1 Backward, D = alpha * H_along_n(acc . M), is
+// applied on the way: mask select, the stages that combine whole 32-column groups and butterflies of stride 1 and 2 inside
+// the lane, strides 4, 8, 16 between the 8 lanes that hold a row's slice (QUARTET_BUTTERFLIES_ACROSS: lane i holds 4-column
+// chunk i ^ (i & 4 ? 3 : 0), which makes the partners lane ^ 1, lane ^ 2 and 7 - lane, all reachable by DPP), the
+// normalization, then the scale: the same fp32 operations in the same order as the stand-alone epilogue kernel.
 // Row 4*lhalf + e of a pass comes from register 4*qd + e of the four accumulators of tile row i; a lane reads
 // back chunk c (4 columns) of all four 32-column slices of row `sub`, so Hadamard blocks of 32, 64 and 128 columns
 // are handled alike (group-combining stages inside the lane, then the 32-point stages of each slice).

@@ -13,8 +13,8 @@
 // so a wave's scale fragment is one coalesced 256-byte global load and the paper's separate
 // scale-rearrangement step does not exist here.
 //
-// Two kernel shapes: gemm_mxfp4_kernel (one block per tile, two LDS buffers; small problems) and
-// gemm_mxfp4_stream_kernel (one block per compute unit streaming its tiles through a ring of LDS stages).
+// Kernels: gemm_mxfp4_stream_kernel (256 x 256 tiles) and gemm_mxfp4_stream_tile_kernel (128 x 256 and 128 x 128 tiles
+// for small problems): one block per compute unit streams its tiles through a ring of LDS stages.
 #include "gemm_common.h"
 #include "launchers.h"
 
@@ -39,195 +39,6 @@ __device__ __forceinline__ v16f mfma_fp4(const uint4& a, const uint4& b, v16f c,
     v8i va = {(int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0};
     v8i vb = {(int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0};
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, vb, c, 4, 4, S, (int)sa, S, (int)sb);
-}
-
-// Block = 4 waves (2 x 2), wave tile (TM*32) x (TN*32), block tile BM x BN = (2*TM*32) x (2*TN*32).
-// Per stage (256 K-elements) a block moves BM + BN rows of 128 code bytes straight from global
-// memory into LDS (buffer_load ... lds, 16 bytes per lane, lane l landing at base + 16 l), into the
-// buffer the matrix cores are not reading; the 16-byte chunk a lane fetches is chosen so that the
-// linear LDS image is the XOR-swizzled tile (chunk c of row r sits at r*8 + (c ^ (r/2)%8)), which
-// makes the 16-byte fragment reads bank-conflict free.  One wave runs per SIMD, so the instruction
-// stream is software-pipelined by hand: fragments of K-step s+1 are read, and a quarter of the next
-// stage's loads is issued, between the matrix-core instructions of K-step s.
-template <int TM, int TN, bool OUT_BF16, bool FUSED>
-__global__ void __launch_bounds__(256)
-gemm_mxfp4_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
-                  const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
-                  uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                  const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t nb) {
-    constexpr uint32_t BM = 2 * TM * 32, BN = 2 * TN * 32;
-    constexpr uint32_t LA = BM / 32, LB = BN / 32;      // 1 KB (64 lanes x 16 B) loads per wave per stage
-    constexpr uint32_t STAGE = (BM + BN) * 8;           // 16-byte chunks per LDS buffer
-    __shared__ uint4 lds[2 * STAGE];
-    static_assert(2 * STAGE * 16 >= 4 * TM * 32 * kEpiStride * 4 && 2 * STAGE * 16 >= 4 * 32 * (TN * 32 + 8) * 4,
-                  "the epilogue's per-wave scratch (either form) must fit in the stage buffers");
-
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lives in an SGPR
-    const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-
-    // XCD-aware tile order: consecutive block ids land on different XCDs (8, round-robin), so give
-    // each XCD one contiguous range of tiles, and walk tiles in bands of 8 tile-rows so that the
-    // blocks running together on an XCD share A and B panels in its L2.
-    uint32_t tile;
-    {
-        const uint32_t nb = gridDim.x, xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
-        const uint32_t per = nb >> 3, rem = nb & 7u;
-        tile = xcd * per + (xcd < rem ? xcd : rem) + q;
-    }
-    constexpr uint32_t GM = 8;
-    const uint32_t band = tile / (GM * tiles_n);
-    const uint32_t band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
-    const uint32_t in_band = tile - band * GM * tiles_n;
-    const uint32_t m0 = (band * GM + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
-    const uint32_t wm0 = (wave >> 1) * (TM * 32), wn0 = (wave & 1u) * (TN * 32);
-
-    const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;   // code bytes, groups, K-quads per row
-    const uint32_t rows_a = (m - m0) < BM ? (m - m0) : BM, rows_b = (n - n0) < BN ? (n - n0) : BN;
-
-    const __amdgpu_buffer_rsrc_t res_a = make_rsrc(a_codes + (size_t)m0 * kb, rows_a * kb);
-    const __amdgpu_buffer_rsrc_t res_b = make_rsrc(b_codes + (size_t)n0 * kb, rows_b * kb);
-    // scale tiles: [row block][K-quad][lane][4 bytes]
-    const __amdgpu_buffer_rsrc_t res_sa = make_rsrc(a_scales + (size_t)(m0 >> 5) * kq * 256u, ((rows_a + 31u) >> 5) * kq * 256u);
-    const __amdgpu_buffer_rsrc_t res_sb = make_rsrc(b_scales + (size_t)(n0 >> 5) * kq * 256u, ((rows_b + 31u) >> 5) * kq * 256u);
-
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    // global -> LDS: load j of this wave fills LDS chunks [j*256 + wave*64, +64) of the operand's
-    // region, i.e. rows j*32 + wave*8 + lane/8; the lane fetches logical chunk (lane%8) ^ ((row/2)%8).
-    const uint32_t drow = wave * 8u + (lane >> 3);
-    const uint32_t dcol = (lane & 7u) ^ ((drow >> 1) & 7u);
-    const uint32_t goff = drow * kb + dcol * 16u;       // + j * 32 * kb, + stage * 128
-    const uint32_t gstep = 32u * kb;
-    const uint32_t soff_a = ((wm0 >> 5) * kq * 64u + lane) * 4u;   // + i * kq*256 per 32-row block, + st*256
-    const uint32_t soff_b = ((wn0 >> 5) * kq * 64u + lane) * 4u;
-    const uint32_t sstep = kq * 256u;
-    // fragment reads: chunk (2S + lhalf) ^ ((row/2) % 8) of row w?0 + i*32 + lrow
-    const uint32_t swz = lhalf ^ ((lrow >> 1) & 7u);
-    const uint32_t fa_base = (wm0 + lrow) * 8u, fb_base = BM * 8u + (wn0 + lrow) * 8u;
-
-    const uint32_t stages = kq;
-    uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
-    uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-
-// Quarter P (0..3) of the loads of stage ST into LDS buffer BUF and scale registers XA, XB.  A stage
-// past the end of K is out of range of the resources and arrives as zeros, so no branch is needed.
-#define QUARTET_ISSUE_PART(P, ST, BUF, XA, XB)                                                          \
-    {                                                                                                   \
-        const uint32_t st_ = (ST);                                                                      \
-        const uint32_t base_ = (st_ * 128u + dcol * 16u < kb) ? goff + st_ * 128u : kOutOfRange;        \
-        _Pragma("unroll") for (uint32_t j = (P) * LA / 4; j < ((P) + 1) * LA / 4; ++j)                  \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_a, (lds_ptr_t)&lds[(BUF) * STAGE + j * 256u + wave * 64u], 16, \
-                                                     base_ + j * gstep, 0, 0, 0);                       \
-        _Pragma("unroll") for (uint32_t j = (P) * LB / 4; j < ((P) + 1) * LB / 4; ++j)                  \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_b, (lds_ptr_t)&lds[(BUF) * STAGE + BM * 8u + j * 256u + wave * 64u], 16, \
-                                                     base_ + j * gstep, 0, 0, 0);                       \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                             \
-            if (i * 4 / TM == (P) && (i * 4) % TM == 0)                                                 \
-                XA[i] = __builtin_amdgcn_raw_buffer_load_b32(res_sa, soff_a + i * sstep + st_ * 256u, 0, 0); \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
-            if (j * 4 / TN == (P) && (j * 4) % TN == 0)                                                 \
-                XB[j] = __builtin_amdgcn_raw_buffer_load_b32(res_sb, soff_b + j * sstep + st_ * 256u, 0, 0); \
-    }
-// ragged K: groups past k/32 hold zero codes; neutralize whatever their scale bytes hold
-#define QUARTET_FIX_SCALES(ST, XA, XB)                                                                  \
-    if ((ST) + 1u >= stages && (gk & 7u) != 0u) {                                                       \
-        uint32_t keep = 0u;                                                                             \
-        _Pragma("unroll") for (uint32_t p = 0; p < 4; ++p)                                              \
-            if ((ST) * 8u + 2u * p + lhalf < gk) keep |= 0xFFu << (8u * p);                             \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (XA[i] & keep) | (0x7F7F7F7Fu & ~keep); \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (XB[j] & keep) | (0x7F7F7F7Fu & ~keep); \
-    }
-#define QUARTET_READ_FRAGS(BUF, S, FA, FB)                                                              \
-    {                                                                                                   \
-        const uint4* sbuf_ = &lds[(BUF) * STAGE];                                                       \
-        const uint32_t c_ = (2u * (S)) ^ swz;                                                           \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) FA[i] = sbuf_[fa_base + i * 256u + c_];     \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) FB[j] = sbuf_[fb_base + j * 256u + c_];     \
-    }
-#define QUARTET_MFMAS(S, FA, FB)                                                                        \
-    _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                                 \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                             \
-            acc[i][j] = mfma_fp4<S>(FA[i], FB[j], acc[i][j], sa[i], sb[j]);
-// Zero-instruction pin: the accumulators must hold the results of every matrix-core instruction
-// issued so far, which keeps the compiler from sinking that work below the wait and the barrier.
-#define QUARTET_PIN_ACC()                                                                               \
-    _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i)                                                 \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
-// Issue order inside a K-step: one LDS fragment read (if READS), one global load (the first NV
-// groups), then the group's share of the matrix-core instructions.
-#define QUARTET_PIPE(READS, NV)                                                                         \
-    _Pragma("unroll") for (uint32_t g_ = 0; g_ < TM + TN; ++g_) {                                       \
-        if (READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
-        if (g_ < (NV)) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                               \
-        __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);                          \
-    }
-    constexpr uint32_t NV = LA / 4 + LB / 4 + 2;   // loads per quarter (TM = TN = 2: scale loads only in quarters 0, 2)
-
-    if (stages > 0) {
-        QUARTET_ISSUE_PART(0, 0u, 0u, sa, sb)
-        QUARTET_ISSUE_PART(1, 0u, 0u, sa, sb)
-        QUARTET_ISSUE_PART(2, 0u, 0u, sa, sb)
-        QUARTET_ISSUE_PART(3, 0u, 0u, sa, sb)
-        QUARTET_FIX_SCALES(0u, sa, sb)
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-direct loads have landed
-        __syncthreads();
-        QUARTET_READ_FRAGS(0u, 0u, fa0, fb0)
-    }
-
-    for (uint32_t st = 0; st < stages; ++st) {
-        const uint32_t buf = st & 1u;
-        __builtin_amdgcn_sched_barrier(0);
-        QUARTET_ISSUE_PART(0, st + 1u, buf ^ 1u, sa_n, sb_n)
-        QUARTET_READ_FRAGS(buf, 1u, fa1, fb1)
-        QUARTET_MFMAS(0, fa0, fb0)
-        QUARTET_PIPE(true, NV)
-        QUARTET_PIN_ACC()
-        __builtin_amdgcn_sched_barrier(0);
-        QUARTET_ISSUE_PART(1, st + 1u, buf ^ 1u, sa_n, sb_n)
-        QUARTET_READ_FRAGS(buf, 2u, fa0, fb0)
-        QUARTET_MFMAS(1, fa1, fb1)
-        QUARTET_PIPE(true, NV)
-        QUARTET_PIN_ACC()
-        __builtin_amdgcn_sched_barrier(0);
-        QUARTET_ISSUE_PART(2, st + 1u, buf ^ 1u, sa_n, sb_n)
-        QUARTET_READ_FRAGS(buf, 3u, fa1, fb1)
-        QUARTET_MFMAS(2, fa0, fb0)
-        QUARTET_PIPE(true, NV)
-        QUARTET_PIN_ACC()
-        __builtin_amdgcn_sched_barrier(0);
-        QUARTET_ISSUE_PART(3, st + 1u, buf ^ 1u, sa_n, sb_n)
-        QUARTET_MFMAS(3, fa1, fb1)
-        QUARTET_PIPE(false, NV)
-        QUARTET_PIN_ACC()
-        __builtin_amdgcn_sched_barrier(0);    // the matrix-core work stays ahead of the wait
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // next stage's codes are in LDS, its scales in registers
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        QUARTET_READ_FRAGS(buf ^ 1u, 0u, fa0, fb0)
-        QUARTET_FIX_SCALES(st + 1u, sa_n, sb_n)
-#pragma unroll
-        for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];
-#pragma unroll
-        for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];
-    }
-#undef QUARTET_ISSUE_PART
-#undef QUARTET_FIX_SCALES
-#undef QUARTET_READ_FRAGS
-#undef QUARTET_MFMAS
-#undef QUARTET_PIPE
-#undef QUARTET_PIN_ACC
-
-    // every wave is done reading the stage buffers: reuse them as the epilogue's scratch
-    __syncthreads();
-    store_tile<TM, TN, OUT_BF16, FUSED>(acc, reinterpret_cast<float*>(lds) + wave * (TM * 32u * kEpiStride), d, ldd, mask,
-                                        alpha, m0 + wm0, n0 + wn0, m, n, lane, nb);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -747,22 +558,10 @@ static void launch_stream_tile_t(const uint8_t* a_codes, const uint8_t* a_scales
                        tiles_m, tiles_n, gm, nb, g_clock_counters);
 }
 
-template <int TM, int TN, bool OUT_BF16, bool FUSED>
-static void launch_variant_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                             const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                             int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
-    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
-    uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
-    hipLaunchKernelGGL((gemm_mxfp4_kernel<TM, TN, OUT_BF16, FUSED>), dim3(tiles_m * tiles_n), dim3(256), 0, st, a_codes,
-                       a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, nb);
-}
-
-// Variants: 0 = 256x256 tiles streamed by one block per compute unit through a ring of 4 LDS stages, two stages
-// per trip with the scale byte picked by op_sel (large problems); 3, 4 = the same design with 128x256 and 128x128
-// tiles (3: problems too small to fill the chip with big tiles); 1 = 128x128 block, 2 = 256x256 block, one block per
-// tile with two LDS buffers (the earlier design, kept as an independent cross-check in the tests).
-// set_gemm_plan overrides the size heuristic (tests reach every variant through it).
+// Variants: 0 = 256x256 tiles (hand-scheduled stage), 1 = 128x256 tiles, 2 = 128x128 tiles (stage generated from the
+// tile shape); all three: one block per compute unit streams its tiles through a ring of 4 LDS stages, two stages per
+// trip with the scale byte picked by op_sel.  set_gemm_plan overrides the size heuristic (tests reach every variant
+// through it).
 // fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
 // be null = all ones), n % (32 nb) == 0.
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
@@ -774,11 +573,10 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
         // measured on an MI355X: 176 big tiles (5632 x 2048 x 8192) run 1.25 x faster as 256 x 256 tiles than as 128 x 256
         // ones although they leave 80 compute units idle; 128 big tiles (4096 x 2048 x 2048) run 1.2 x faster as 128 x 256
-        // tiles, one per compute unit (and 1.17 x faster than the two-buffer kernel with 128 x 128 tiles)
-        variant = big_tiles >= 160 ? 0 : 3;
+        // tiles, one per compute unit
+        variant = big_tiles >= 160 ? 0 : 1;
     }
-    if (fused && nb >= 4u && variant == 1) variant = 2;   // a block of 128 columns needs the 128-column wave tile
-    if (fused && nb >= 4u && variant == 4) variant = 3;
+    if (fused && nb >= 4u && variant == 2) variant = 1;   // a block of 128 columns needs the 128-column wave tile
 #define QUARTET_DISPATCH(FN, ...)                                                                     \
     do {                                                                                              \
         if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); \
@@ -786,11 +584,9 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         else { if (fused) FN<__VA_ARGS__ false, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st);      \
                else FN<__VA_ARGS__ false, false>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); }         \
     } while (0)
-    if (variant == 3) QUARTET_DISPATCH(launch_stream_tile_t, 2, 4, );
-    else if (variant == 4) QUARTET_DISPATCH(launch_stream_tile_t, 2, 2, );
-    else if (variant == 0) QUARTET_DISPATCH(launch_stream_t, );
-    else if (variant == 2) QUARTET_DISPATCH(launch_variant_t, 4, 4, );
-    else QUARTET_DISPATCH(launch_variant_t, 2, 2, );
+    if (variant == 1) QUARTET_DISPATCH(launch_stream_tile_t, 2, 4, );
+    else if (variant == 2) QUARTET_DISPATCH(launch_stream_tile_t, 2, 2, );
+    else QUARTET_DISPATCH(launch_stream_t, );
 #undef QUARTET_DISPATCH
     return hipGetLastError();
 }

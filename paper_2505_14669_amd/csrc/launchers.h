@@ -34,7 +34,7 @@ hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t r
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                        int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st);
-// variant: -1 = size heuristic, 0..2 = force that GEMM kernel; band_height: 0 = heuristic, > 0 = tile rows per band
+// variant: -1 = size heuristic, 0..2 = force that tile shape (256x256, 128x256, 128x128); band_height: 0 = heuristic, > 0 = tile rows per band
 void set_gemm_plan(int variant, int band_height);
 hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, uint32_t nb, float scale,
                                 void* out, int out_bf16, hipStream_t st);

@@ -150,7 +150,7 @@ def test_static_scratch_backward_rejects_layers_beyond_its_array_on_the_host():
     assert q.quartet_linear_bwd_static(*args(2 ** 40, 2 ** 30, 2 ** 30)) == q.QUARTET_ENOTSUP
     assert q.quartet_linear_bwd_static(*args(48, 32, 32)) == q.QUARTET_EINVAL
     assert q.quartet_linear_bwd_static(None, 32, 32, 32, P, P, P, P, P, P, 0, 0, P, P, 0, 0) == q.QUARTET_EINVAL
-    assert q.quartet_debug_set_gemm_plan(5, 0) == q.QUARTET_EINVAL and q.quartet_debug_set_gemm_plan(-1, 0) == q.QUARTET_OK
+    assert q.quartet_debug_set_gemm_plan(3, 0) == q.QUARTET_EINVAL and q.quartet_debug_set_gemm_plan(-1, 0) == q.QUARTET_OK
 
 
 def test_profile_record_can_be_set_up_and_dropped_without_a_gpu():

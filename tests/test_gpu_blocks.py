@@ -106,10 +106,10 @@ def test_grad_epilogue_block(G, block):
         assert np.array_equal(got_nm.view(np.uint32), oracle.grad_epilogue_block(g, None, block, 1.0).view(np.uint32))
 
 
-@pytest.fixture(params=["auto", "0", "1", "2", "3", "4"])
+@pytest.fixture(params=["auto", "0", "1", "2"])
 def gemm_variant(request, G):
-    # every tile shape of the GEMM kernel; a block of 128 columns does not fit the 64-column wave tile of variant 1,
-    # the library switches to variant 2 by itself
+    # every tile shape of the GEMM kernel; a block of 128 columns does not fit the 64-column wave tile of variant 2,
+    # the library switches to variant 1 by itself
     G.q.check(G.q.quartet_debug_set_gemm_plan(-1 if request.param == "auto" else int(request.param), 0))
     yield request.param
     G.q.check(G.q.quartet_debug_set_gemm_plan(-1, 0))

@@ -176,7 +176,7 @@ def test_gemm_exhaustive_code_pairs_bit_exact(G):
     assert np.array_equal(got.astype(np.float64), oracle.mxfp4_gemm(ac, one_a, bc, one_b))
 
 
-@pytest.fixture(params=["auto", "0", "1", "2", "3", "4"])
+@pytest.fixture(params=["auto", "0", "1", "2"])
 def gemm_variant(request, G):
     # every tile shape of the GEMM kernel is checked, not only the one the size heuristic picks
     G.q.check(G.q.quartet_debug_set_gemm_plan(-1 if request.param == "auto" else int(request.param), 0))
