@@ -24,7 +24,7 @@ constexpr uint32_t kOutOfRange = 0x80000000u;   // byte offset no resource here 
 // Plain epilogue of a kernel whose ring is free when it ends (the MXFP8 twin): the wave's accumulator tile goes through
 // LDS one 32-column slice at a time and comes back with 8 consecutive lanes holding the 32 columns of one row (4 each):
 // a store instruction then writes 8 whole 128-byte lines.  wbuf: this wave's LDS scratch of TM*32 rows x kEpiStride floats.
-constexpr uint32_t kEpiStride = 40;   // floats per LDS row: 16-byte aligned, and the two half-waves of a write (4 rows apart) fall into different halves of the 64 banks
+constexpr uint32_t kEpiStride = 32;   // floats per LDS row, no padding: the LDS has 64 banks and serves a 16-byte read 16 lanes (two rows here) at a time, so neighbouring rows must sit 32 banks apart (counters: every read took twice its cycles with rows of 36 or 40 floats)
 
 template <int TM, int TN, bool OUT_BF16>
 __device__ __forceinline__ void store_tile(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd, float alpha,
@@ -116,8 +116,9 @@ __device__ __forceinline__ float epilogue_norm(float v, float signed_norm) { ret
 // Row 4*lhalf + e of a pass comes from register 4*qd + e of the four accumulators of tile row i; a lane reads
 // back chunk c (4 columns) of all four 32-column slices of row `sub`, so Hadamard blocks of 32, 64 and 128 columns
 // are handled alike (group-combining stages inside the lane, then the 32-point stages of each slice).
-// LDS image: row r at r*128 floats, slice j of rows 4..7 stored at slice position j^1 (the two half-waves of a
-// write then hit different bank halves).
+// LDS image: row r at r * TN*32 floats with its slices j stored at position j ^ f(r), f(r) = (r ^ r/4) & 1: the LDS has
+// 64 banks and serves a 16-byte read 16 lanes at a time -- rows 2a and 2a+1 here, which f puts into different bank halves
+// (counters: without it every read took twice its cycles); rows r and r+4, the two half-waves of a write, differ too.
 template <int TM, int TN, bool OUT_BF16, bool FUSED, bool FULL>
 __device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][TN], float* wbuf, void* d, uint32_t ldd,
                                                  const uint32_t* mask, float alpha, uint32_t row_base,
@@ -130,9 +131,9 @@ __device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][TN], float* wbu
     const float norm = ((c ^ (c >> 1) ^ (c >> 2)) & 1u) ? -block_norm(nb) : block_norm(nb);
     const bool wide = FULL || (ldd & 3u) == 0u;
     const uint32_t mask_ld = n >> 5;
-    float* wr = wbuf + lhalf * 4u * W + lrow;          // + e*W + ((j ^ lhalf) * 32)
-    const float* rd = wbuf + sub * W + 4u * c;         // + ((j ^ (sub >> 2)) * 32)
-    const uint32_t rswz = sub >> 2;
+    float* wr = wbuf + lhalf * 4u * W + lrow;          // + e*W + ((j ^ f(4 lhalf + e)) * 32)
+    const float* rd = wbuf + sub * W + 4u * c;         // + ((j ^ f(sub)) * 32)
+    const uint32_t rswz = (sub ^ (sub >> 2)) & 1u;
     uint32_t mw[PASSES][TN];
     if (FUSED) {
         const bool mvec = FULL && TN == 4 && (mask_ld & 3u) == 0u && (reinterpret_cast<uintptr_t>(mask) & 15u) == 0u;   // wave-uniform
@@ -155,7 +156,7 @@ __device__ __forceinline__ void store_tile_rows8(v16f (&acc)[TM][TN], float* wbu
 #define ROWS8_WRITE(P)                                                                                  \
     _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j)                                                 \
         _Pragma("unroll") for (uint32_t e = 0; e < 4; ++e)                                              \
-            wr[e * W + ((j ^ lhalf) * 32u)] = acc[(P) >> 2][j][((P) & 3u) * 4u + e];
+            wr[e * W + ((j ^ ((e & 1u) ^ lhalf)) * 32u)] = acc[(P) >> 2][j][((P) & 3u) * 4u + e];
     ROWS8_WRITE(0u)
 #pragma unroll
     for (uint32_t p = 0; p < PASSES; ++p) {
