@@ -28,13 +28,13 @@ grad_epilogue_kernel(const uint4* g, const uint32_t* __restrict__ mask, uint32_t
         uint32_t c = 64u * j + lane;                       // 16-byte chunk in the wave's 8 KB
         uint32_t grp = base_group + (c >> 3);
         uint4 q = (grp < n_groups) ? load_stream16(&g[(size_t)base_group * 8u + c]) : zero;
-        stage[wave][(c & ~7u) | ((c & 7u) ^ ((c >> 3) & 7u))] = q;
+        stage[wave][(c & ~7u) | ((c & 7u) ^ ((c >> 4) & 7u))] = q;
     }
     __syncthreads();
     float v[32];
 #pragma unroll
     for (uint32_t j = 0; j < 8; ++j) {
-        uint4 q = stage[wave][8u * lane + (j ^ (lane & 7u))];
+        uint4 q = stage[wave][8u * lane + (j ^ ((lane >> 1) & 7u))];
         v[4 * j] = u2f(q.x); v[4 * j + 1] = u2f(q.y); v[4 * j + 2] = u2f(q.z); v[4 * j + 3] = u2f(q.w);
     }
     const uint32_t grp = base_group + lane;

@@ -49,13 +49,13 @@ mxfp8_quant_kernel(const uint16_t* __restrict__ x, uint32_t rows, uint32_t gk, i
         uint32_t c = 64u * j + lane;
         const uint32_t voff = ((wave * 2u + (c >> 7)) * (uint32_t)ldx + kq0 * 256u + (c & 127u) * 8u) * 2u;
         v4u_t q = __builtin_amdgcn_raw_buffer_load_b128(res_x, (int)voff, 0, 2 /* non-temporal */);
-        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = make_uint4(q.x, q.y, q.z, q.w);
+        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 4) & 3u))] = make_uint4(q.x, q.y, q.z, q.w);
     }
     __syncthreads();
     float v[32];
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
-        const uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 1) & 3u))];
+        const uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 2) & 3u))];
         v[8 * j] = u2f(q.x << 16); v[8 * j + 1] = u2f(q.x & 0xFFFF0000u);
         v[8 * j + 2] = u2f(q.y << 16); v[8 * j + 3] = u2f(q.y & 0xFFFF0000u);
         v[8 * j + 4] = u2f(q.z << 16); v[8 * j + 5] = u2f(q.z & 0xFFFF0000u);

@@ -160,13 +160,13 @@ __device__ __forceinline__ void quant_row_tile(const uint16_t* __restrict__ x, u
         uint32_t c = 64u * j + lane;                       // 16-byte chunk inside the wave's 2 rows x 2 KB
         const uint32_t voff = ((wave * 2u + (c >> 7)) * (uint32_t)ldx + kq0 * 256u + (c & 127u) * 8u) * 2u;
         v4u_t q = __builtin_amdgcn_raw_buffer_load_b128(res_x, (int)voff, 0, 2 /* non-temporal */);
-        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 3) & 3u))] = make_uint4(q.x, q.y, q.z, q.w);
+        stage[wave][(c & ~3u) | ((c & 3u) ^ ((c >> 4) & 3u))] = make_uint4(q.x, q.y, q.z, q.w);
     }
     __syncthreads();
     float v[32];
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
-        uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 1) & 3u))];
+        uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 2) & 3u))];
         unpack_bf16x8(q, &v[8 * j]);
     }
     const uint32_t row_local = wave * 2u + (lane >> 5), gi = lane & 31u;
@@ -235,7 +235,8 @@ quant_row_pair_kernel(RowMatrix a, RowMatrix b, uint32_t split, uint32_t gk, SrP
 }
 
 // Store phase of the transposed kernels: the tile's codes, scale bytes and mask words gathered in LDS
-// ([local column][group], codes with a 16-byte slot swizzle) leave as full 128-byte lines of codes,
+// ([local column][group], codes with a 16-byte slot swizzle; columns 16..31 of every 32 swap places in pairs, which
+// puts the 16 lanes of a 16-byte LDS access on the 64 banks' 16 different slots) leave as full 128-byte lines of codes,
 // 32-byte runs of mask words and whole dwords of the scale tiles.
 template <bool MASK>
 __device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, const uint8_t* s_scales, const uint32_t* s_mask,
@@ -249,7 +250,7 @@ __device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, cons
         uint32_t lc = id >> 3, part = id & 7u;
         uint32_t r = col0 + lc, grp = grp0 + part;
         if (r < rows && grp < gk) {
-            uint4 q = s_codes[lc * 8u + (part ^ ((lc >> 1) & 7u))];
+            uint4 q = s_codes[(lc ^ ((lc >> 4) & 1u)) * 8u + (part ^ ((lc >> 1) & 7u))];
             store_stream16(codes + (size_t)r * (k >> 1) + (size_t)grp * 16u, q);
         }
     }
@@ -336,7 +337,7 @@ __device__ __forceinline__ void quant_transposed_tile(const uint16_t* __restrict
             // output position of element 0 of the group: row*k + grp*32, divided by 16
             quantize_group<MODE>(v, p, ((uint64_t)(col + c) * k + grp * 32u) >> 4, q, sb, m);
             const uint32_t lc = 2u * lane + c;            // local column
-            s_codes[lc * 8u + (gl ^ sw)] = q;
+            s_codes[(lc ^ ((lc >> 4) & 1u)) * 8u + (gl ^ sw)] = q;
             s_scales[lc * 8u + gl] = (uint8_t)sb;
             if (MASK) s_mask[lc * 8u + gl] = m;
         }
@@ -430,7 +431,7 @@ quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, u
         uint32_t sbyte, m;
         encode_group<MODE>(v, p, ((uint64_t)(col + c) * k + (grp0 + gl) * 32u) >> 4, q, sbyte, m);
         const uint32_t lc = 2u * lane + c;
-        s_codes[lc * 8u + (gl ^ sw)] = q;
+        s_codes[(lc ^ ((lc >> 4) & 1u)) * 8u + (gl ^ sw)] = q;
         s_scales[lc * 8u + gl] = (uint8_t)sbyte;
         if (MASK) s_mask[lc * 8u + gl] = m;
     }
@@ -483,9 +484,9 @@ __device__ __forceinline__ void requant_transposed_wave(const uint8_t* __restric
     const uint32_t code_off = rl * half + ((wave * 64u + 32u * ch) >> 1);
     const uint32_t scale_off = (((cg & 1u) << 5) + rl) * 4u + (cg >> 1);
     const uint32_t code_step = 32u * half, scale_step = skq * 256u;   // wave-uniform: they ride in the scalar offset
-    const uint32_t wr = (rl + 8u * ch) & 31u;                   // rotated row slot: the two chunks land on different banks
+    const uint32_t wr = (rl + 16u * ch) & 31u;                  // rotated row slot: the 32 lanes of a write pass (16 source rows x 2 chunks) land on 32 different banks
     // quantize role: output row c0 + lane
-    const uint32_t out_row = c0 + lane, rot = (8u * (lane >> 5)) & 31u;
+    const uint32_t out_row = c0 + lane, rot = (16u * (lane >> 5)) & 31u;
 
     v4u_t cw = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, 0, 0);
     uint32_t sb_src = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, 0, 0);
@@ -673,8 +674,8 @@ requant_transposed_block_kernel(const uint8_t* __restrict__ src_codes, const uin
     const uint32_t code_off = rl * half + ((wave * 64u + 32u * ch) >> 1);
     const uint32_t scale_off = (((cg & 1u) << 5) + rl) * 4u + (cg >> 1);
     const uint32_t code_step = 32u * half, scale_step = skq * 256u;
-    const uint32_t wr = (rl + 8u * ch) & 31u;
-    const uint32_t out_row = c0 + lane, rot = (8u * (lane >> 5)) & 31u;
+    const uint32_t wr = (rl + 16u * ch) & 31u;
+    const uint32_t out_row = c0 + lane, rot = (16u * (lane >> 5)) & 31u;
     const float norm = block_norm((uint32_t)NB);
     uint32_t sw0 = 0u, sw1 = 0u;
     uint8_t* crow = codes + (size_t)out_row * (k >> 1) + (size_t)grp0 * 16u;
