@@ -183,7 +183,9 @@ QUARTET_SR_CVT(3, "[0,0,1,1]")
 __device__ __forceinline__ uint32_t rotr32(uint32_t x, uint32_t n) { return __builtin_amdgcn_alignbit(x, x, n); }
 
 __device__ __forceinline__ uint32_t sr_pack8(const float* v, uint32_t w0, uint32_t w1) {
-    uint32_t even = 0u, odd = 0u;
+    uint32_t even, odd;      // every byte of both is written by a conversion below: no initial value needed
+    asm volatile("" : "=v"(even));
+    asm volatile("" : "=v"(odd));
     v2f p0 = {v[0], v[1]}, p1 = {v[2], v[3]}, p2 = {v[4], v[5]}, p3 = {v[6], v[7]};
     sr_cvt_pair<0>(even, p0, rotr32(w0, 8u));     // element 0: byte 0 leads
     sr_cvt_pair<1>(even, p1, rotr32(w0, 24u));    // element 2

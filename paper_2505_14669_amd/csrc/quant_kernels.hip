@@ -39,11 +39,12 @@ __device__ __forceinline__ void flip_signs(float (&v)[32], uint32_t sign_word) {
     for (int i = 0; i < 32; ++i) v[i] = u2f(f2u(v[i]) ^ (((sign_word >> i) & 1u) << 31));
 }
 
-// Quantize one group held in v[] (not yet rotated), Hadamard block = the group.
-template <int MODE>
+// Quantize one group held in v[] (not yet rotated), Hadamard block = the group.  FLIPPED: the caller has applied the
+// sign vector of the randomized rotation already (where it is cheaper: while unpacking, or on the codes before decoding).
+template <int MODE, bool FLIPPED = false>
 __device__ __forceinline__ void quantize_group(float (&v)[32], const SrParams& p, uint64_t q_base,
                                                uint4& codes, uint32_t& scale_byte, uint32_t& mask_word) {
-    if (MODE != kFwd) flip_signs(v, p.sign_word);
+    if (MODE != kFwd && !FLIPPED) flip_signs(v, p.sign_word);
     fwht32(v);
     encode_group<MODE>(v, p, q_base, codes, scale_byte, mask_word);
 }
@@ -123,6 +124,21 @@ __device__ __forceinline__ void encode_group(float (&v)[32], const SrParams& p, 
     codes = make_uint4(c[0], c[1], c[2], c[3]);
 }
 
+// Sign bit of element i of the randomized rotation's sign vector as a float's sign bit (wave-uniform: scalar arithmetic).
+__device__ __forceinline__ uint32_t sign_bit(uint32_t sign_word, uint32_t i) { return ((sign_word >> i) & 1u) << 31; }
+
+// Eight bf16 values (elements first .. first+7 of a group) to fp32 with the sign vector applied on the way.  An even
+// element is x << 16 plus its sign bit: adding 0x80000000 flips the top bit, and shift-and-add is one instruction where
+// shift and XOR are two; an odd element is one three-input bit operation either way.
+__device__ __forceinline__ void unpack_bf16x8_signed(const uint4& q, float* v, uint32_t sign_word, uint32_t first) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        v[2 * j] = u2f((w[j] << 16) + sign_bit(sign_word, first + 2u * j));
+        v[2 * j + 1] = u2f((w[j] & 0xFFFF0000u) ^ sign_bit(sign_word, first + 2u * j + 1u));
+    }
+}
+
 __device__ __forceinline__ void unpack_bf16x8(const uint4& q, float* v) {
     v[0] = u2f(q.x << 16); v[1] = u2f(q.x & 0xFFFF0000u);
     v[2] = u2f(q.y << 16); v[3] = u2f(q.y & 0xFFFF0000u);
@@ -167,14 +183,15 @@ __device__ __forceinline__ void quant_row_tile(const uint16_t* __restrict__ x, u
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
         uint4 q = stage[wave][4u * lane + (j ^ ((lane >> 2) & 3u))];
-        unpack_bf16x8(q, &v[8 * j]);
+        if (MODE != kFwd && !BIG) unpack_bf16x8_signed(q, &v[8 * j], p.sign_word, 8u * j);
+        else unpack_bf16x8(q, &v[8 * j]);
     }
     const uint32_t row_local = wave * 2u + (lane >> 5), gi = lane & 31u;
     const uint32_t row = row0 + row_local, g = kq0 * 8u + gi;
     uint4 out;
     uint32_t sb, mw;
     if (BIG) quantize_group_lanes<MODE>(v, p, lane, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
-    else quantize_group<MODE>(v, p, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
+    else quantize_group<MODE, true>(v, p, ((uint64_t)row * gk + g) * 2u, out, sb, mw);
     // scale byte of (row, group gi) -> position of the tiled layout inside the block's 256 bytes:
     // [K-quad gi/8][h = gi%2][row_local][p = (gi%8)/2]
     reinterpret_cast<uint8_t*>(s_scale)[(((gi >> 3) * 2u + (gi & 1u)) * 8u + row_local) * 4u + ((gi & 7u) >> 1)] = (uint8_t)sb;
@@ -331,11 +348,14 @@ __device__ __forceinline__ void quant_transposed_tile(const uint16_t* __restrict
         for (uint32_t c = 0; c < 2; ++c) {
             float v[32];
 #pragma unroll
-            for (uint32_t i = 0; i < 32; ++i) v[i] = c ? u2f(raw[rb][i] & 0xFFFF0000u) : u2f(raw[rb][i] << 16);
+            for (uint32_t i = 0; i < 32; ++i) {       // with the sign vector applied on the way (forward: sign word 0 in p)
+                const uint32_t sbit = MODE != kFwd ? sign_bit(p.sign_word, i) : 0u;
+                v[i] = c ? u2f((raw[rb][i] & 0xFFFF0000u) ^ sbit) : u2f((raw[rb][i] << 16) + sbit);
+            }
             uint4 q;
             uint32_t sb, m;
             // output position of element 0 of the group: row*k + grp*32, divided by 16
-            quantize_group<MODE>(v, p, ((uint64_t)(col + c) * k + grp * 32u) >> 4, q, sb, m);
+            quantize_group<MODE, true>(v, p, ((uint64_t)(col + c) * k + grp * 32u) >> 4, q, sb, m);
             const uint32_t lc = 2u * lane + c;            // local column
             s_codes[(lc ^ ((lc >> 4) & 1u)) * 8u + (gl ^ sw)] = q;
             s_scales[lc * 8u + gl] = (uint8_t)sb;
@@ -488,6 +508,9 @@ __device__ __forceinline__ void requant_transposed_wave(const uint8_t* __restric
     // quantize role: output row c0 + lane
     const uint32_t out_row = c0 + lane, rot = (16u * (lane >> 5)) & 31u;
 
+    // sign of element rl of the rotation's sign vector as the sign bits of eight E2M1 codes (sign-magnitude: decoding
+    // the flipped code gives the negated value exactly, zeros included)
+    const uint32_t code_flip = (MODE != kFwd && ((p.sign_word >> rl) & 1u)) ? 0x88888888u : 0u;
     v4u_t cw = __builtin_amdgcn_raw_buffer_load_b128(res_c, (int)code_off, 0, 0);
     uint32_t sb_src = __builtin_amdgcn_raw_buffer_load_b8(res_s, (int)scale_off, 0, 0);
     uint32_t sw0 = 0u, sw1 = 0u;   // the row's scale bytes as the two dwords of the output's scale tile (groups h, 2+h, 4+h, 6+h)
@@ -506,7 +529,8 @@ __device__ __forceinline__ void requant_transposed_wave(const uint8_t* __restric
         __builtin_amdgcn_sched_barrier(0);                                                              \
         asm volatile("" : "+v"(sb_src)); /* the scale is formed here, not next to its load: no early wait */ \
         const float sc = u2f(sb_src << 23);                                                             \
-        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};                                                 \
+        /* the sign vector applied on the codes: all 32 values of this lane are element rl of their groups */ \
+        const uint32_t w[4] = {cw.x ^ code_flip, cw.y ^ code_flip, cw.z ^ code_flip, cw.w ^ code_flip}; \
         float f[32];                                                                                    \
         _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
             v2f a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(w[i], sc, 0);                              \
@@ -530,7 +554,7 @@ __device__ __forceinline__ void requant_transposed_wave(const uint8_t* __restric
             v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;                 \
         }                                                                                               \
         uint32_t sb, mw;                                                                                \
-        quantize_group<MODE>(v, p, ((uint64_t)out_row * k + (grp0 + (G)) * 32u) >> 4, OUT, sb, mw);     \
+        quantize_group<MODE, true>(v, p, ((uint64_t)out_row * k + (grp0 + (G)) * 32u) >> 4, OUT, sb, mw); \
         if ((G) & 1u) sw1 |= sb << (8u * ((G) >> 1));                                                   \
         else sw0 |= sb << (8u * ((G) >> 1));                                                            \
     }
