@@ -349,7 +349,7 @@ def main():
     ws_bytes = max(l.ws_bytes for l in layers)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     flops_step = sum(l.flops for l in layers)
-    launches_per_step = 11 * len(layers)   # capacity (wider Hadamard blocks): 2 + 1 forward, (2 + 1) x 2 backward, + 2 epilogue kernels; blocks of 32 need 6
+    launches_per_step = 11 * len(layers)   # capacity (wider Hadamard blocks): 2 + 1 forward, (2 + 1) x 2 backward, + 2 epilogue kernels; blocks of 32 need 5
 
     def one_step(step):
         for l in layers:

@@ -183,8 +183,8 @@ int quartet_fwd_operands(const void *x_bf16, const void *w_bf16, int64_t tokens,
  *   wt  = quartet_requant_transpose_sr(W_q, rows = in, k = out,    stream id 1)
  * with the same sign_word, seed and rounding; the six outputs are bit-identical to those of the
  * three calls (dyt [out x tokens], xt [in x tokens], wt [in x out], codes and tiled scales).
- * quartet_linear_bwd runs this, the dW product, quartet_quant_bwd_sr on dy (stream id 0), the dx
- * product.  Errors as for the three calls.
+ * quartet_linear_bwd runs the same kernel with quartet_quant_bwd_sr on dy (stream id 0) as a fourth
+ * part of the grid, then the dW and the dx product.  Errors as for the three calls.
  */
 int quartet_bwd_operands(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
                          const uint8_t *xq_codes, const uint8_t *xq_scales,
@@ -288,7 +288,7 @@ size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out);
  * X_q^T.  tokens, in, out all % 32 == 0.  workspace: device memory of at least
  * quartet_linear_workspace_bytes() bytes, 256-byte aligned, used only during the call's work (it holds
  * the four quantized operands of the two gradient products, each in a region of its own).
- * Launch order: Q(dy^T), Q(X_q^T) and Q(W_q^T) in one kernel, the dW product, Q(dy), the dx product;
+ * Launches: Q(dy), Q(dy^T), Q(X_q^T) and Q(W_q^T) in one kernel, the dW product, the dx product;
  * the results do not depend on the order (every operand has its own Philox stream).
  */
 int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,

@@ -570,11 +570,22 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     if (m == 0 || n == 0) return hipSuccess;
     int variant = g_forced_variant;
     if (variant < 0) {
-        int64_t big_tiles = ((m + 255) / 256) * ((n + 255) / 256);
-        // measured on an MI355X: 176 big tiles (5632 x 2048 x 8192) run 1.25 x faster as 256 x 256 tiles than as 128 x 256
-        // ones although they leave 80 compute units idle; 128 big tiles (4096 x 2048 x 2048) run 1.2 x faster as 128 x 256
-        // tiles, one per compute unit
-        variant = big_tiles >= 160 ? 0 : 1;
+        // The tile shape that keeps most of the chip's matrix-core time useful: share of the compute-unit rounds that hold a
+        // tile x what a compute unit gets out of the shape (256x256: 1; 128x256: 0.84; 128x128: 0.54 -- per-area round times
+        // measured on an MI355X at K = 2048 .. 8192).  Checked against measured best shapes: 16384x4096x4096 and every other
+        // product of configuration 4 -> 256x256; 5632x2048x8192 (176 big tiles, 80 units idle) -> 256x256 (58.8 us against
+        // 73.2 as 128x256); 3072^3 -> 256x256; 4096x2048x2048 -> 128x256 (19.1 us against 23.0); 2048x2048x4096 -> 128x128
+        // (20.5 us against 23.7 and 34.9); 1024x1024x8192 -> 128x128.
+        const double cus = (double)stream_blocks();
+        const double worth[3] = {1.0, 0.84, 0.54};
+        const int64_t bm[3] = {256, 128, 128}, bn[3] = {256, 256, 128};
+        double best = -1.0;
+        for (int v = 0; v < 3; ++v) {
+            const double tiles = (double)(((m + bm[v] - 1) / bm[v]) * ((n + bn[v] - 1) / bn[v]));
+            const double rounds = (double)(int64_t)((tiles + cus - 1.0) / cus);
+            const double score = tiles / (rounds * cus) * worth[v];
+            if (score > best) { best = score; variant = v; }
+        }
     }
     if (fused && nb >= 4u && variant == 2) variant = 1;   // a block of 128 columns needs the 128-column wave tile
 #define QUARTET_DISPATCH(FN, ...)                                                                     \

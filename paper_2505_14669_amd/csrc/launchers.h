@@ -23,12 +23,14 @@ hipError_t launch_requant_transpose(int mode, const uint8_t* src_codes, const ui
 hipError_t launch_fwd_operands(const void* x, int64_t tokens, const void* w, int64_t out, int64_t in, uint8_t* xq_codes,
                                uint8_t* xq_scales, uint32_t* x_mask, uint8_t* wq_codes, uint8_t* wq_scales, uint32_t* w_mask,
                                const SrParams& p, hipStream_t st);
-// dy^T quantized along the tokens, X_q and W_q re-quantized along their other dimension: one launch (Hadamard block 32)
+// dy^T quantized along the tokens, X_q and W_q re-quantized along their other dimension: one launch (Hadamard block 32);
+// with dy_codes != null also dy itself quantized along out (parameters p_dy) in the same launch
 hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t in, int64_t out,
                                const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
                                const SrParams& p_dyt, const SrParams& p_x, const SrParams& p_w,
                                uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
-                               uint8_t* wt_codes, uint8_t* wt_scales, hipStream_t st);
+                               uint8_t* wt_codes, uint8_t* wt_scales,
+                               const SrParams& p_dy, uint8_t* dy_codes, uint8_t* dy_scales, hipStream_t st);
 hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t rows, int64_t k, float* out,
                           hipStream_t st);
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,

@@ -635,6 +635,9 @@ struct BwdOperandsMap {
     uint32_t n_rq_w, n_rq;           // re-quantizer blocks of W_q, and of W_q and X_q together: block indices [0, n_rq)
     uint32_t t_gx, w_quads, x_quads; // dy^T tiles per column tile row (K-quads); 256-column stretches of W_q^T, X_q^T
     FastDiv div_t_gx, div_w_quads, div_x_quads;
+    uint32_t n_tiles_end;            // blocks [n_rq, n_tiles_end): dy^T tiles; blocks from n_tiles_end on: row tiles of dy (optional)
+    uint32_t r_k_blocks;             // row tiles per 8 rows of dy
+    FastDiv div_r_k_blocks;
 };
 
 template <int MODE>
@@ -644,9 +647,11 @@ bwd_operands_kernel(const uint16_t* __restrict__ dy, uint32_t t_rows, uint32_t t
                     const uint8_t* __restrict__ x_src_codes, const uint8_t* __restrict__ x_src_scales, uint32_t x_rows, uint32_t x_k,
                     uint8_t* __restrict__ x_codes, uint8_t* __restrict__ x_scales, SrParams x_p,
                     const uint8_t* __restrict__ w_src_codes, const uint8_t* __restrict__ w_src_scales, uint32_t w_rows, uint32_t w_k,
-                    uint8_t* __restrict__ w_codes, uint8_t* __restrict__ w_scales, SrParams w_p, BwdOperandsMap map) {
+                    uint8_t* __restrict__ w_codes, uint8_t* __restrict__ w_scales, SrParams w_p,
+                    uint4* __restrict__ r_codes, uint8_t* __restrict__ r_scales, SrParams r_p, BwdOperandsMap map) {
     __shared__ __align__(16) uint8_t smem[4u * 64u * kStageStride * sizeof(float)];   // 36 KB: four re-quantizer stages
     static_assert(sizeof(smem) >= 128 * 8 * (16 + 1 + 4), "the dy^T tile's staging must fit as well");
+    static_assert(sizeof(smem) >= 4 * 256 * 16 + 64 * 4, "the row tile's staging must fit as well");
     const uint32_t b = blockIdx.x;
     if (b < map.n_rq) {
         const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -659,6 +664,13 @@ bwd_operands_kernel(const uint16_t* __restrict__ dy, uint32_t t_rows, uint32_t t
             const uint32_t kq = fast_div(j, map.div_x_quads), quad = j - kq * map.x_quads;
             requant_transposed_wave<MODE>(x_src_codes, x_src_scales, x_rows, x_k, x_codes, x_scales, x_p, wave, quad, kq, stage);
         }
+    } else if (b >= map.n_tiles_end) {
+        // Q(dy) in row mode (the first operand of the dx product), for callers that want all four conversions in one launch:
+        // dy is [t_k x t_rows] row-major, groups along its rows
+        uint4 (*stage)[256] = reinterpret_cast<uint4 (*)[256]>(smem);
+        uint32_t* s_scale = reinterpret_cast<uint32_t*>(smem + 4 * 256 * 16);
+        quant_row_tile<MODE, false, false>(dy, t_k, t_rows >> 5, t_ldx, r_codes, r_scales, nullptr, r_p, map.r_k_blocks,
+                                           map.div_r_k_blocks, b - map.n_tiles_end, stage, s_scale);
     } else {
         const uint32_t tb = b - map.n_rq;
         const uint32_t by = fast_div(tb, map.div_t_gx), bx = tb - by * map.t_gx;
@@ -926,7 +938,8 @@ hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t
                                const uint8_t* xq_codes, const uint8_t* xq_scales, const uint8_t* wq_codes, const uint8_t* wq_scales,
                                const SrParams& p_dyt, const SrParams& p_x, const SrParams& p_w,
                                uint8_t* dyt_codes, uint8_t* dyt_scales, uint8_t* xt_codes, uint8_t* xt_scales,
-                               uint8_t* wt_codes, uint8_t* wt_scales, hipStream_t st) {
+                               uint8_t* wt_codes, uint8_t* wt_scales,
+                               const SrParams& p_dy, uint8_t* dy_codes, uint8_t* dy_scales, hipStream_t st) {
     BwdOperandsMap map;
     // dy^T: logical [out x tokens]; X_q^T: [in x tokens] from [tokens x in]; W_q^T: [in x out] from [out x in].
     // An empty dimension empties the conversions it belongs to, not the others.
@@ -935,21 +948,29 @@ hipError_t launch_bwd_operands(int mode, const void* dy, int64_t tokens, int64_t
     map.w_quads = map.x_quads = (uint32_t)((in + 255) / 256);
     map.n_rq_w = map.w_quads * (uint32_t)((out + 255) / 256);
     map.n_rq = map.n_rq_w + map.x_quads * (uint32_t)((tokens + 255) / 256);
-    const uint64_t total = (uint64_t)map.t_gx * t_gy + map.n_rq;
+    uint64_t total = (uint64_t)map.t_gx * t_gy + map.n_rq;
+    if (total >= ((uint64_t)1 << 31)) return hipErrorInvalidValue;
+    map.n_tiles_end = (uint32_t)total;
+    // optional fourth conversion: dy [tokens x out] in row mode, 8 rows x 1024 columns per block
+    map.r_k_blocks = (uint32_t)((out / 32 + 31) / 32);
+    if (dy_codes) total += (uint64_t)((tokens + 7) / 8) * map.r_k_blocks;
     if (total == 0) return hipSuccess;
     if (total >= ((uint64_t)1 << 31)) return hipErrorInvalidValue;
     map.div_t_gx = make_fast_div(map.t_gx ? map.t_gx : 1u);
     map.div_w_quads = make_fast_div(map.w_quads ? map.w_quads : 1u);
     map.div_x_quads = make_fast_div(map.x_quads ? map.x_quads : 1u);
+    map.div_r_k_blocks = make_fast_div(map.r_k_blocks ? map.r_k_blocks : 1u);
     dim3 grid((uint32_t)total), block(256);
     if (mode == kBwdRtn)
         hipLaunchKernelGGL((bwd_operands_kernel<kBwdRtn>), grid, block, 0, st, (const uint16_t*)dy, (uint32_t)out, (uint32_t)tokens, out,
                            dyt_codes, dyt_scales, p_dyt, xq_codes, xq_scales, (uint32_t)in, (uint32_t)tokens, xt_codes, xt_scales, p_x,
-                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w, map);
+                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w,
+                           reinterpret_cast<uint4*>(dy_codes), dy_scales, p_dy, map);
     else
         hipLaunchKernelGGL((bwd_operands_kernel<kBwdSr>), grid, block, 0, st, (const uint16_t*)dy, (uint32_t)out, (uint32_t)tokens, out,
                            dyt_codes, dyt_scales, p_dyt, xq_codes, xq_scales, (uint32_t)in, (uint32_t)tokens, xt_codes, xt_scales, p_x,
-                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w, map);
+                           wq_codes, wq_scales, (uint32_t)in, (uint32_t)out, wt_codes, wt_scales, p_w,
+                           reinterpret_cast<uint4*>(dy_codes), dy_scales, p_dy, map);
     return hipGetLastError();
 }
 

@@ -9,7 +9,7 @@ namespace quartet {
 hipError_t launch_quant(int, const void*, int64_t, int64_t, int64_t, int, const SrParams&, uint8_t*, uint8_t*, uint32_t*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_requant_transpose(int, const uint8_t*, const uint8_t*, int64_t, int64_t, const SrParams&, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_fwd_operands(const void*, int64_t, const void*, int64_t, int64_t, uint8_t*, uint8_t*, uint32_t*, uint8_t*, uint8_t*, uint32_t*, const SrParams&, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_bwd_operands(int, const void*, int64_t, int64_t, int64_t, const uint8_t*, const uint8_t*, const uint8_t*, const uint8_t*, const SrParams&, const SrParams&, const SrParams&, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_bwd_operands(int, const void*, int64_t, int64_t, int64_t, const uint8_t*, const uint8_t*, const uint8_t*, const uint8_t*, const SrParams&, const SrParams&, const SrParams&, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, const SrParams&, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_dequant(const uint8_t*, const uint8_t*, int64_t, int64_t, float*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_gemm(const uint8_t*, const uint8_t*, const uint8_t*, const uint8_t*, int64_t, int64_t, int64_t, float, void*, int, int64_t, int, const uint32_t*, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 void set_gemm_plan(int, int) {}
