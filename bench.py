@@ -349,7 +349,7 @@ def main():
     ws_bytes = max(l.ws_bytes for l in layers)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
     flops_step = sum(l.flops for l in layers)
-    launches_per_step = 11 * len(layers)   # capacity (wider Hadamard blocks): 2 + 1 forward, (2 + 1) x 2 backward, + 2 epilogue kernels; blocks of 32 need 5
+    launches_per_step = 11 * len(layers)   # capacity (wider Hadamard blocks): 2 + 1 forward, (2 + 1) x 2 backward, + 2 epilogue kernels; blocks of 32 need 4
 
     def one_step(step):
         for l in layers:
@@ -404,21 +404,28 @@ def main():
     # per GEMM shape, from the same event pairs (launch order inside a step: forward, dW, dX of each layer): the rate,
     # and the share of the HBM peak that the minimum traffic (operands once, result once) comes to -- products with a
     # short inner dimension and an fp32 result are bound by the result's stores, not by the matrix cores
+    # (Hadamard block 32: the backward pass runs its two products, dW and dX, in one launch: two records per layer)
     by_shape = {}
-    if len(gemm_ms) == 3 * len(layers) * args.steps:
+    per_layer = 2 if args.hadamard_block == 32 else 3
+    if len(gemm_ms) == per_layer * len(layers) * args.steps:
         for idx, m_s in enumerate(gemm_ms):
-            l, which = layers[(idx // 3) % len(layers)], idx % 3
-            mnk = ((l.t, l.o, l.i), (l.o, l.i, l.t), (l.t, l.i, l.o))[which]
-            by_shape.setdefault(mnk, []).append(m_s)
+            l, which = layers[(idx // per_layer) % len(layers)], idx % per_layer
+            fwd, dw, dx = (l.t, l.o, l.i), (l.o, l.i, l.t), (l.t, l.i, l.o)
+            key = ((fwd,), (dw, dx))[which] if per_layer == 2 else ((fwd,), (dw,), (dx,))[which]
+            by_shape.setdefault(key, []).append(m_s)
     gemm_by_shape = []
-    for (m, n, k), v in sorted(by_shape.items()):
+    for products, v in sorted(by_shape.items()):
         avg = sum(v) / len(v)
-        min_bytes = (m + n) * k * (0.5 + 1.0 / 32.0) + 4.0 * m * n
-        gemm_by_shape.append({"m": m, "n": n, "k": k, "launches": len(v), "avg_ms": round(avg, 4),
-                              "TFLOPs": round(2.0 * m * n * k / avg / 1e9, 1),
-                              "frac_mfma": round(2.0 * m * n * k / avg / 1e9 / PEAK_FP4_TFLOPS, 4),
-                              "min_GBps": round(min_bytes / avg / 1e6, 1),
-                              "frac_hbm": round(min_bytes / avg / 1e6 / PEAK_HBM_GBS, 4)})
+        flops = sum(2.0 * m * n * k for (m, n, k) in products)
+        min_bytes = sum((m + n) * k * (0.5 + 1.0 / 32.0) + 4.0 * m * n for (m, n, k) in products)
+        entry = {"m": products[0][0], "n": products[0][1], "k": products[0][2]}
+        if len(products) == 2:
+            entry = {"products": [list(pr) for pr in products], "what": "dW and dX of one layer in one launch"}
+        entry.update({"launches": len(v), "avg_ms": round(avg, 4), "TFLOPs": round(flops / avg / 1e9, 1),
+                      "frac_mfma": round(flops / avg / 1e9 / PEAK_FP4_TFLOPS, 4),
+                      "min_GBps": round(min_bytes / avg / 1e6, 1),
+                      "frac_hbm": round(min_bytes / avg / 1e6 / PEAK_HBM_GBS, 4)})
+        gemm_by_shape.append(entry)
 
     ms_per_step = dt * 1e3 / args.steps
     big_gemm = any(((l.t + 255) // 256) * ((l.o + 255) // 256) >= 160 for l in layers)
@@ -436,7 +443,7 @@ def main():
                                + ("" if args.hadamard_block == 32 else f", Hadamard block {args.hadamard_block}"),
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
         "roofline": {"bound": "mfma",
-                     "kernel": ("gemm_mxfp4_stream_kernel" if big_gemm else "gemm_mxfp4_kernel") + " (all three GEMMs of every layer)",
+                     "kernel": ("gemm_mxfp4_stream_kernel" if big_gemm else "gemm_mxfp4_kernel") + " (all three GEMMs of every layer: the forward product, and dW with dX in one launch)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
                      "traffic": recorded(args.config, "gemm_config{config}_hbm_traffic.txt", "traffic_bytes_per_launch"),

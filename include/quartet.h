@@ -230,6 +230,29 @@ int quartet_mxfp4_gemm_grad(const uint8_t *a_codes, const uint8_t *a_scales,
                             void *d, int d_dtype, int64_t ldd, void *stream);
 
 /*
+ * Two products with the gradient epilogue in one launch (Algorithm 1 Backward computes dW and dx from four operands
+ * that are all known before either product starts, so neither waits for the other).  Each argument block describes one
+ * product exactly as the arguments of quartet_mxfp4_gemm_grad do; both results have the type d_dtype.  The structures
+ * are read on the host during the call; every pointer inside them is a device pointer.  The results are bit-identical
+ * to two calls of quartet_mxfp4_gemm_grad (first, then second).  The compute units go through the first product's tiles,
+ * then the second's, without draining in between: one ramp-up and one drain, and the second product fills the compute
+ * units the first leaves idle in its last round.  (When either product alone would run on tiles smaller than 256 x 256,
+ * the two are simply launched one after the other.)  The two results must not overlap.  Errors as
+ * quartet_mxfp4_gemm_grad, checked for both products before anything is launched.
+ */
+typedef struct quartet_gemm_grad_args {
+    const uint8_t *a_codes, *a_scales;   /* A: [m x k/2] codes, scales tiled for [m x k] */
+    const uint8_t *b_codes, *b_scales;   /* B: [n x k/2] codes, scales tiled for [n x k] */
+    int64_t m, n, k;
+    const uint32_t *mask;                /* [m x n/32] words or NULL */
+    float scale;
+    void *d;                             /* [m x ldd] fp32 or bf16 */
+    int64_t ldd;
+} quartet_gemm_grad_args;
+int quartet_mxfp4_gemm_grad_pair(const quartet_gemm_grad_args *first, const quartet_gemm_grad_args *second,
+                                 int d_dtype, void *stream);
+
+/*
  * MXFP8 twin of the quantizer and the GEMM, for the comparison the paper draws (Section 5, "Speedup
  * results": MXFP4 linear layers against MXFP8 ones; Section 3 names the format).  Elements are E4M3
  * (OCP 8-bit floating point: bias 7, largest magnitude 448, S.1111.111 = NaN, no infinities), one
@@ -288,8 +311,8 @@ size_t quartet_linear_workspace_bytes(int64_t tokens, int64_t in, int64_t out);
  * X_q^T.  tokens, in, out all % 32 == 0.  workspace: device memory of at least
  * quartet_linear_workspace_bytes() bytes, 256-byte aligned, used only during the call's work (it holds
  * the four quantized operands of the two gradient products, each in a region of its own).
- * Launches: Q(dy), Q(dy^T), Q(X_q^T) and Q(W_q^T) in one kernel, the dW product, the dx product;
- * the results do not depend on the order (every operand has its own Philox stream).
+ * Launches: Q(dy), Q(dy^T), Q(X_q^T) and Q(W_q^T) in one kernel, then the dW and the dx product in one kernel
+ * (quartet_mxfp4_gemm_grad_pair); the results do not depend on the order (every operand has its own Philox stream).
  */
 int quartet_linear_bwd(const void *dy_bf16, int64_t tokens, int64_t in, int64_t out,
                        const uint8_t *xq_codes, const uint8_t *xq_scales, const uint32_t *x_mask,

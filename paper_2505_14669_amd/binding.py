@@ -26,7 +26,7 @@ EXPORTS = [
     "quartet_profile_enable", "quartet_profile_kinds", "quartet_profile_read", "quartet_scale_bytes",
     "quartet_profile_clock", "quartet_wall_clock_khz", "quartet_probe_mfma_ceiling",
     "quartet_quant_fwd", "quartet_quant_bwd_sr", "quartet_requant_transpose_sr", "quartet_fwd_operands", "quartet_bwd_operands",
-    "quartet_mxfp4_gemm", "quartet_debug_set_gemm_plan", "quartet_mxfp4_gemm_grad", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
+    "quartet_mxfp4_gemm", "quartet_debug_set_gemm_plan", "quartet_mxfp4_gemm_grad", "quartet_mxfp4_gemm_grad_pair", "quartet_mxfp8_quant", "quartet_mxfp8_gemm", "quartet_grad_epilogue", "quartet_mxfp4_dequant",
     "quartet_linear_fwd", "quartet_linear_workspace_bytes", "quartet_linear_bwd",
     "quartet_static_scratch_bytes", "quartet_linear_bwd_static",
     "quartet_sign_words", "quartet_quant_fwd_block", "quartet_quant_bwd_sr_block",
@@ -62,6 +62,15 @@ _lib.quartet_bwd_operands.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p, _p, _u32
 _lib.quartet_mxfp4_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
 _lib.quartet_debug_set_gemm_plan.argtypes = [_int, _int]
 _lib.quartet_mxfp4_gemm_grad.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _p, _f, _p, _int, _i64, _p]
+
+
+class GemmGradArgs(ctypes.Structure):
+    """quartet_gemm_grad_args: one product of quartet_mxfp4_gemm_grad_pair (host structure of device pointers and sizes)."""
+    _fields_ = [("a_codes", _p), ("a_scales", _p), ("b_codes", _p), ("b_scales", _p),
+                ("m", _i64), ("n", _i64), ("k", _i64), ("mask", _p), ("scale", _f), ("d", _p), ("ldd", _i64)]
+
+
+_lib.quartet_mxfp4_gemm_grad_pair.argtypes = [ctypes.POINTER(GemmGradArgs), ctypes.POINTER(GemmGradArgs), _int, _p]
 _lib.quartet_mxfp8_quant.argtypes = [_p, _i64, _i64, _i64, _p, _p, _p]
 _lib.quartet_mxfp8_gemm.argtypes = [_p, _p, _p, _p, _i64, _i64, _i64, _f, _p, _int, _i64, _p]
 _lib.quartet_grad_epilogue.argtypes = [_p, _p, _i64, _i64, _f, _p, _int, _p]
@@ -213,6 +222,16 @@ def quartet_debug_set_gemm_plan(variant, band_height):
 def quartet_mxfp4_gemm_grad(a_codes, a_scales, b_codes, b_scales, m, n, k, mask, scale, d, d_dtype, ldd, stream=None):
     return _lib.quartet_mxfp4_gemm_grad(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k,
                                         _ptr(mask), scale, _ptr(d), d_dtype, ldd, _stream(stream))
+
+
+def gemm_grad_args(a_codes, a_scales, b_codes, b_scales, m, n, k, mask, scale, d, ldd):
+    """One argument block of quartet_mxfp4_gemm_grad_pair (the tensors must stay alive until the call has been made)."""
+    return GemmGradArgs(_ptr(a_codes), _ptr(a_scales), _ptr(b_codes), _ptr(b_scales), m, n, k, _ptr(mask), scale, _ptr(d), ldd)
+
+
+def quartet_mxfp4_gemm_grad_pair(first, second, d_dtype, stream=None):
+    return _lib.quartet_mxfp4_gemm_grad_pair(ctypes.byref(first) if first is not None else None,
+                                             ctypes.byref(second) if second is not None else None, d_dtype, _stream(stream))
 
 
 def quartet_mxfp8_quant(x_bf16, rows, k, ldx, codes, scales, stream=None):

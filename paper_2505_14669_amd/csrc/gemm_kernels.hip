@@ -34,6 +34,25 @@ void set_gemm_plan(int variant, int band_height) {
     g_forced_band = band_height;
 }
 
+// One product of a launch of the 256 x 256 streaming kernel, and the one or two products a launch works through: the
+// block's virtual tile ids run over the first product's tiles, then the second's (Algorithm 1 Backward: the two gradient
+// products do not depend on each other; in one launch the second starts where the first leaves compute units idle and
+// there is one ramp-up and one drain instead of two).
+struct GemmProblem {
+    const uint8_t* a_codes;
+    const uint8_t* a_scales;
+    const uint8_t* b_codes;
+    const uint8_t* b_scales;
+    void* d;
+    const uint32_t* mask;
+    uint32_t m, n, k, ldd;
+    float alpha;
+    uint32_t tiles_m, tiles_n, band_height, total_tiles;
+};
+struct GemmBatch {
+    GemmProblem p[2];
+};
+
 template <int S>
 __device__ __forceinline__ v16f mfma_fp4(const uint4& a, const uint4& b, v16f c, uint32_t sa, uint32_t sb) {
     v8i va = {(int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0};
@@ -48,11 +67,7 @@ __device__ __forceinline__ v16f mfma_fp4(const uint4& a, const uint4& b, v16f c,
 // The epilogue uses a scratch of its own (16 KB beside the 144 KB ring).
 template <bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
-gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
-                         const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
-                         uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                         const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb,
-                         uint64_t* __restrict__ clock_counters) {
+gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uint64_t* __restrict__ clock_counters) {
     constexpr uint32_t TM = 4, TN = 4, BM = 256, BN = 256;
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
     constexpr uint32_t STAGE = CODES + 256;              // + 16 scale tiles of 256 B
@@ -70,58 +85,70 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-    const uint32_t total_tiles = tiles_m * tiles_n, G = gridDim.x;
-    const uint32_t per = total_tiles >> 3, rem = total_tiles & 7u;
-    const uint32_t GM = band_height;
+    const uint32_t G = gridDim.x, first_tiles = batch.p[0].total_tiles;
     const uint32_t wm0 = (wave >> 1) * 128u, wn0 = (wave & 1u) * 128u;
-    const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;
     const bool scales_of_a = wave < 2u;
 
-// tile origin of virtual block id V (XCD-aware order, bands of GM tile rows); V >= total_tiles: M0 = m (no rows)
-#define STREAM_TILE(V, M0, N0)                                                                          \
+// product SEL and the tile's number in it for virtual block id V (ids past the last tile: a number past the product's tiles)
+#define STREAM_PRODUCT(V, SEL, LOCAL)                                                                   \
     {                                                                                                   \
-        const uint32_t v_ = (V);                                                                        \
-        if (v_ < total_tiles) {                                                                         \
+        LOCAL = (V);                                                                                    \
+        SEL = 0u;                                                                                       \
+        if (LOCAL >= first_tiles) { LOCAL -= first_tiles; SEL = 1u; }                                   \
+    }
+// tile origin of tile number V of product Q (XCD-aware order, bands of band_height tile rows); V >= its tiles: M0 = m (no rows)
+#define STREAM_TILE(Q, V, M0, N0)                                                                       \
+    {                                                                                                   \
+        const uint32_t v_ = (V), tt_ = (Q).total_tiles;                                                 \
+        if (v_ < tt_) {                                                                                 \
+            const uint32_t per_ = tt_ >> 3, rem_ = tt_ & 7u, GM_ = (Q).band_height;                     \
+            const uint32_t tiles_m_ = (Q).tiles_m, tiles_n_ = (Q).tiles_n;                              \
             const uint32_t xcd_ = v_ & 7u;                                                              \
-            const uint32_t tile_ = xcd_ * per + (xcd_ < rem ? xcd_ : rem) + (v_ >> 3);                  \
-            const uint32_t band_ = tile_ / (GM * tiles_n);                                              \
-            const uint32_t band_rows_ = (tiles_m - band_ * GM) < GM ? (tiles_m - band_ * GM) : GM;      \
-            const uint32_t in_band_ = tile_ - band_ * GM * tiles_n;                                     \
-            M0 = (band_ * GM + in_band_ % band_rows_) * BM;                                             \
+            const uint32_t tile_ = xcd_ * per_ + (xcd_ < rem_ ? xcd_ : rem_) + (v_ >> 3);               \
+            const uint32_t band_ = tile_ / (GM_ * tiles_n_);                                            \
+            const uint32_t band_rows_ = (tiles_m_ - band_ * GM_) < GM_ ? (tiles_m_ - band_ * GM_) : GM_; \
+            const uint32_t in_band_ = tile_ - band_ * GM_ * tiles_n_;                                   \
+            M0 = (band_ * GM_ + in_band_ % band_rows_) * BM;                                            \
             N0 = (in_band_ / band_rows_) * BN;                                                          \
         } else {                                                                                        \
-            M0 = m; N0 = n;                                                                             \
+            M0 = (Q).m; N0 = (Q).n;                                                                     \
         }                                                                                               \
     }
     // issue cursor: the tile and stage the next LDS-direct loads belong to
+    // (its product's inner dimension decides the offsets: kb = bytes per code row, kq = K-quads, S2i = stages per tile)
     uint32_t iv = blockIdx.x, ist = 0u;
     v4i_t res_a, res_b, res_s;
+    uint32_t kb, istages, S2i, goff, gstep, soff;
+    const uint32_t drow = wave * 16u + (lane >> 2);
+    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
 #define STREAM_ISSUE_SETUP()                                                                            \
     {                                                                                                   \
-        uint32_t m0_, n0_;                                                                              \
-        STREAM_TILE(iv, m0_, n0_)                                                                       \
-        const uint32_t rows_a_ = (m - m0_) < BM ? (m - m0_) : BM, rows_b_ = (n - n0_) < BN ? (n - n0_) : BN; \
-        res_a = make_rsrc_words(a_codes + (size_t)m0_ * kb, rows_a_ * kb);                              \
-        res_b = make_rsrc_words(b_codes + (size_t)n0_ * kb, rows_b_ * kb);                              \
+        uint32_t sel_, lv_, m0_, n0_;                                                                   \
+        STREAM_PRODUCT(iv, sel_, lv_)                                                                   \
+        const GemmProblem& q_ = batch.p[sel_];                                                          \
+        STREAM_TILE(q_, lv_, m0_, n0_)                                                                  \
+        const uint32_t k_ = q_.k, kq_ = (k_ + 255u) >> 8;                                               \
+        kb = k_ >> 1;                                                                                   \
+        istages = (k_ + 127u) >> 7;                                                                     \
+        S2i = istages < 2u ? 2u : ((istages + 1u) & ~1u);                                               \
+        goff = drow * kb + dcol * 16u;          /* + j*64*kb, + stage*64 */                             \
+        gstep = 64u * kb;                                                                               \
+        soff = (((wave & 1u) * 4u + (lane >> 4)) * kq_) * 256u + (lane & 15u) * 16u;   /* + quad*256 */ \
+        const uint32_t rows_a_ = (q_.m - m0_) < BM ? (q_.m - m0_) : BM, rows_b_ = (q_.n - n0_) < BN ? (q_.n - n0_) : BN; \
+        res_a = make_rsrc_words(q_.a_codes + (size_t)m0_ * kb, rows_a_ * kb);                           \
+        res_b = make_rsrc_words(q_.b_codes + (size_t)n0_ * kb, rows_b_ * kb);                           \
         const uint32_t srow0_ = scales_of_a ? m0_ : n0_, srows_ = scales_of_a ? rows_a_ : rows_b_;      \
-        res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0_ >> 5) * kq * 256u, \
-                                ((srows_ + 31u) >> 5) * kq * 256u);                                     \
+        res_s = make_rsrc_words((scales_of_a ? q_.a_scales : q_.b_scales) + (size_t)(srow0_ >> 5) * kq_ * 256u, \
+                                ((srows_ + 31u) >> 5) * kq_ * 256u);                                    \
     }
     STREAM_ISSUE_SETUP()
 
-    const uint32_t drow = wave * 16u + (lane >> 2);
-    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
-    const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
-    const uint32_t gstep = 64u * kb;
-    const uint32_t soff = (((wave & 1u) * 4u + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
     const uint32_t swz = (lrow >> 2) & 3u;
     const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
     const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
     const uint32_t sb_base = CODES * 4u + 8u * 64u + (wn0 >> 5) * 64u + lane;
 
-    const uint32_t stages = (k + 127u) >> 7;
-    const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);   // stages per tile, even (extra stages are zero-filled)
     uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
     uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
@@ -133,14 +160,14 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
             const uint32_t base_ = (ist * 64u + dcol * 16u < kb) ? goff + ist * 64u : kOutOfRange;      \
             lds_direct_load16((J) < 4u ? res_a : res_b, base_ + ((J) & 3u) * gstep, slot_ + (J) * 4096u); \
         } else {                                                                                        \
-            lds_direct_load16(res_s, (ist < stages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+            lds_direct_load16(res_s, (ist < istages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
         }                                                                                               \
     }
 // the stage is issued: move the cursor on (to the next tile of this block after the tile's last stage)
 #define STREAM_ISSUE_ADVANCE()                                                                          \
     {                                                                                                   \
         ++ist;                                                                                          \
-        if (ist == S2) {                                                                                \
+        if (ist == S2i) {                                                                               \
             ist = 0u;                                                                                   \
             iv += G;                                                                                    \
             STREAM_ISSUE_SETUP()                                                                        \
@@ -163,16 +190,17 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (uint32_t i = 0; i < TM; ++i) { STREAM_FRAG_A(0u, 0u, fa0, i) STREAM_FRAG_B(0u, 0u, fb0, i) }
-    const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
-// scale dwords of the K-quad that starts with (even) local stage ST, held in ring slot SLOT; bytes of groups past k/32 become 2^0
-#define STREAM_SCALES(SLOT, ST, XA, XB)                                                                 \
+// scale dwords of the K-quad that starts with (even) local stage ST of a tile whose product has GK groups along K, held in
+// ring slot SLOT; bytes of groups past GK become 2^0
+#define STREAM_SCALES(SLOT, ST, GK, XA, XB)                                                             \
     {                                                                                                   \
         const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(SLOT) * STAGE]);                \
         uint32_t ra_[TM], rb_[TN];                                                                      \
         _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_[i] = sbuf_[sa_base + i * 64u];          \
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_[j] = sbuf_[sb_base + j * 64u];          \
         uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
-        if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */             \
+        if (((ST) + 2u) * 4u > (GK)) {        /* wave-uniform: only a ragged last K-quad */             \
+            const uint32_t ksteps_lane = ((GK) + 1u - lhalf) >> 1;   /* K-steps in which this half-wave has a group */ \
             const uint32_t done_ = (ST) * 2u;                                                           \
             const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
             keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
@@ -180,13 +208,15 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
     }
-    STREAM_SCALES(0u, 0u, sa, sb)
+    uint32_t csel, clv;
+    STREAM_PRODUCT(blockIdx.x, csel, clv)
+    STREAM_SCALES(0u, 0u, batch.p[csel].k >> 5, sa, sb)
 #define STREAM_MF(S, FA, FB, I, J)                                                                      \
     acc[I][J] = mfma_fp4<S>(FA[I], FB[J], acc[I][J], sa[I], sb[J]);                                     \
     asm volatile("" : "+a"(acc[I][J]));                                                                 \
     STREAM_FENCE()
 // one stage: PAR = its parity, ST = its local index, slots: SL = its own, SL1 = the next stage's, SLI = the one being filled
-#define STREAM_BODY(PAR, ST, SL, SL1, SLI, NEXT_ST)                                                     \
+#define STREAM_BODY(PAR, ST, SL, SL1, SLI, NEXT_ST, NEXT_GK)                                            \
     {                                                                                                   \
         STREAM_MF(2 * PAR, fa0, fb0, 0, 0) STREAM_FRAG_B(SL, 1u, fb1, 0) STREAM_FENCE()                 \
         STREAM_MF(2 * PAR, fa0, fb0, 0, 1) STREAM_FRAG_B(SL, 1u, fb1, 1) STREAM_FENCE()                 \
@@ -223,7 +253,7 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 3) STREAM_FRAG_A(SL1, 0u, fa0, 1) STREAM_FENCE()            \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 0) STREAM_FRAG_A(SL1, 0u, fa0, 2) STREAM_FENCE()            \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 1) STREAM_FRAG_A(SL1, 0u, fa0, 3) STREAM_FENCE()            \
-        if (PAR == 1) { STREAM_SCALES(SL1, NEXT_ST, sa_n, sb_n) STREAM_FENCE() }                        \
+        if (PAR == 1) { STREAM_SCALES(SL1, NEXT_ST, NEXT_GK, sa_n, sb_n) STREAM_FENCE() }               \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 2)                                                          \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 3)                                                          \
         if (PAR == 1) {                                                                                 \
@@ -236,6 +266,11 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
     float* wbuf = reinterpret_cast<float*>(&lds[kRing * STAGE]) + wave * 1024u;
     uint32_t g = 0u;                                       // stages done by this block (ring slot = g % kRing)
     for (uint32_t cv = blockIdx.x; cv < total_tiles; cv += G) {
+        STREAM_PRODUCT(cv, csel, clv)
+        const uint32_t ck = batch.p[csel].k, gk = ck >> 5, stages = (ck + 127u) >> 7;
+        const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);   // stages per tile, even (extra stages are zero-filled)
+        // the tile's last pair of stages reads the first scales of the block's next tile, which may belong to the other product
+        const uint32_t gk_after = (cv + G >= first_tiles && cv + G < total_tiles) ? (batch.p[1].k >> 5) : gk;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -245,18 +280,22 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         for (uint32_t st = 0u; st < S2; st += 2u, g += 2u) {
             const uint32_t sl = g & 3u;                    // g is even: sl is 0 or 2
             const uint32_t next_st = st + 2u < S2 ? st + 2u : 0u;   // after the tile's last pair: the next tile's stage 0
-            STREAM_BODY(0, st, sl, sl + 1u, sl ^ 3u, 0u)                        /* fills slot (g + 3) % 4 */
-            STREAM_BODY(1, st + 1u, sl + 1u, sl ^ 2u, sl, next_st)              /* fills slot (g + 4) % 4 */
+            const uint32_t next_gk = st + 2u < S2 ? gk : gk_after;
+            STREAM_BODY(0, st, sl, sl + 1u, sl ^ 3u, 0u, 0u)                    /* fills slot (g + 3) % 4 */
+            STREAM_BODY(1, st + 1u, sl + 1u, sl ^ 2u, sl, next_st, next_gk)     /* fills slot (g + 4) % 4 */
         }
         // The ring already holds (or is receiving) the next tile's first stages, and fa0 / fb0 / sa / sb its first
         // fragments and scales.  The result stores below are older than every load issued from here on and the
         // vector-memory counter retires in order, so the next tile's first wait also waits for them.
+        const GemmProblem& q = batch.p[csel];
         uint32_t m0, n0;
-        STREAM_TILE(cv, m0, n0)
+        STREAM_TILE(q, clv, m0, n0)
+        const uint32_t m = q.m, n = q.n, ldd = q.ldd;
+        const uint32_t* __restrict__ mask = q.mask;
         const uint32_t row_base = m0 + wm0, col_base = n0 + wn0;
         const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n && (!FUSED || mask != nullptr);
-        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
-        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, q.d, ldd, mask, q.alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, q.d, ldd, mask, q.alpha, row_base, col_base, m, n, lane, nb);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
     if (clock_counters && tid == 0) {
@@ -264,6 +303,7 @@ gemm_mxfp4_stream_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __r
         atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters), (unsigned long long)(t1 - clk_t0));
         atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters) + 1, (unsigned long long)(w1 - clk_w0));
     }
+#undef STREAM_PRODUCT
 #undef STREAM_TILE
 #undef STREAM_ISSUE_SETUP
 #undef STREAM_ISSUE
@@ -531,17 +571,36 @@ static int stream_blocks() {
     return cus;
 }
 
+// tile grid and band height of one product for the 256 x 256 streaming kernel
+static GemmProblem make_problem(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes, const uint8_t* b_scales,
+                                int64_t m, int64_t n, int64_t k, float alpha, void* d, int64_t ldd, const uint32_t* mask) {
+    GemmProblem q;
+    q.a_codes = a_codes; q.a_scales = a_scales; q.b_codes = b_codes; q.b_scales = b_scales;
+    q.d = d; q.mask = mask;
+    q.m = (uint32_t)m; q.n = (uint32_t)n; q.k = (uint32_t)k; q.ldd = (uint32_t)ldd;
+    q.alpha = alpha;
+    q.tiles_m = (uint32_t)((m + 255) / 256); q.tiles_n = (uint32_t)((n + 255) / 256);
+    q.band_height = (q.tiles_n >= 40u && (q.tiles_m & 1u) == 0u) ? 2u : 4u;
+    if (g_forced_band > 0) q.band_height = (uint32_t)g_forced_band;
+    q.total_tiles = q.tiles_m * q.tiles_n;
+    return q;
+}
+
+template <bool OUT_BF16, bool FUSED>
+static void launch_stream_batch_t(const GemmBatch& batch, uint32_t nb, hipStream_t st) {
+    const uint32_t total = batch.p[0].total_tiles + batch.p[1].total_tiles, cus = (uint32_t)stream_blocks();
+    hipLaunchKernelGGL((gemm_mxfp4_stream_kernel<OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st, batch, total,
+                       nb, g_clock_counters);
+}
+
 template <bool OUT_BF16, bool FUSED>
 static void launch_stream_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                             const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                             int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
-    uint32_t tiles_m = (uint32_t)((m + 255) / 256), tiles_n = (uint32_t)((n + 255) / 256);
-    uint32_t gm = (tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
-    if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
-    const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
-    hipLaunchKernelGGL((gemm_mxfp4_stream_kernel<OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st, a_codes,
-                       a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, gm, nb, g_clock_counters);
+    GemmBatch batch;
+    batch.p[0] = make_problem(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask);
+    batch.p[1] = GemmProblem{};      // no second product
+    launch_stream_batch_t<OUT_BF16, FUSED>(batch, nb, st);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
@@ -564,10 +623,7 @@ static void launch_stream_tile_t(const uint8_t* a_codes, const uint8_t* a_scales
 // through it).
 // fused != 0: D = alpha * H_along_n((A B^T) . mask) with Hadamard blocks of nb = 1, 2 or 4 groups of 32 columns (mask may
 // be null = all ones), n % (32 nb) == 0.
-hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
-                       const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
-                       int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st) {
-    if (m == 0 || n == 0) return hipSuccess;
+static int pick_variant(int64_t m, int64_t n, int fused, uint32_t nb) {
     int variant = g_forced_variant;
     if (variant < 0) {
         // The tile shape that keeps most of the chip's matrix-core time useful: share of the compute-unit rounds that hold a
@@ -588,6 +644,14 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
         }
     }
     if (fused && nb >= 4u && variant == 2) variant = 1;   // a block of 128 columns needs the 128-column wave tile
+    return variant;
+}
+
+hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
+                       const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
+                       int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st) {
+    if (m == 0 || n == 0) return hipSuccess;
+    const int variant = pick_variant(m, n, fused, nb);
 #define QUARTET_DISPATCH(FN, ...)                                                                     \
     do {                                                                                              \
         if (d_bf16) { if (fused) FN<__VA_ARGS__ true, true>(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, nb, st); \
@@ -599,6 +663,25 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     else if (variant == 2) QUARTET_DISPATCH(launch_stream_tile_t, 2, 2, );
     else QUARTET_DISPATCH(launch_stream_t, );
 #undef QUARTET_DISPATCH
+    return hipGetLastError();
+}
+
+// Two gradient products in one launch of the 256 x 256 streaming kernel (both with the fused epilogue, results of one type).
+// When either product would not take that tile shape on its own, they are launched one after the other instead.
+hipError_t launch_gemm_grad_pair(const GemmArgs& g0, const GemmArgs& g1, int d_bf16, uint32_t nb, hipStream_t st) {
+    const bool empty0 = g0.m == 0 || g0.n == 0, empty1 = g1.m == 0 || g1.n == 0;
+    if (empty0 || empty1 || pick_variant(g0.m, g0.n, 1, nb) != 0 || pick_variant(g1.m, g1.n, 1, nb) != 0) {
+        hipError_t e = launch_gemm(g0.a_codes, g0.a_scales, g0.b_codes, g0.b_scales, g0.m, g0.n, g0.k, g0.alpha, g0.d, d_bf16, g0.ldd,
+                                   1, g0.mask, nb, st);
+        if (e != hipSuccess) return e;
+        return launch_gemm(g1.a_codes, g1.a_scales, g1.b_codes, g1.b_scales, g1.m, g1.n, g1.k, g1.alpha, g1.d, d_bf16, g1.ldd, 1,
+                           g1.mask, nb, st);
+    }
+    GemmBatch batch;
+    batch.p[0] = make_problem(g0.a_codes, g0.a_scales, g0.b_codes, g0.b_scales, g0.m, g0.n, g0.k, g0.alpha, g0.d, g0.ldd, g0.mask);
+    batch.p[1] = make_problem(g1.a_codes, g1.a_scales, g1.b_codes, g1.b_scales, g1.m, g1.n, g1.k, g1.alpha, g1.d, g1.ldd, g1.mask);
+    if (d_bf16) launch_stream_batch_t<true, true>(batch, nb, st);
+    else launch_stream_batch_t<false, true>(batch, nb, st);
     return hipGetLastError();
 }
 

@@ -36,6 +36,19 @@ hipError_t launch_dequant(const uint8_t* codes, const uint8_t* scales, int64_t r
 hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                        const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                        int d_bf16, int64_t ldd, int fused, const uint32_t* mask, uint32_t nb, hipStream_t st);
+// two gradient products (fused epilogue, same result type) in one launch where the tile-shape heuristic allows it
+struct GemmArgs {
+    const uint8_t* a_codes;
+    const uint8_t* a_scales;
+    const uint8_t* b_codes;
+    const uint8_t* b_scales;
+    int64_t m, n, k;
+    float alpha;
+    void* d;
+    int64_t ldd;
+    const uint32_t* mask;
+};
+hipError_t launch_gemm_grad_pair(const GemmArgs& g0, const GemmArgs& g1, int d_bf16, uint32_t nb, hipStream_t st);
 // variant: -1 = size heuristic, 0..2 = force that tile shape (256x256, 128x256, 128x128); band_height: 0 = heuristic, > 0 = tile rows per band
 void set_gemm_plan(int variant, int band_height);
 hipError_t launch_grad_epilogue(const float* g, const uint32_t* mask, int64_t m, int64_t n, uint32_t nb, float scale,

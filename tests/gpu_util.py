@@ -126,6 +126,22 @@ def gemm_grad(a_codes, a_scales, b_codes, b_scales, mask, scale, bf16=False, ldd
     return to_host(d, np.uint16 if bf16 else np.float32)
 
 
+def gemm_grad_pair(first, second, bf16=False):
+    """first, second: (a_codes, a_scales, b_codes, b_scales, mask, scale) of the two products; returns both results."""
+    keep, blocks, outs = [], [], []
+    for (a_codes, a_scales, b_codes, b_scales, mask, scale) in (first, second):
+        m, k = a_codes.shape[0], a_codes.shape[1] * 2
+        n = b_codes.shape[0]
+        d = dev_empty((m, n), np.uint16, 0x7FC0) if bf16 else dev_empty((m, n), np.float32, float("nan"))
+        tensors = [to_dev(a_codes), to_dev(scales_to_tiled(a_scales)), to_dev(b_codes), to_dev(scales_to_tiled(b_scales)),
+                   None if mask is None else to_dev(mask)]
+        keep.append(tensors)
+        blocks.append(q.gemm_grad_args(tensors[0], tensors[1], tensors[2], tensors[3], m, n, k, tensors[4], scale, d, n))
+        outs.append(d)
+    q.check(q.quartet_mxfp4_gemm_grad_pair(blocks[0], blocks[1], q.QUARTET_DTYPE_BF16 if bf16 else q.QUARTET_DTYPE_F32))
+    return tuple(to_host(d, np.uint16 if bf16 else np.float32) for d in outs)
+
+
 def grad_epilogue(g, mask, scale, bf16=False, in_place=False):
     m, n = g.shape
     gd = to_dev(g)

@@ -12,6 +12,7 @@ hipError_t launch_fwd_operands(const void*, int64_t, const void*, int64_t, int64
 hipError_t launch_bwd_operands(int, const void*, int64_t, int64_t, int64_t, const uint8_t*, const uint8_t*, const uint8_t*, const uint8_t*, const SrParams&, const SrParams&, const SrParams&, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, uint8_t*, const SrParams&, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_dequant(const uint8_t*, const uint8_t*, int64_t, int64_t, float*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_gemm(const uint8_t*, const uint8_t*, const uint8_t*, const uint8_t*, int64_t, int64_t, int64_t, float, void*, int, int64_t, int, const uint32_t*, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_gemm_grad_pair(const GemmArgs&, const GemmArgs&, int, uint32_t, hipStream_t) { ++g_launches; return hipSuccess; }
 void set_gemm_plan(int, int) {}
 hipError_t launch_grad_epilogue(const float*, const uint32_t*, int64_t, int64_t, uint32_t, float, void*, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_mfma_ceiling(const uint8_t*, const uint8_t*, uint32_t, uint32_t, float*, uint64_t*, hipStream_t) { ++g_launches; return hipSuccess; }

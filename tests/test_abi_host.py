@@ -52,6 +52,30 @@ def launches(q):
         return None
 
 
+def test_gemm_grad_pair_checks_both_products_before_launching():
+    from paper_2505_14669_amd import binding as q
+    P = 0x10000
+    E = q.QUARTET_EINVAL
+    good = lambda: q.gemm_grad_args(P, P, P, P, 64, 64, 64, P, 1.0, P, 64)
+    before = launches(q)
+    bad = []
+    for field, value in (("a_codes", None), ("b_scales", None), ("d", None), ("k", 48), ("n", 48), ("ldd", 32), ("m", -1),
+                         ("a_codes", P + 8), ("mask", P + 2), ("a_scales", P + 1)):
+        g = good()
+        setattr(g, field, value)
+        bad.append(g)
+    for g in bad:
+        assert q.quartet_mxfp4_gemm_grad_pair(g, good(), q.QUARTET_DTYPE_F32, 0) == E
+        assert q.quartet_mxfp4_gemm_grad_pair(good(), g, q.QUARTET_DTYPE_F32, 0) == E
+    assert q.quartet_mxfp4_gemm_grad_pair(None, good(), q.QUARTET_DTYPE_F32, 0) == E
+    assert q.quartet_mxfp4_gemm_grad_pair(good(), None, q.QUARTET_DTYPE_F32, 0) == E
+    assert q.quartet_mxfp4_gemm_grad_pair(good(), good(), 7, 0) == E
+    huge = good()
+    huge.k = 2 ** 24
+    assert q.quartet_mxfp4_gemm_grad_pair(good(), huge, q.QUARTET_DTYPE_F32, 0) == q.QUARTET_ENOTSUP
+    assert launches(q) == before
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     from paper_2505_14669_amd import binding as q
     P = 0x10000  # fake, aligned, never dereferenced: validation fails first

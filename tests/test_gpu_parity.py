@@ -231,6 +231,31 @@ def test_gemm_grad_fused(G, mnk, gemm_variant):
     assert within_elem_bound(got_nomask, oracle.grad_epilogue(acc, None, 1.0), absp, k, grad_scale=1.0)
 
 
+@pytest.mark.parametrize("shapes", [((40, 96, 64), (7, 32, 160)), ((300, 544, 192), (513, 288, 416)),
+                                    ((1, 32, 32), (260, 1056, 32)), ((2080, 2080, 96), (300, 4128, 224))])
+def test_gemm_grad_pair_matches_two_calls(G, shapes, gemm_variant):
+    # Algorithm 1 Backward: the dW and the dx product in one launch -- the same bits as one launch each, for products
+    # with different inner dimensions, ragged tiles, a product of one tile beside one of 150, and every tile shape
+    # (with tiles below 256 x 256 the entry point launches the two products one after the other)
+    prods = []
+    for idx, (m, n, k) in enumerate(shapes):
+        rng = np.random.default_rng(m * 1000 + n + k + idx)
+        prods.append((rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8),
+                      rng.integers(117, 137, size=(m, k // 32), dtype=np.uint8),
+                      rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8),
+                      rng.integers(117, 137, size=(n, k // 32), dtype=np.uint8),
+                      None if n == 1056 else rng.integers(0, 2 ** 32, size=(m, n // 32), dtype=np.uint32),
+                      oracle.FL_16_9 if idx == 0 else 1.25))
+    got = G.gemm_grad_pair(prods[0], prods[1])
+    for g, pr in zip(got, prods):
+        alone = G.gemm_grad(*pr)
+        assert np.array_equal(g.view(np.uint32), alone.view(np.uint32))
+        want = oracle.grad_epilogue(oracle.mxfp4_gemm(pr[0], pr[1], pr[2], pr[3]).astype(np.float32), pr[4], pr[5])
+        assert rel_fro(g, want) < FRO_TOL
+    got_bf = G.gemm_grad_pair(prods[1], prods[0], bf16=True)     # the other order, bf16 results
+    assert np.array_equal(got_bf[0], synth.f32_to_bf16(got[1])) and np.array_equal(got_bf[1], synth.f32_to_bf16(got[0]))
+
+
 @pytest.mark.parametrize("shape", [(1, 32), (6, 96), (77, 160), (256, 512)])
 def test_grad_epilogue(G, shape):
     rng = np.random.default_rng(shape[0])

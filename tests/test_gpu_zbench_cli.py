@@ -29,7 +29,7 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     roof = d["roofline"]
     assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 10100.0
     assert roof["achieved"] > 0 and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
-    assert roof["launches"] == 3 * 3                      # three products per layer pass, every one carries an event pair
+    assert roof["launches"] == 3 * 2                      # per layer pass: the forward product, and dW with dX under one event pair
     assert roof["mfma_ceiling"]["TFLOPs"] > 0 and 0.5 < roof["mfma_ceiling"]["clock_ghz"] < 3.0
     assert roof["traffic_source"].startswith("recorded")
     sweep = d["quantizer_sweep"]                          # configuration 5: 3 matrices x 5 modes
