@@ -232,10 +232,11 @@ def test_gemm_grad_fused(G, mnk, gemm_variant):
 
 
 @pytest.mark.parametrize("shapes", [((40, 96, 64), (7, 32, 160)), ((300, 544, 192), (513, 288, 416)),
-                                    ((1, 32, 32), (260, 1056, 32)), ((2080, 2080, 96), (300, 4128, 224))])
+                                    ((1, 32, 32), (260, 1056, 32)), ((4352, 4352, 64), (1100, 2080, 96))])
 def test_gemm_grad_pair_matches_two_calls(G, shapes, gemm_variant):
     # Algorithm 1 Backward: the dW and the dx product in one launch -- the same bits as one launch each, for products
-    # with different inner dimensions, ragged tiles, a product of one tile beside one of 150, and every tile shape
+    # with different inner dimensions, ragged tiles, a product of one tile beside one of ten, 289 tiles beside 45 (more tiles
+    # than compute units: blocks walk from one product into the other), and every tile shape
     # (with tiles below 256 x 256 the entry point launches the two products one after the other)
     prods = []
     for idx, (m, n, k) in enumerate(shapes):
