@@ -149,7 +149,7 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
     const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
     const uint32_t sb_base = CODES * 4u + 8u * 64u + (wn0 >> 5) * 64u + lane;
 
-    uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
+    uint32_t sa[TM], sb[TN], ra_n[TM], rb_n[TN];
     uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
 // load J (0..3: A rows, 4..7: B rows, 8: scale tiles) of the issue cursor's stage into ring slot SLOT
@@ -190,14 +190,19 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (uint32_t i = 0; i < TM; ++i) { STREAM_FRAG_A(0u, 0u, fa0, i) STREAM_FRAG_B(0u, 0u, fb0, i) }
-// scale dwords of the K-quad that starts with (even) local stage ST of a tile whose product has GK groups along K, held in
-// ring slot SLOT; bytes of groups past GK become 2^0
-#define STREAM_SCALES(SLOT, ST, GK, XA, XB)                                                             \
+// Scale dwords of a K-quad, in two steps a few hundred cycles apart: the raw dwords are read from ring slot SLOT right
+// behind the barrier that makes them visible, and turned into the operands of the next pair of stages (the K-quad that
+// starts with the even local stage ST of a tile whose product has GK groups along K; bytes of groups past GK become 2^0)
+// only behind the current pair's last matrix-core instruction.  Used at once, the reads made the wave wait for every LDS
+// read in flight at the end of each odd stage.
+#define STREAM_SCALES_READ(SLOT)                                                                        \
     {                                                                                                   \
         const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(SLOT) * STAGE]);                \
-        uint32_t ra_[TM], rb_[TN];                                                                      \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_[i] = sbuf_[sa_base + i * 64u];          \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_[j] = sbuf_[sb_base + j * 64u];          \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_n[i] = sbuf_[sa_base + i * 64u];         \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_n[j] = sbuf_[sb_base + j * 64u];         \
+    }
+#define STREAM_SCALES_USE(ST, GK)                                                                       \
+    {                                                                                                   \
         uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
         if (((ST) + 2u) * 4u > (GK)) {        /* wave-uniform: only a ragged last K-quad */             \
             const uint32_t ksteps_lane = ((GK) + 1u - lhalf) >> 1;   /* K-steps in which this half-wave has a group */ \
@@ -205,12 +210,13 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
             const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
             keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
         }                                                                                               \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = (ra_n[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = (rb_n[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
     }
     uint32_t csel, clv;
     STREAM_PRODUCT(blockIdx.x, csel, clv)
-    STREAM_SCALES(0u, 0u, batch.p[csel].k >> 5, sa, sb)
+    STREAM_SCALES_READ(0u)
+    STREAM_SCALES_USE(0u, batch.p[csel].k >> 5)
 #define STREAM_MF(S, FA, FB, I, J)                                                                      \
     acc[I][J] = mfma_fp4<S>(FA[I], FB[J], acc[I][J], sa[I], sb[J]);                                     \
     asm volatile("" : "+a"(acc[I][J]));                                                                 \
@@ -247,19 +253,16 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
         __builtin_amdgcn_s_waitcnt(WAIT2);                                                              \
         __builtin_amdgcn_s_barrier();                                                                   \
         STREAM_FENCE()                                                                                  \
+        if (PAR == 1) { STREAM_SCALES_READ(SL1) STREAM_FENCE() }                                        \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 0) STREAM_FRAG_A(SL1, 0u, fa0, 0) STREAM_FRAG_B(SL1, 0u, fb0, 0) STREAM_FENCE() \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 1) STREAM_FRAG_B(SL1, 0u, fb0, 1) STREAM_FRAG_B(SL1, 0u, fb0, 2) STREAM_FENCE() \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 2) STREAM_FRAG_B(SL1, 0u, fb0, 3) STREAM_FENCE()            \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 2, 3) STREAM_FRAG_A(SL1, 0u, fa0, 1) STREAM_FENCE()            \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 0) STREAM_FRAG_A(SL1, 0u, fa0, 2) STREAM_FENCE()            \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 1) STREAM_FRAG_A(SL1, 0u, fa0, 3) STREAM_FENCE()            \
-        if (PAR == 1) { STREAM_SCALES(SL1, NEXT_ST, NEXT_GK, sa_n, sb_n) STREAM_FENCE() }               \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 2)                                                          \
         STREAM_MF(2 * PAR + 1, fa1, fb1, 3, 3)                                                          \
-        if (PAR == 1) {                                                                                 \
-            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                        \
-            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                        \
-        }                                                                                               \
+        if (PAR == 1) { STREAM_SCALES_USE(NEXT_ST, NEXT_GK) STREAM_FENCE() }                            \
     }
 
     v16f acc[TM][TN];
@@ -311,7 +314,8 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
 #undef STREAM_FRAG_A
 #undef STREAM_FRAG_B
 #undef STREAM_FENCE
-#undef STREAM_SCALES
+#undef STREAM_SCALES_READ
+#undef STREAM_SCALES_USE
 #undef STREAM_MF
 #undef STREAM_BODY
 }
@@ -410,7 +414,7 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
 
     const uint32_t stages = (k + 127u) >> 7;
     const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);
-    uint32_t sa[TM], sb[TN], sa_n[TM], sb_n[TN];
+    uint32_t sa[TM], sb[TN], ra_n[TM], rb_n[TN];
     uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
 // code load J (0 .. LA-1: A rows, LA .. NL-1: B rows) or the scale tiles (J == NL) of the cursor's stage into ring slot SLOT
@@ -448,20 +452,24 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
         READ_FRAG(SLOT, 0u, FA, FB, rn_ == 0 ? TN : (rn_ <= TN ? rn_ - 1 : rn_))                        \
     }
 #define FENCE() __builtin_amdgcn_sched_barrier(0);
-#define READ_SCALES(SLOT, ST, XA, XB)                                                                   \
+// scale dwords of a K-quad: read right behind the barrier, used behind the pair's last matrix-core instruction (see the
+// 256 x 256 kernel)
+#define READ_SCALES(SLOT)                                                                               \
     {                                                                                                   \
         const uint32_t* sbuf_ = reinterpret_cast<const uint32_t*>(&lds[(SLOT) * STAGE]);                \
-        uint32_t ra_[TM], rb_[TN];                                                                      \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_[i] = sbuf_[sa_base + i * 64u];          \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_[j] = sbuf_[sb_base + j * 64u];          \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_n[i] = sbuf_[sa_base + i * 64u];         \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_n[j] = sbuf_[sb_base + j * 64u];         \
+    }
+#define USE_SCALES(ST)                                                                                  \
+    {                                                                                                   \
         uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
         if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */             \
             const uint32_t done_ = (ST) * 2u;                                                           \
             const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
             keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
         }                                                                                               \
-        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) XA[i] = (ra_[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
-        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) XB[j] = (rb_[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = (ra_n[i] & keep_) | (0x7F7F7F7Fu & ~keep_); \
+        _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = (rb_n[j] & keep_) | (0x7F7F7F7Fu & ~keep_); \
     }
 
     constexpr uint32_t KEEP2 = 2u * NL + 1u;           // loads of one even and one odd stage stay in flight
@@ -479,7 +487,8 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
     for (int r = 0; r < R; ++r) READ_FRAG(0u, 0u, fa0, fb0, r)
     static_assert(XR >= 0 && XR <= R / 2 + 1, "the next stage's fragment reads must fit behind the barrier");
     const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
-    READ_SCALES(0u, 0u, sa, sb)
+    READ_SCALES(0u)
+    USE_SCALES(0u)
 
 // one stage: PAR = its parity, slots SL = its own, SL1 = the next stage's, SLI = the one being filled; NEXT_ST: the
 // local index of the stage after the next (odd stages read its K-quad's scales)
@@ -505,18 +514,15 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
                 __builtin_amdgcn_s_waitcnt(WAIT2);                                                      \
                 __builtin_amdgcn_s_barrier();                                                           \
                 FENCE()                                                                                 \
+                if (PAR == 1) { READ_SCALES(SL1) FENCE() }                                              \
             }                                                                                           \
             if (idx >= P) {         /* two reads per slot while more reads than slots are left, then one */ \
                 _Pragma("unroll") for (int r_ = 0; r_ < R; ++r_)                                        \
                     if (P + (r_ < 2 * XR ? r_ / 2 : r_ - XR) == idx) READ_FRAG_NEXT(SL1, fa0, fb0, r_)  \
                 FENCE()                                                                                 \
             }                                                                                           \
-            if (PAR == 1 && idx == 2 * NM - (POST > 2 ? 3 : 1)) { READ_SCALES(SL1, NEXT_ST, sa_n, sb_n) FENCE() } \
         }                                                                                               \
-        if (PAR == 1) {                                                                                 \
-            _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) sa[i] = sa_n[i];                        \
-            _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) sb[j] = sb_n[j];                        \
-        }                                                                                               \
+        if (PAR == 1) { USE_SCALES(NEXT_ST) FENCE() }                                                   \
     }
 
     v16f acc[TM][TN];
@@ -556,6 +562,7 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
 #undef READ_FRAG_NEXT
 #undef FENCE
 #undef READ_SCALES
+#undef USE_SCALES
 #undef STAGE_BODY
 }
 
