@@ -305,7 +305,11 @@ __device__ __forceinline__ void transposed_store_tile(const uint4* s_codes, cons
 // Block tile: 8 groups (256 source rows, one K-quad of the output) x 128 source columns; wave w owns
 // groups 2w, 2w+1; lane l owns columns 2l, 2l+1.  Blocks are numbered K-quad first: the blocks that
 // run at the same time then write neighbouring 128-byte lines of the same output rows (measured 10 %
-// faster than column-tile first, where every block's lines lie a whole output row apart).
+// faster than column-tile first, where every block's lines lie a whole output row apart).  The callers
+// rotate the column tile by the K-quad (transposed_column_tile): with a dense source whose row pitch is a
+// multiple of a few KB, the blocks in flight would otherwise all read the same 4 KB-wide stretch of
+// columns of every row, which the memory channels serve unevenly (measured: 5-9 % slower; a source
+// with 128 bytes of padding per row does not show it).
 // bx, by: the block's K-quad and column tile; s_codes (16 KB), s_scales (1 KB), s_mask (4 KB): the block's LDS
 template <int MODE, bool MASK>
 __device__ __forceinline__ void quant_transposed_tile(const uint16_t* __restrict__ src,
@@ -366,6 +370,9 @@ __device__ __forceinline__ void quant_transposed_tile(const uint16_t* __restrict
     transposed_store_tile<MASK>(s_codes, s_scales, s_mask, col0, grp0, rows, gk, k, codes, scales, mask);
 }
 
+// Column tile of the block with K-quad bx and nominal column tile by, of n_ct column tiles (a bijection for every bx).
+__device__ __forceinline__ uint32_t transposed_column_tile(uint32_t bx, uint32_t by, uint32_t n_ct) { return (by + bx) % n_ct; }
+
 template <int MODE, bool MASK>
 __global__ void __launch_bounds__(256, MODE == kBwdSr ? 3 : 4)
 quant_transposed_kernel(const uint16_t* __restrict__ src,
@@ -374,7 +381,8 @@ quant_transposed_kernel(const uint16_t* __restrict__ src,
     __shared__ uint4 s_codes[128 * 8];
     __shared__ uint8_t s_scales[128 * 8];
     __shared__ uint32_t s_mask[128 * 8];
-    quant_transposed_tile<MODE, MASK>(src, rows, k, ldx, codes, scales, mask, p, blockIdx.x, blockIdx.y, s_codes, s_scales, s_mask);
+    quant_transposed_tile<MODE, MASK>(src, rows, k, ldx, codes, scales, mask, p, blockIdx.x,
+                                      transposed_column_tile(blockIdx.x, blockIdx.y, gridDim.y), s_codes, s_scales, s_mask);
 }
 
 // The same tile for Hadamard blocks of NB = 2, 4 or 8 groups.  The groups of a block are whole source
@@ -392,7 +400,7 @@ quant_transposed_block_kernel(const uint16_t* __restrict__ src, uint32_t rows, u
     __shared__ uint32_t s_mask[128 * 8];
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
     const uint32_t gk = k >> 5;
-    const uint32_t col0 = blockIdx.y * 128u;
+    const uint32_t col0 = transposed_column_tile(blockIdx.x, blockIdx.y, gridDim.y) * 128u;
     const uint32_t grp0 = blockIdx.x * 8u;
     const uint32_t col = col0 + 2u * lane;
     const uint32_t src_rows = (k - grp0 * 32u) < 256u ? (k - grp0 * 32u) : 256u;
@@ -677,7 +685,8 @@ bwd_operands_kernel(const uint16_t* __restrict__ dy, uint32_t t_rows, uint32_t t
         uint4* s_codes = reinterpret_cast<uint4*>(smem);
         uint32_t* s_mask = reinterpret_cast<uint32_t*>(smem + 128 * 8 * 16);
         uint8_t* s_scales = smem + 128 * 8 * 20;
-        quant_transposed_tile<MODE, false>(dy, t_rows, t_k, t_ldx, t_codes, t_scales, nullptr, t_p, bx, by, s_codes, s_scales, s_mask);
+        quant_transposed_tile<MODE, false>(dy, t_rows, t_k, t_ldx, t_codes, t_scales, nullptr, t_p, bx,
+                                           transposed_column_tile(bx, by, (t_rows + 127u) >> 7), s_codes, s_scales, s_mask);
     }
 }
 
