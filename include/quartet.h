@@ -236,8 +236,8 @@ int quartet_mxfp4_gemm_grad(const uint8_t *a_codes, const uint8_t *a_scales,
  * are read on the host during the call; every pointer inside them is a device pointer.  The results are bit-identical
  * to two calls of quartet_mxfp4_gemm_grad (first, then second).  The compute units go through the first product's tiles,
  * then the second's, without draining in between: one ramp-up and one drain, and the second product fills the compute
- * units the first leaves idle in its last round.  (When either product alone would run on tiles smaller than 256 x 256,
- * the two are simply launched one after the other.)  The two results must not overlap.  Errors as
+ * units the first leaves idle in its last round.  One tile shape serves both products (chosen for the pair, or the one
+ * quartet_debug_set_gemm_plan forces).  The two results must not overlap.  Errors as
  * quartet_mxfp4_gemm_grad, checked for both products before anything is launched.
  */
 typedef struct quartet_gemm_grad_args {

@@ -329,11 +329,7 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
 // stage's end, and behind the barrier the next stage's first fragments (and, on odd stages, the next K-quad's scales).
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
 __global__ void __launch_bounds__(256)
-gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t* __restrict__ a_scales,
-                              const uint8_t* __restrict__ b_codes, const uint8_t* __restrict__ b_scales,
-                              uint32_t m, uint32_t n, uint32_t k, float alpha, void* __restrict__ d, uint32_t ldd,
-                              const uint32_t* __restrict__ mask, uint32_t tiles_m, uint32_t tiles_n, uint32_t band_height, uint32_t nb,
-                              uint64_t* __restrict__ clock_counters) {
+gemm_mxfp4_stream_tile_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uint64_t* __restrict__ clock_counters) {
     constexpr uint32_t BM = 64 * TM, BN = 64 * TN;
     static_assert(BM % 128 == 0 && BN % 128 == 0, "a wave's four scale tiles must belong to one operand");
     constexpr uint32_t CODES = (BM + BN) * 4;            // 16-byte chunks of codes per stage
@@ -361,59 +357,71 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
-    const uint32_t total_tiles = tiles_m * tiles_n, G = gridDim.x;
-    const uint32_t per = total_tiles >> 3, rem = total_tiles & 7u;
-    const uint32_t GM = band_height;
+    const uint32_t G = gridDim.x, first_tiles = batch.p[0].total_tiles;
     const uint32_t wm0 = (wave >> 1) * (TM * 32u), wn0 = (wave & 1u) * (TN * 32u);
-    const uint32_t kb = k >> 1, gk = k >> 5, kq = (k + 255u) >> 8;
     // scale tiles 4 wave .. 4 wave + 3 of [A's | B's] are this wave's to fetch (waves past the last tile fetch nothing real:
     // their load is out of range and delivers zeros, which keeps every wave's count of loads the same)
     const bool has_scales = 4u * wave < NT, scales_of_a = 4u * wave < BM / 32u;
     const uint32_t stile0 = scales_of_a ? 4u * wave : 4u * wave - BM / 32u;
 
-#define TILE_ORIGIN(V, M0, N0)                                                                          \
+// product SEL and the tile's number in it for virtual block id V; tile origin of tile number V of product Q (as in the
+// 256 x 256 kernel)
+#define PRODUCT_OF(V, SEL, LOCAL)                                                                       \
     {                                                                                                   \
-        const uint32_t v_ = (V);                                                                        \
-        if (v_ < total_tiles) {                                                                         \
+        LOCAL = (V);                                                                                    \
+        SEL = 0u;                                                                                       \
+        if (LOCAL >= first_tiles) { LOCAL -= first_tiles; SEL = 1u; }                                   \
+    }
+#define TILE_ORIGIN(Q, V, M0, N0)                                                                       \
+    {                                                                                                   \
+        const uint32_t v_ = (V), tt_ = (Q).total_tiles;                                                 \
+        if (v_ < tt_) {                                                                                 \
+            const uint32_t per_ = tt_ >> 3, rem_ = tt_ & 7u, GM_ = (Q).band_height;                     \
+            const uint32_t tiles_m_ = (Q).tiles_m, tiles_n_ = (Q).tiles_n;                              \
             const uint32_t xcd_ = v_ & 7u;                                                              \
-            const uint32_t tile_ = xcd_ * per + (xcd_ < rem ? xcd_ : rem) + (v_ >> 3);                  \
-            const uint32_t band_ = tile_ / (GM * tiles_n);                                              \
-            const uint32_t band_rows_ = (tiles_m - band_ * GM) < GM ? (tiles_m - band_ * GM) : GM;      \
-            const uint32_t in_band_ = tile_ - band_ * GM * tiles_n;                                     \
-            M0 = (band_ * GM + in_band_ % band_rows_) * BM;                                             \
+            const uint32_t tile_ = xcd_ * per_ + (xcd_ < rem_ ? xcd_ : rem_) + (v_ >> 3);               \
+            const uint32_t band_ = tile_ / (GM_ * tiles_n_);                                            \
+            const uint32_t band_rows_ = (tiles_m_ - band_ * GM_) < GM_ ? (tiles_m_ - band_ * GM_) : GM_; \
+            const uint32_t in_band_ = tile_ - band_ * GM_ * tiles_n_;                                   \
+            M0 = (band_ * GM_ + in_band_ % band_rows_) * BM;                                            \
             N0 = (in_band_ / band_rows_) * BN;                                                          \
         } else {                                                                                        \
-            M0 = m; N0 = n;                                                                             \
+            M0 = (Q).m; N0 = (Q).n;                                                                     \
         }                                                                                               \
     }
     uint32_t iv = blockIdx.x, ist = 0u;                  // issue cursor: the tile and stage the next loads belong to
     v4i_t res_a, res_b, res_s;
+    uint32_t kb, istages, S2i, goff, gstep, soff;        // of the cursor's product
+    const uint32_t drow = wave * 16u + (lane >> 2);
+    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
 #define ISSUE_SETUP()                                                                                   \
     {                                                                                                   \
-        uint32_t m0_, n0_;                                                                              \
-        TILE_ORIGIN(iv, m0_, n0_)                                                                       \
-        const uint32_t rows_a_ = (m - m0_) < BM ? (m - m0_) : BM, rows_b_ = (n - n0_) < BN ? (n - n0_) : BN; \
-        res_a = make_rsrc_words(a_codes + (size_t)m0_ * kb, rows_a_ * kb);                              \
-        res_b = make_rsrc_words(b_codes + (size_t)n0_ * kb, rows_b_ * kb);                              \
+        uint32_t sel_, lv_, m0_, n0_;                                                                   \
+        PRODUCT_OF(iv, sel_, lv_)                                                                       \
+        const GemmProblem& q_ = batch.p[sel_];                                                          \
+        TILE_ORIGIN(q_, lv_, m0_, n0_)                                                                  \
+        const uint32_t k_ = q_.k, kq_ = (k_ + 255u) >> 8;                                               \
+        kb = k_ >> 1;                                                                                   \
+        istages = (k_ + 127u) >> 7;                                                                     \
+        S2i = istages < 2u ? 2u : ((istages + 1u) & ~1u);                                               \
+        goff = drow * kb + dcol * 16u;          /* + j*64*kb, + stage*64 */                             \
+        gstep = 64u * kb;                                                                               \
+        soff = ((stile0 + (lane >> 4)) * kq_) * 256u + (lane & 15u) * 16u;   /* + quad*256 */           \
+        const uint32_t rows_a_ = (q_.m - m0_) < BM ? (q_.m - m0_) : BM, rows_b_ = (q_.n - n0_) < BN ? (q_.n - n0_) : BN; \
+        res_a = make_rsrc_words(q_.a_codes + (size_t)m0_ * kb, rows_a_ * kb);                           \
+        res_b = make_rsrc_words(q_.b_codes + (size_t)n0_ * kb, rows_b_ * kb);                           \
         const uint32_t srow0_ = scales_of_a ? m0_ : n0_, srows_ = scales_of_a ? rows_a_ : rows_b_;      \
-        res_s = make_rsrc_words((scales_of_a ? a_scales : b_scales) + (size_t)(srow0_ >> 5) * kq * 256u, \
-                                has_scales ? ((srows_ + 31u) >> 5) * kq * 256u : 0u);                   \
+        res_s = make_rsrc_words((scales_of_a ? q_.a_scales : q_.b_scales) + (size_t)(srow0_ >> 5) * kq_ * 256u, \
+                                has_scales ? ((srows_ + 31u) >> 5) * kq_ * 256u : 0u);                  \
     }
     ISSUE_SETUP()
 
-    const uint32_t drow = wave * 16u + (lane >> 2);
-    const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
-    const uint32_t goff = drow * kb + dcol * 16u;          // + j*64*kb, + stage*64
-    const uint32_t gstep = 64u * kb;
-    const uint32_t soff = ((stile0 + (lane >> 4)) * kq) * 256u + (lane & 15u) * 16u;   // + quad*256
     const uint32_t lds0 = (uint32_t)(size_t)(lds_ptr_t)&lds[0];
     const uint32_t swz = (lrow >> 2) & 3u;
     const uint32_t fa_base = (wm0 + lrow) * 4u, fb_base = BM * 4u + (wn0 + lrow) * 4u;
     const uint32_t sa_base = CODES * 4u + (wm0 >> 5) * 64u + lane;             // dword index in a stage
     const uint32_t sb_base = CODES * 4u + (BM / 32u) * 64u + (wn0 >> 5) * 64u + lane;
 
-    const uint32_t stages = (k + 127u) >> 7;
-    const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);
     uint32_t sa[TM], sb[TN], ra_n[TM], rb_n[TN];
     uint4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 
@@ -426,13 +434,13 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
             const uint32_t jj_ = (uint32_t)(J) < LA ? (uint32_t)(J) : (uint32_t)(J) - LA;               \
             lds_direct_load16((uint32_t)(J) < LA ? res_a : res_b, base_ + jj_ * gstep, slot_ + (uint32_t)(J) * 4096u); \
         } else {                                                                                        \
-            lds_direct_load16(res_s, (ist < stages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+            lds_direct_load16(res_s, (ist < istages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
         }                                                                                               \
     }
 #define ISSUE_ADVANCE()                                                                                 \
     {                                                                                                   \
         ++ist;                                                                                          \
-        if (ist == S2) {                                                                                \
+        if (ist == S2i) {                                                                               \
             ist = 0u;                                                                                   \
             iv += G;                                                                                    \
             ISSUE_SETUP()                                                                               \
@@ -460,10 +468,11 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
         _Pragma("unroll") for (uint32_t i = 0; i < TM; ++i) ra_n[i] = sbuf_[sa_base + i * 64u];         \
         _Pragma("unroll") for (uint32_t j = 0; j < TN; ++j) rb_n[j] = sbuf_[sb_base + j * 64u];         \
     }
-#define USE_SCALES(ST)                                                                                  \
+#define USE_SCALES(ST, GK)                                                                              \
     {                                                                                                   \
         uint32_t keep_ = 0xFFFFFFFFu;                                                                   \
-        if (((ST) + 2u) * 4u > gk) {          /* wave-uniform: only a ragged last K-quad */             \
+        if (((ST) + 2u) * 4u > (GK)) {        /* wave-uniform: only a ragged last K-quad */             \
+            const uint32_t ksteps_lane = ((GK) + 1u - lhalf) >> 1;   /* K-steps in which this half-wave has a group */ \
             const uint32_t done_ = (ST) * 2u;                                                           \
             const uint32_t nv_ = ksteps_lane > done_ ? (ksteps_lane - done_ < 4u ? ksteps_lane - done_ : 4u) : 0u; \
             keep_ = nv_ >= 4u ? 0xFFFFFFFFu : ((1u << (8u * nv_)) - 1u);                                \
@@ -486,13 +495,14 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
 #pragma unroll
     for (int r = 0; r < R; ++r) READ_FRAG(0u, 0u, fa0, fb0, r)
     static_assert(XR >= 0 && XR <= R / 2 + 1, "the next stage's fragment reads must fit behind the barrier");
-    const uint32_t ksteps_lane = (gk + 1u - lhalf) >> 1;   // K-steps in which this half-wave has a group
+    uint32_t csel, clv;
+    PRODUCT_OF(blockIdx.x, csel, clv)
     READ_SCALES(0u)
-    USE_SCALES(0u)
+    USE_SCALES(0u, batch.p[csel].k >> 5)
 
 // one stage: PAR = its parity, slots SL = its own, SL1 = the next stage's, SLI = the one being filled; NEXT_ST: the
 // local index of the stage after the next (odd stages read its K-quad's scales)
-#define STAGE_BODY(PAR, SL, SL1, SLI, NEXT_ST)                                                          \
+#define STAGE_BODY(PAR, SL, SL1, SLI, NEXT_ST, NEXT_GK)                                                 \
     {                                                                                                   \
         _Pragma("unroll") for (int idx = 0; idx < 2 * NM; ++idx) {                                      \
             const int ij_ = idx % NM, I_ = ij_ / TN, J_ = ij_ % TN;                                     \
@@ -522,13 +532,18 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
                 FENCE()                                                                                 \
             }                                                                                           \
         }                                                                                               \
-        if (PAR == 1) { USE_SCALES(NEXT_ST) FENCE() }                                                   \
+        if (PAR == 1) { USE_SCALES(NEXT_ST, NEXT_GK) FENCE() }                                          \
     }
 
     v16f acc[TM][TN];
     float* wbuf = reinterpret_cast<float*>(&lds[kRing * STAGE]) + wave * (TN * 256u);
     uint32_t g = 0u;                                       // stages done by this block (ring slot = g % kRing)
     for (uint32_t cv = blockIdx.x; cv < total_tiles; cv += G) {
+        PRODUCT_OF(cv, csel, clv)
+        const uint32_t ck = batch.p[csel].k, gk = ck >> 5, stages = (ck + 127u) >> 7;
+        const uint32_t S2 = stages < 2u ? 2u : ((stages + 1u) & ~1u);
+        // the tile's last pair of stages reads the first scales of the block's next tile, which may belong to the other product
+        const uint32_t gk_after = (cv + G >= first_tiles && cv + G < total_tiles) ? (batch.p[1].k >> 5) : gk;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -538,15 +553,19 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
         for (uint32_t st = 0u; st < S2; st += 2u, g += 2u) {
             const uint32_t sl = g & 3u;                    // g is even: sl is 0 or 2
             const uint32_t next_st = st + 2u < S2 ? st + 2u : 0u;
-            STAGE_BODY(0, sl, sl + 1u, sl ^ 3u, 0u)
-            STAGE_BODY(1, sl + 1u, sl ^ 2u, sl, next_st)
+            const uint32_t next_gk = st + 2u < S2 ? gk : gk_after;
+            STAGE_BODY(0, sl, sl + 1u, sl ^ 3u, 0u, 0u)
+            STAGE_BODY(1, sl + 1u, sl ^ 2u, sl, next_st, next_gk)
         }
+        const GemmProblem& q = batch.p[csel];
         uint32_t m0, n0;
-        TILE_ORIGIN(cv, m0, n0)
+        TILE_ORIGIN(q, clv, m0, n0)
+        const uint32_t m = q.m, n = q.n, ldd = q.ldd;
+        const uint32_t* __restrict__ mask = q.mask;
         const uint32_t row_base = m0 + wm0, col_base = n0 + wn0;
         const bool full = (ldd & 3u) == 0u && row_base + TM * 32u <= m && col_base + TN * 32u <= n && (!FUSED || mask != nullptr);
-        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
-        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, d, ldd, mask, alpha, row_base, col_base, m, n, lane, nb);
+        if (full) store_tile_rows8<TM, TN, OUT_BF16, FUSED, true>(acc, wbuf, q.d, ldd, mask, q.alpha, row_base, col_base, m, n, lane, nb);
+        else store_tile_rows8<TM, TN, OUT_BF16, FUSED, false>(acc, wbuf, q.d, ldd, mask, q.alpha, row_base, col_base, m, n, lane, nb);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the stages issued past the last tile (zero-filled) have landed before the LDS is given back
     if (clock_counters && tid == 0) {
@@ -554,6 +573,7 @@ gemm_mxfp4_stream_tile_kernel(const uint8_t* __restrict__ a_codes, const uint8_t
         atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters), (unsigned long long)(t1 - clk_t0));
         atomicAdd(reinterpret_cast<unsigned long long*>(clock_counters) + 1, (unsigned long long)(w1 - clk_w0));
     }
+#undef PRODUCT_OF
 #undef TILE_ORIGIN
 #undef ISSUE_SETUP
 #undef ISSUE
@@ -578,16 +598,17 @@ static int stream_blocks() {
     return cus;
 }
 
-// tile grid and band height of one product for the 256 x 256 streaming kernel
+// tile grid and band height of one product for block tiles of bm x bn
 static GemmProblem make_problem(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes, const uint8_t* b_scales,
-                                int64_t m, int64_t n, int64_t k, float alpha, void* d, int64_t ldd, const uint32_t* mask) {
+                                int64_t m, int64_t n, int64_t k, float alpha, void* d, int64_t ldd, const uint32_t* mask,
+                                int64_t bm, int64_t bn) {
     GemmProblem q;
     q.a_codes = a_codes; q.a_scales = a_scales; q.b_codes = b_codes; q.b_scales = b_scales;
     q.d = d; q.mask = mask;
     q.m = (uint32_t)m; q.n = (uint32_t)n; q.k = (uint32_t)k; q.ldd = (uint32_t)ldd;
     q.alpha = alpha;
-    q.tiles_m = (uint32_t)((m + 255) / 256); q.tiles_n = (uint32_t)((n + 255) / 256);
-    q.band_height = (q.tiles_n >= 40u && (q.tiles_m & 1u) == 0u) ? 2u : 4u;
+    q.tiles_m = (uint32_t)((m + bm - 1) / bm); q.tiles_n = (uint32_t)((n + bn - 1) / bn);
+    q.band_height = (bm == 256 && bn == 256 && q.tiles_n >= 40u && (q.tiles_m & 1u) == 0u) ? 2u : 4u;
     if (g_forced_band > 0) q.band_height = (uint32_t)g_forced_band;
     q.total_tiles = q.tiles_m * q.tiles_n;
     return q;
@@ -605,23 +626,26 @@ static void launch_stream_t(const uint8_t* a_codes, const uint8_t* a_scales, con
                             const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                             int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
     GemmBatch batch;
-    batch.p[0] = make_problem(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask);
+    batch.p[0] = make_problem(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, 256, 256);
     batch.p[1] = GemmProblem{};      // no second product
     launch_stream_batch_t<OUT_BF16, FUSED>(batch, nb, st);
+}
+
+template <int TM, int TN, bool OUT_BF16, bool FUSED>
+static void launch_stream_tile_batch_t(const GemmBatch& batch, uint32_t nb, hipStream_t st) {
+    const uint32_t total = batch.p[0].total_tiles + batch.p[1].total_tiles, cus = (uint32_t)stream_blocks();
+    hipLaunchKernelGGL((gemm_mxfp4_stream_tile_kernel<TM, TN, OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st,
+                       batch, total, nb, g_clock_counters);
 }
 
 template <int TM, int TN, bool OUT_BF16, bool FUSED>
 static void launch_stream_tile_t(const uint8_t* a_codes, const uint8_t* a_scales, const uint8_t* b_codes,
                                  const uint8_t* b_scales, int64_t m, int64_t n, int64_t k, float alpha, void* d,
                                  int64_t ldd, const uint32_t* mask, uint32_t nb, hipStream_t st) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    uint32_t tiles_m = (uint32_t)((m + BM - 1) / BM), tiles_n = (uint32_t)((n + BN - 1) / BN);
-    uint32_t gm = (BM == 256 && BN == 256 && tiles_n >= 40u && (tiles_m & 1u) == 0u) ? 2u : 4u;
-    if (g_forced_band > 0) gm = (uint32_t)g_forced_band;
-    const uint32_t total = tiles_m * tiles_n, cus = (uint32_t)stream_blocks();
-    hipLaunchKernelGGL((gemm_mxfp4_stream_tile_kernel<TM, TN, OUT_BF16, FUSED>), dim3(total < cus ? total : cus), dim3(256), 0, st,
-                       a_codes, a_scales, b_codes, b_scales, (uint32_t)m, (uint32_t)n, (uint32_t)k, alpha, d, (uint32_t)ldd, mask,
-                       tiles_m, tiles_n, gm, nb, g_clock_counters);
+    GemmBatch batch;
+    batch.p[0] = make_problem(a_codes, a_scales, b_codes, b_scales, m, n, k, alpha, d, ldd, mask, 64 * TM, 64 * TN);
+    batch.p[1] = GemmProblem{};      // no second product
+    launch_stream_tile_batch_t<TM, TN, OUT_BF16, FUSED>(batch, nb, st);
 }
 
 // Variants: 0 = 256x256 tiles (hand-scheduled stage), 1 = 128x256 tiles, 2 = 128x128 tiles (stage generated from the
@@ -673,22 +697,50 @@ hipError_t launch_gemm(const uint8_t* a_codes, const uint8_t* a_scales, const ui
     return hipGetLastError();
 }
 
-// Two gradient products in one launch of the 256 x 256 streaming kernel (both with the fused epilogue, results of one type).
-// When either product would not take that tile shape on its own, they are launched one after the other instead.
+// Two gradient products in one launch (both with the fused epilogue, results of one type).  One tile shape serves both: the
+// one with the smallest estimated time of the busiest block, which walks the virtual tile ids b, b + G, ... over the first
+// product's tiles and then the second's; a tile costs its inner dimension plus the epilogue (about 1100 elements' worth of
+// stages), times the shape's area, over the shape's efficiency (pick_variant's figures).
 hipError_t launch_gemm_grad_pair(const GemmArgs& g0, const GemmArgs& g1, int d_bf16, uint32_t nb, hipStream_t st) {
     const bool empty0 = g0.m == 0 || g0.n == 0, empty1 = g1.m == 0 || g1.n == 0;
-    if (empty0 || empty1 || pick_variant(g0.m, g0.n, 1, nb) != 0 || pick_variant(g1.m, g1.n, 1, nb) != 0) {
+    if (empty0 || empty1) {
         hipError_t e = launch_gemm(g0.a_codes, g0.a_scales, g0.b_codes, g0.b_scales, g0.m, g0.n, g0.k, g0.alpha, g0.d, d_bf16, g0.ldd,
                                    1, g0.mask, nb, st);
         if (e != hipSuccess) return e;
         return launch_gemm(g1.a_codes, g1.a_scales, g1.b_codes, g1.b_scales, g1.m, g1.n, g1.k, g1.alpha, g1.d, d_bf16, g1.ldd, 1,
                            g1.mask, nb, st);
     }
+    const int64_t bm[3] = {256, 128, 128}, bn[3] = {256, 256, 128};
+    int variant = g_forced_variant;
+    if (variant < 0) {
+        const double cost_per_area[3] = {1.0, 0.5 / 0.84, 0.25 / 0.54};
+        const int64_t cus = stream_blocks();
+        double best = -1.0;
+        for (int v = 0; v < 3; ++v) {
+            const int64_t t0 = ((g0.m + bm[v] - 1) / bm[v]) * ((g0.n + bn[v] - 1) / bn[v]);
+            const int64_t t1 = ((g1.m + bm[v] - 1) / bm[v]) * ((g1.n + bn[v] - 1) / bn[v]);
+            const int64_t blocks = t0 + t1 < cus ? t0 + t1 : cus;
+            double busiest = 0.0;
+            for (int64_t b = 0; b < blocks; ++b) {
+                const int64_t n0 = t0 > b ? (t0 - b + blocks - 1) / blocks : 0;
+                const int64_t upto = t0 + t1 - 1, before = t0 - 1;     // ids congruent to b up to these, inclusive
+                const int64_t n1 = (upto >= b ? (upto - b) / blocks + 1 : 0) - (before >= b ? (before - b) / blocks + 1 : 0);
+                const double load = (double)n0 * (double)(g0.k + 1100) + (double)n1 * (double)(g1.k + 1100);
+                if (load > busiest) busiest = load;
+            }
+            const double t = busiest * cost_per_area[v];
+            if (best < 0.0 || t < best) { best = t; variant = v; }
+        }
+    }
+    if (nb >= 4u && variant == 2) variant = 1;   // a block of 128 columns needs the 128-column wave tile
     GemmBatch batch;
-    batch.p[0] = make_problem(g0.a_codes, g0.a_scales, g0.b_codes, g0.b_scales, g0.m, g0.n, g0.k, g0.alpha, g0.d, g0.ldd, g0.mask);
-    batch.p[1] = make_problem(g1.a_codes, g1.a_scales, g1.b_codes, g1.b_scales, g1.m, g1.n, g1.k, g1.alpha, g1.d, g1.ldd, g1.mask);
-    if (d_bf16) launch_stream_batch_t<true, true>(batch, nb, st);
-    else launch_stream_batch_t<false, true>(batch, nb, st);
+    batch.p[0] = make_problem(g0.a_codes, g0.a_scales, g0.b_codes, g0.b_scales, g0.m, g0.n, g0.k, g0.alpha, g0.d, g0.ldd, g0.mask,
+                              bm[variant], bn[variant]);
+    batch.p[1] = make_problem(g1.a_codes, g1.a_scales, g1.b_codes, g1.b_scales, g1.m, g1.n, g1.k, g1.alpha, g1.d, g1.ldd, g1.mask,
+                              bm[variant], bn[variant]);
+    if (variant == 1) { if (d_bf16) launch_stream_tile_batch_t<2, 4, true, true>(batch, nb, st); else launch_stream_tile_batch_t<2, 4, false, true>(batch, nb, st); }
+    else if (variant == 2) { if (d_bf16) launch_stream_tile_batch_t<2, 2, true, true>(batch, nb, st); else launch_stream_tile_batch_t<2, 2, false, true>(batch, nb, st); }
+    else { if (d_bf16) launch_stream_batch_t<true, true>(batch, nb, st); else launch_stream_batch_t<false, true>(batch, nb, st); }
     return hipGetLastError();
 }
 
