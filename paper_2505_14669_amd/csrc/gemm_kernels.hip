@@ -14,7 +14,8 @@
 // scale-rearrangement step does not exist here.
 //
 // Kernels: gemm_mxfp4_stream_kernel (256 x 256 tiles) and gemm_mxfp4_stream_tile_kernel (128 x 256 and 128 x 128 tiles
-// for small problems): one block per compute unit streams its tiles through a ring of LDS stages.
+// for small problems): one block per compute unit streams its tiles through a ring of LDS stages.  Both work
+// through a batch of one or two products per launch (GemmBatch).
 #include "gemm_common.h"
 #include "launchers.h"
 
