@@ -257,6 +257,33 @@ def test_gemm_grad_pair_matches_two_calls(G, shapes, gemm_variant):
     assert np.array_equal(got_bf[0], synth.f32_to_bf16(got[1])) and np.array_equal(got_bf[1], synth.f32_to_bf16(got[0]))
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("band", [1, 3, 5, 64])
+def test_gemm_tile_order_covers_every_tile_for_any_band_height(G, variant, band):
+    # the XCD-aware tile order (bands of `band` tile rows per XCD) is a tuning knob of the C ABI: whatever its value, every
+    # tile must be computed exactly once -- the result (prefilled with NaN) is bit-identical to the default order's, for one
+    # product and for two in one launch
+    rng = np.random.default_rng(99)
+    def operands(m, n, k):
+        return (rng.integers(0, 256, size=(m, k // 2), dtype=np.uint8), rng.integers(117, 137, size=(m, k // 32), dtype=np.uint8),
+                rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8), rng.integers(117, 137, size=(n, k // 32), dtype=np.uint8))
+    one = operands(1300, 1100, 64)
+    first = operands(2100, 800, 96) + (rng.integers(0, 2 ** 32, size=(2100, 25), dtype=np.uint32), 1.5)
+    second = operands(700, 1568, 32) + (None, 0.75)
+    try:
+        G.q.check(G.q.quartet_debug_set_gemm_plan(variant, 0))
+        want_one = G.gemm(*one)
+        want_pair = G.gemm_grad_pair(first, second)
+        G.q.check(G.q.quartet_debug_set_gemm_plan(variant, band))
+        got_one = G.gemm(*one)
+        got_pair = G.gemm_grad_pair(first, second)
+    finally:
+        G.q.check(G.q.quartet_debug_set_gemm_plan(-1, 0))
+    assert np.isfinite(want_one).all() and np.array_equal(got_one.view(np.uint32), want_one.view(np.uint32))
+    for g, w in zip(got_pair, want_pair):
+        assert np.isfinite(w).all() and np.array_equal(g.view(np.uint32), w.view(np.uint32))
+
+
 @pytest.mark.parametrize("shape", [(1, 32), (6, 96), (77, 160), (256, 512)])
 def test_grad_epilogue(G, shape):
     rng = np.random.default_rng(shape[0])
