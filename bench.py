@@ -404,9 +404,9 @@ def main():
     # per GEMM shape, from the same event pairs (launch order inside a step: forward, dW, dX of each layer): the rate,
     # and the share of the HBM peak that the minimum traffic (operands once, result once) comes to -- products with a
     # short inner dimension and an fp32 result are bound by the result's stores, not by the matrix cores
-    # (Hadamard block 32: the backward pass runs its two products, dW and dX, in one launch: two records per layer)
+    # (Hadamard blocks up to 128: the backward pass runs its two products, dW and dX, in one launch: two records per layer)
     by_shape = {}
-    per_layer = 2 if args.hadamard_block == 32 else 3
+    per_layer = 2 if args.hadamard_block <= 128 else 3
     if len(gemm_ms) == per_layer * len(layers) * args.steps:
         for idx, m_s in enumerate(gemm_ms):
             l, which = layers[(idx // per_layer) % len(layers)], idx % per_layer

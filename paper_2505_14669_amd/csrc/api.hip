@@ -450,28 +450,36 @@ int quartet_mxfp4_gemm_grad_block(const uint8_t* a_codes, const uint8_t* a_scale
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
 }
 
-static int check_gemm_grad_args(const quartet_gemm_grad_args* g, int d_dtype) {
+static int check_gemm_grad_args(const quartet_gemm_grad_args* g, int d_dtype, int hadamard_block) {
     if (!g) return QUARTET_EINVAL;
     int rc = check_gemm_args(g->a_codes, g->a_scales, g->b_codes, g->b_scales, g->m, g->n, g->k, g->d, d_dtype, g->ldd);
     if (rc) return rc;
-    if ((g->n % 32) != 0) return QUARTET_EINVAL;
+    if ((g->n % hadamard_block) != 0) return QUARTET_EINVAL;
     if (g->mask && (reinterpret_cast<uintptr_t>(g->mask) & 3u)) return QUARTET_EINVAL;
     return QUARTET_OK;
 }
 
-int quartet_mxfp4_gemm_grad_pair(const quartet_gemm_grad_args* first, const quartet_gemm_grad_args* second, int d_dtype,
-                                 void* stream) {
-    int rc = check_gemm_grad_args(first, d_dtype);
+// both products with Hadamard blocks of hadamard_block = 32, 64 or 128 columns
+static int gemm_grad_pair_block(const quartet_gemm_grad_args* first, const quartet_gemm_grad_args* second, int hadamard_block,
+                                int d_dtype, void* stream) {
+    const uint32_t nb = block_groups(hadamard_block);
+    if (nb == 0u || nb > 4u) return QUARTET_EINVAL;
+    int rc = check_gemm_grad_args(first, d_dtype, hadamard_block);
     if (rc) return rc;
-    rc = check_gemm_grad_args(second, d_dtype);
+    rc = check_gemm_grad_args(second, d_dtype, hadamard_block);
     if (rc) return rc;
     const quartet::GemmArgs g0 = {first->a_codes, first->a_scales, first->b_codes, first->b_scales, first->m, first->n, first->k,
                                   first->scale, first->d, first->ldd, first->mask};
     const quartet::GemmArgs g1 = {second->a_codes, second->a_scales, second->b_codes, second->b_scales, second->m, second->n,
                                   second->k, second->scale, second->d, second->ldd, second->mask};
     ProfileScope prof(QUARTET_KIND_GEMM, (hipStream_t)stream);
-    hipError_t e = quartet::launch_gemm_grad_pair(g0, g1, d_dtype == QUARTET_DTYPE_BF16, 1u, (hipStream_t)stream);
+    hipError_t e = quartet::launch_gemm_grad_pair(g0, g1, d_dtype == QUARTET_DTYPE_BF16, nb, (hipStream_t)stream);
     return e == hipSuccess ? QUARTET_OK : hip_fail(e);
+}
+
+int quartet_mxfp4_gemm_grad_pair(const quartet_gemm_grad_args* first, const quartet_gemm_grad_args* second, int d_dtype,
+                                 void* stream) {
+    return gemm_grad_pair_block(first, second, 32, d_dtype, stream);
 }
 
 int quartet_mxfp8_quant(const void* x_bf16, int64_t rows, int64_t k, int64_t ldx,
@@ -646,26 +654,30 @@ int quartet_linear_bwd_block(const void* dy_bf16, int64_t tokens, int64_t in, in
         const quartet_gemm_grad_args dx_args = {g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, x_mask, c169, dx, in};
         return quartet_mxfp4_gemm_grad_pair(&dw_args, &dx_args, grad_dtype, stream);
     }
-    // wider Hadamard blocks: one launch per operand, the products in the same order
+    // wider Hadamard blocks: one launch per operand conversion
     rc = quartet_quant_bwd_sr_block(dy_bf16, out, tokens, out, 1, hb, sw, seed, 2u, rounding, gt_codes, gt_scales, stream);
     if (rc) return rc;
     rc = quartet_requant_transpose_sr_block(xq_codes, xq_scales, in, tokens, hb, sw, seed, 3u, rounding, bx_codes, bx_scales, stream);
     if (rc) return rc;
     if (!big) {
-        rc = quartet_mxfp4_gemm_grad_block(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, hb, w_mask, c169, dw, grad_dtype, in, stream);
-    } else {
-        // a block of 256 columns spans two waves' tiles: fp32 product, then the epilogue kernel
-        rc = quartet_mxfp4_gemm(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+        // blocks of 64 and 128 columns: the other two conversions, then both products (epilogue inside) in one launch
+        rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
         if (rc) return rc;
-        rc = quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);
+        rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, bw_codes, bw_scales, stream);
+        if (rc) return rc;
+        const quartet_gemm_grad_args dw_args = {gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, w_mask, c169, dw, in};
+        const quartet_gemm_grad_args dx_args = {g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, x_mask, c169, dx, in};
+        return gemm_grad_pair_block(&dw_args, &dx_args, hb, grad_dtype, stream);
     }
+    // a block of 256 columns spans two waves' tiles: fp32 product, then the epilogue kernel
+    rc = quartet_mxfp4_gemm(gt_codes, gt_scales, bx_codes, bx_scales, out, in, tokens, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
+    if (rc) return rc;
+    rc = quartet_grad_epilogue_block(acc, w_mask, out, in, hb, c169, dw, grad_dtype, stream);
     if (rc) return rc;
     rc = quartet_quant_bwd_sr_block(dy_bf16, tokens, out, out, 0, hb, sw, seed, 0u, rounding, g_codes, g_scales, stream);
     if (rc) return rc;
     rc = quartet_requant_transpose_sr_block(wq_codes, wq_scales, in, out, hb, sw, seed, 1u, rounding, bw_codes, bw_scales, stream);
     if (rc) return rc;
-    if (!big)
-        return quartet_mxfp4_gemm_grad_block(g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, hb, x_mask, c169, dx, grad_dtype, in, stream);
     rc = quartet_mxfp4_gemm(g_codes, g_scales, bw_codes, bw_scales, tokens, in, out, 1.0f, acc, QUARTET_DTYPE_F32, in, stream);
     if (rc) return rc;
     return quartet_grad_epilogue_block(acc, x_mask, tokens, in, hb, c169, dx, grad_dtype, stream);
