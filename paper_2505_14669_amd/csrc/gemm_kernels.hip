@@ -117,9 +117,16 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
     }
     // issue cursor: the tile and stage the next LDS-direct loads belong to
     // (its product's inner dimension decides the offsets: kb = bytes per code row, kq = K-quads, S2i = stages per tile)
+    // A tile does not start at K = 0: the tiles of XCD class c (tile number mod 8; an XCD's compute units hold tiles of
+    // one class at a time and must stay in step to share panels in their L2) start c/8 of the way along K, in whole K-quads,
+    // and wrap around: ikst is the K-stage the cursor's local stage ist stands for.  Otherwise every compute unit of the
+    // chip asks for the same few hundred bytes of its operand rows at the same time, and with a row pitch of a few KB the
+    // memory channels behind the L2s serve that unevenly (measured: 1-2 % of the K = 4096 products' time).  fp32 sums are
+    // formed in a rotated order then, the same for a tile wherever it runs.  Only for K a multiple of 256: a ragged last
+    // K-quad keeps its place at the end.
     uint32_t iv = blockIdx.x, ist = 0u;
     v4i_t res_a, res_b, res_s;
-    uint32_t kb, istages, S2i, goff, gstep, soff;
+    uint32_t kb, istages, S2i, goff, gstep, soff, ikst;
     const uint32_t drow = wave * 16u + (lane >> 2);
     const uint32_t dcol = (lane & 3u) ^ ((drow >> 2) & 3u);
 #define STREAM_ISSUE_SETUP()                                                                            \
@@ -132,6 +139,7 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
         kb = k_ >> 1;                                                                                   \
         istages = (k_ + 127u) >> 7;                                                                     \
         S2i = istages < 2u ? 2u : ((istages + 1u) & ~1u);                                               \
+        ikst = ((k_ & 255u) == 0u) ? (((lv_ & 7u) * (S2i >> 1)) >> 3) * 2u : 0u;                        \
         goff = drow * kb + dcol * 16u;          /* + j*64*kb, + stage*64 */                             \
         gstep = 64u * kb;                                                                               \
         soff = (((wave & 1u) * 4u + (lane >> 4)) * kq_) * 256u + (lane & 15u) * 16u;   /* + quad*256 */ \
@@ -158,16 +166,18 @@ gemm_mxfp4_stream_kernel(GemmBatch batch, uint32_t total_tiles, uint32_t nb, uin
     {                                                                                                   \
         const uint32_t slot_ = lds0 + ((SLOT) * STAGE + wave * 64u) * 16u;                              \
         if ((J) < 8u) {                                                                                 \
-            const uint32_t base_ = (ist * 64u + dcol * 16u < kb) ? goff + ist * 64u : kOutOfRange;      \
+            const uint32_t base_ = (ikst * 64u + dcol * 16u < kb) ? goff + ikst * 64u : kOutOfRange;      \
             lds_direct_load16((J) < 4u ? res_a : res_b, base_ + ((J) & 3u) * gstep, slot_ + (J) * 4096u); \
         } else {                                                                                        \
-            lds_direct_load16(res_s, (ist < istages) ? soff + (ist >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
+            lds_direct_load16(res_s, (ikst < istages) ? soff + (ikst >> 1) * 256u : kOutOfRange, slot_ + CODES * 16u); \
         }                                                                                               \
     }
 // the stage is issued: move the cursor on (to the next tile of this block after the tile's last stage)
 #define STREAM_ISSUE_ADVANCE()                                                                          \
     {                                                                                                   \
         ++ist;                                                                                          \
+        ++ikst;                                                                                         \
+        if (ikst == S2i) ikst = 0u;                                                                     \
         if (ist == S2i) {                                                                               \
             ist = 0u;                                                                                   \
             iv += G;                                                                                    \

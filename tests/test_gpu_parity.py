@@ -231,7 +231,7 @@ def test_gemm_grad_fused(G, mnk, gemm_variant):
     assert within_elem_bound(got_nomask, oracle.grad_epilogue(acc, None, 1.0), absp, k, grad_scale=1.0)
 
 
-@pytest.mark.parametrize("shapes", [((40, 96, 64), (7, 32, 160)), ((300, 544, 192), (513, 288, 416)),
+@pytest.mark.parametrize("shapes", [((40, 96, 64), (7, 32, 160)), ((300, 544, 192), (513, 288, 416)), ((300, 544, 512), (513, 288, 1280)),
                                     ((1, 32, 32), (260, 1056, 32)), ((4352, 4352, 64), (1100, 2080, 96))])
 def test_gemm_grad_pair_matches_two_calls(G, shapes, gemm_variant):
     # Algorithm 1 Backward: the dW and the dx product in one launch -- the same bits as one launch each, for products
