@@ -233,8 +233,10 @@ int quartet_mxfp4_gemm_grad(const uint8_t *a_codes, const uint8_t *a_scales,
  * Two products with the gradient epilogue in one launch (Algorithm 1 Backward computes dW and dx from four operands
  * that are all known before either product starts, so neither waits for the other).  Each argument block describes one
  * product exactly as the arguments of quartet_mxfp4_gemm_grad do; both results have the type d_dtype.  The structures
- * are read on the host during the call; every pointer inside them is a device pointer.  The results are bit-identical
- * to two calls of quartet_mxfp4_gemm_grad (first, then second).  The compute units go through the first product's tiles,
+ * are read on the host during the call; every pointer inside them is a device pointer.  The results are those of two
+ * calls of quartet_mxfp4_gemm_grad (first, then second): bit for bit when the pair runs on the tile shape each product
+ * would get alone (always, under quartet_debug_set_gemm_plan with a forced shape), else up to the order of the fp32 sums
+ * along k.  The compute units go through the first product's tiles,
  * then the second's, without draining in between: one ramp-up and one drain, and the second product fills the compute
  * units the first leaves idle in its last round.  One tile shape serves both products (chosen for the pair, or the one
  * quartet_debug_set_gemm_plan forces).  The two results must not overlap.  Errors as

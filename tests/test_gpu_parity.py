@@ -250,9 +250,14 @@ def test_gemm_grad_pair_matches_two_calls(G, shapes, gemm_variant):
     got = G.gemm_grad_pair(prods[0], prods[1])
     for g, pr in zip(got, prods):
         alone = G.gemm_grad(*pr)
-        assert np.array_equal(g.view(np.uint32), alone.view(np.uint32))
+        if gemm_variant != "auto":      # one tile shape for the pair and for each product alone: the same bits
+            assert np.array_equal(g.view(np.uint32), alone.view(np.uint32))
+        else:                           # the pair's shape may differ from a product's own: the same sums in another order
+            assert rel_fro(g, alone) < FRO_TOL
         want = oracle.grad_epilogue(oracle.mxfp4_gemm(pr[0], pr[1], pr[2], pr[3]).astype(np.float32), pr[4], pr[5])
         assert rel_fro(g, want) < FRO_TOL
+        absp = indep.gemm_abs_products(pr[0], pr[1], pr[2], pr[3])
+        assert within_elem_bound(g, want, absp, pr[0].shape[1] * 2, grad_scale=pr[5])
     got_bf = G.gemm_grad_pair(prods[1], prods[0], bf16=True)     # the other order, bf16 results
     assert np.array_equal(got_bf[0], synth.f32_to_bf16(got[1])) and np.array_equal(got_bf[1], synth.f32_to_bf16(got[0]))
 
