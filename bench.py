@@ -443,7 +443,7 @@ def main():
                                + ("" if args.hadamard_block == 32 else f", Hadamard block {args.hadamard_block}"),
                    "layers": [[l.name, l.t, l.i, l.o] for l in layers]},
         "roofline": {"bound": "mfma",
-                     "kernel": ("gemm_mxfp4_stream_kernel" if big_gemm else "gemm_mxfp4_kernel") + " (all three GEMMs of every layer: the forward product, and dW with dX in one launch)",
+                     "kernel": ("gemm_mxfp4_stream_kernel" if big_gemm else "gemm_mxfp4_stream_tile_kernel") + " (all three GEMMs of every layer: the forward product, and dW with dX in one launch)",
                      "achieved": round(achieved, 2), "peak": PEAK_FP4_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_FP4_TFLOPS, 4),
                      "traffic": recorded(args.config, "gemm_config{config}_hbm_traffic.txt", "traffic_bytes_per_launch"),
